@@ -1,0 +1,143 @@
+/*
+ * power_smc.h -- C ABI of the MI355X (gfx950) Power-SMC per-token step.
+ *
+ * The library implements what Algorithm 1 of the Power-SMC paper adds on top of one batched decode
+ * step, for B independent prompts with N particles each (R = B*N rows, row r = b*N + i):
+ *
+ *   a0  stage-boundary reweight of exponent bridging (Sec. 5.3, App. B)
+ *   a1  draw y ~ q_t = softmax(l / tau_t)                     (Alg. 1 "sample"; Cor. 1)
+ *   a2  log W~ += alpha_t log p(y) - log q_t(y)               (Eq. "inc"; Alg. 1 "update")
+ *   a3  W = W~ / sum W~ ,  ESS = 1 / sum W^2   per prompt      (Eq. "ess")
+ *   a4  if ESS < kappa N: systematic resampling -> ancestors  (Alg. 1; Sec. 7 implementation details)
+ *   a5  prefixes, cumulative log p and KV cache gathered by ancestor (Alg. 1 "reorder"; App. C)
+ *
+ * Conventions shared by every call
+ *   - "d_" arguments are DEVICE pointers, "h_" arguments are HOST pointers.  All are caller-owned; the
+ *     library allocates no device memory (the caller passes a workspace of smc_workspace_bytes()).
+ *   - Calls enqueue kernels on the HIP stream given to smc_init and return without synchronising,
+ *     except smc_get_state / smc_set_state / smc_get_diag / smc_kv_bind, which are synchronous.
+ *   - Every call returns an smc_status.  Argument errors are detected on the host before anything is
+ *     enqueued and leave all state untouched.  Nothing throws or aborts.
+ *   - One context per stream; a context is not thread-safe.
+ *
+ * Random numbers: Philox4x32-10 (Salmon et al., SC'11), key = (seed low word, seed high word), counter =
+ * (v div 4, row, step t, domain); the word for vocabulary entry v is word (v mod 4) of that block.
+ * domain 0 = token draw, domain 1 = resampling offset (row := prompt index, v := 0).
+ * A word x maps to u = (x + 1/2) / 2^32 in (0,1).  (The paper does not fix the sampler; this is the
+ * library's definition.)
+ */
+#ifndef POWER_SMC_H
+#define POWER_SMC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct smc_ctx smc_ctx; /* opaque, lives in host memory */
+
+typedef enum {
+    SMC_OK = 0,
+    SMC_E_NULL = 1,   /* a required pointer is null */
+    SMC_E_SHAPE = 2,  /* a size is non-positive or exceeds a documented limit */
+    SMC_E_DTYPE = 3,  /* unknown logits dtype / unsupported element size */
+    SMC_E_ALIGN = 4,  /* a pointer or stride is not 16-byte aligned */
+    SMC_E_RANGE = 5,  /* a scalar is outside its domain (t, valid_len, alpha, kappa) */
+    SMC_E_STATE = 6,  /* call not valid in the context's state (e.g. KV not bound) */
+    SMC_E_HIP = 7     /* the HIP runtime reported an error */
+} smc_status;
+
+typedef enum { SMC_BF16 = 0, SMC_F32 = 1 } smc_dtype;
+
+enum { SMC_MAX_PARTICLES = 1024, SMC_MAX_KV_TENSORS = 512 };
+
+typedef struct {
+    int32_t B;             /* prompts                                  >= 1 */
+    int32_t N;             /* particles per prompt (Alg. 1 input N)    1..SMC_MAX_PARTICLES */
+    int32_t V;             /* vocabulary size                          >= 1 */
+    int32_t T_max;         /* capacity of the token history (Alg. 1 input T_max); multiple of 4 */
+    int32_t logits_dtype;  /* smc_dtype */
+    int32_t reserved0;
+    double  kappa;         /* resample iff ESS < kappa*N (strict), 0 <= kappa <= 1 (kappa = 0: never) */
+    uint64_t seed;         /* Philox key */
+    /* KV cache geometry: kv_tensors tensors (2 per layer), each [R, kv_H, kv_S, kv_D] of kv_elem_bytes;
+     * kv_D*kv_elem_bytes must be a multiple of 16.  kv_tensors = 0: no cache is managed. */
+    int32_t kv_tensors, kv_H, kv_S, kv_D, kv_elem_bytes;
+    int32_t reserved1;
+} smc_config;
+
+/* Bytes of device scratch + state the caller must provide to smc_init (0 on an invalid config). */
+size_t smc_workspace_bytes(const smc_config* cfg);
+
+/* Creates a context.  d_workspace: device memory, 256-byte aligned, >= smc_workspace_bytes(cfg), owned
+ * by the caller and left alone by it until smc_destroy.  hip_stream: a hipStream_t (NULL = default stream).
+ * Enqueues the initialisation of Alg. 1: log W~ = 0, cumulative log p = 0, all prompts on buffer A. */
+smc_status smc_init(const smc_config* cfg, void* d_workspace, size_t workspace_bytes, void* hip_stream,
+                    smc_ctx** out_ctx);
+
+/* Frees the host-side context (device memory stays with the caller).  Synchronises the stream. */
+smc_status smc_destroy(smc_ctx* ctx);
+
+/* Registers the double-buffered caches (App. C).  h_bufA / h_bufB: host arrays of kv_tensors device pointers
+ * (16-byte aligned, each tensor [R, kv_H, kv_S, kv_D]); d_histA / d_histB: device int32 [R, T_max] token
+ * histories (may both be NULL: no history is kept).  Prompt b's live data is in buffer A while parity[b] = 0
+ * and in buffer B while parity[b] = 1; smc_kv_reindex reads the live buffer, writes the other and flips parity[b].
+ * Synchronous (copies the pointer tables into the workspace). */
+smc_status smc_kv_bind(smc_ctx* ctx, void* const* h_bufA, void* const* h_bufB, int32_t* d_histA, int32_t* d_histB);
+
+/* a0 + a1 + a2 for step t (1-based, <= T_max).
+ *   d_logits: [R, row_stride_elems] of cfg.logits_dtype, first V entries of each row used; base address and
+ *             row stride in bytes must be multiples of 16.
+ *   alpha_t, alpha_prev: exponents of this and the previous token (equal when not bridging; >= 0).
+ *   tau_t: proposal temperature; tau_t <= 0 selects the locally optimal tau = 1/alpha_t of Thm 1 exactly.
+ *   d_tokens_out: int32 [R], the sampled tokens y_t.
+ * Updates log W~, cumulative log p and column t-1 of the live history in the workspace. */
+smc_status smc_step(smc_ctx* ctx, const void* d_logits, int64_t row_stride_elems, int32_t t, double alpha_t,
+                    double alpha_prev, double tau_t, int32_t* d_tokens_out);
+
+/* a3 on the context's weights: d_ess_out double [B]; d_lognormw_out double [R] = log W (nullable). */
+smc_status smc_ess(smc_ctx* ctx, double* d_ess_out, double* d_lognormw_out);
+
+/* a3 + a4 on the context's weights at step t: d_anc_out int32 [R], ancestor of each row as a global row index
+ * (identity for prompts that do not resample); d_resampled_out int32 [B], 1 where ESS < kappa*N;
+ * d_ess_out double [B] nullable.  Resets log W~ to 0 for resampled prompts (Alg. 1 "reset"). */
+smc_status smc_resample(smc_ctx* ctx, int32_t t, int32_t* d_anc_out, int32_t* d_resampled_out, double* d_ess_out);
+
+/* a5: for every prompt b with d_resampled[b] != 0 and every row k of it, copies row d_anc[k] of the live
+ * buffer into row k of the other buffer -- the first valid_len (0..kv_S) positions of every head of every KV
+ * tensor, the first t columns of the history -- gathers cumulative log p the same way, then flips parity[b].
+ * d_anc entries of a resampled prompt must lie inside that prompt's row range.  Each distinct ancestor row is
+ * read once and written to all of its descendants. */
+smc_status smc_kv_reindex(smc_ctx* ctx, const int32_t* d_anc, const int32_t* d_resampled, int32_t valid_len,
+                          int32_t t);
+
+/* Explicit-input forms of a3 / a4 for component checks: same arithmetic on caller-provided weights.
+ * smc_resample_from writes the reset weights to d_logW_inout. */
+smc_status smc_ess_from(smc_ctx* ctx, const double* d_logW, double* d_ess_out, double* d_lognormw_out);
+smc_status smc_resample_from(smc_ctx* ctx, double* d_logW_inout, int32_t t, int32_t* d_anc_out,
+                             int32_t* d_resampled_out, double* d_ess_out);
+
+/* Synchronous inspection / teacher forcing (host arrays; any may be NULL to skip):
+ * h_logW, h_cumlogp double [R]; h_parity int32 [B]. */
+smc_status smc_get_state(smc_ctx* ctx, double* h_logW, double* h_cumlogp, int32_t* h_parity);
+smc_status smc_set_state(smc_ctx* ctx, const double* h_logW, const double* h_cumlogp);
+
+/* Synchronous per-row diagnostics of the last smc_step (host arrays of R entries, any may be NULL):
+ * increment a2, log Z_1 = LSE(l), log Z_beta = LSE(l/tau), runner-up token, key gap between winner and
+ * runner-up (in fp64), and h_counters[4] = {rows with non-finite sums, candidates scored, candidate-queue
+ * drains, vocabulary entries seen}. */
+smc_status smc_get_diag(smc_ctx* ctx, double* h_delta, double* h_logZ1, double* h_logZb, int32_t* h_second,
+                        double* h_gap, uint64_t* h_counters);
+
+/* Tuning knobs (defaults chosen at smc_init): number of workgroups a row is split over in the vocabulary pass
+ * (1..32; 0 = automatic) and whether every entry is scored (dense = 1) instead of only those that can win. */
+smc_status smc_set_tuning(smc_ctx* ctx, int32_t n_split, int32_t dense);
+
+const char* smc_status_str(smc_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* POWER_SMC_H */

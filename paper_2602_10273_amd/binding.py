@@ -1,0 +1,158 @@
+"""ctypes binding of libpower_smc.so: the same names as the C ABI, argument marshalling only.
+
+PyTorch is used by callers for device memory and streams; this module only turns tensors into pointers.
+If the HIP library has not been built the import of the library fails loudly -- there is no fallback path.
+"""
+import ctypes as C
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpower_smc.so")
+
+SMC_OK = 0
+SMC_BF16, SMC_F32 = 0, 1
+STATUS = {0: "SMC_OK", 1: "SMC_E_NULL", 2: "SMC_E_SHAPE", 3: "SMC_E_DTYPE", 4: "SMC_E_ALIGN", 5: "SMC_E_RANGE",
+          6: "SMC_E_STATE", 7: "SMC_E_HIP"}
+
+EXPORTS = ["smc_workspace_bytes", "smc_init", "smc_destroy", "smc_kv_bind", "smc_step", "smc_ess", "smc_resample",
+           "smc_kv_reindex", "smc_ess_from", "smc_resample_from", "smc_get_state", "smc_set_state", "smc_get_diag",
+           "smc_set_tuning", "smc_status_str"]
+
+
+class smc_config(C.Structure):
+    _fields_ = [("B", C.c_int32), ("N", C.c_int32), ("V", C.c_int32), ("T_max", C.c_int32),
+                ("logits_dtype", C.c_int32), ("reserved0", C.c_int32), ("kappa", C.c_double), ("seed", C.c_uint64),
+                ("kv_tensors", C.c_int32), ("kv_H", C.c_int32), ("kv_S", C.c_int32), ("kv_D", C.c_int32),
+                ("kv_elem_bytes", C.c_int32), ("reserved1", C.c_int32)]
+
+
+class SMCError(RuntimeError):
+    def __init__(self, fn, status):
+        self.status = status
+        super().__init__(f"{fn} -> {STATUS.get(status, status)}")
+
+
+_lib = None
+
+
+def lib():
+    """The loaded library; raises if it was not built (python -c 'import __graft_entry__ as g; g.build()')."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build the HIP library first (no CPU fallback exists)")
+        L = C.CDLL(LIB_PATH)
+        vp, i32, i64, f64, u64 = C.c_void_p, C.c_int32, C.c_int64, C.c_double, C.c_uint64
+        L.smc_workspace_bytes.restype = C.c_size_t
+        L.smc_workspace_bytes.argtypes = [C.POINTER(smc_config)]
+        L.smc_init.argtypes = [C.POINTER(smc_config), vp, C.c_size_t, vp, C.POINTER(vp)]
+        L.smc_destroy.argtypes = [vp]
+        L.smc_kv_bind.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), vp, vp]
+        L.smc_step.argtypes = [vp, vp, i64, i32, f64, f64, f64, vp]
+        L.smc_ess.argtypes = [vp, vp, vp]
+        L.smc_resample.argtypes = [vp, i32, vp, vp, vp]
+        L.smc_kv_reindex.argtypes = [vp, vp, vp, i32, i32]
+        L.smc_ess_from.argtypes = [vp, vp, vp, vp]
+        L.smc_resample_from.argtypes = [vp, vp, i32, vp, vp, vp]
+        L.smc_get_state.argtypes = [vp, vp, vp, vp]
+        L.smc_set_state.argtypes = [vp, vp, vp]
+        L.smc_get_diag.argtypes = [vp, vp, vp, vp, vp, vp, vp]
+        L.smc_set_tuning.argtypes = [vp, i32, i32]
+        L.smc_status_str.restype = C.c_char_p
+        L.smc_status_str.argtypes = [C.c_int]
+        for name in EXPORTS:
+            if name not in ("smc_workspace_bytes", "smc_status_str"):
+                getattr(L, name).restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def _ptr(x):
+    """torch tensor / numpy array / int / None -> address."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    if hasattr(x, "data_ptr"):
+        return x.data_ptr()
+    return x.ctypes.data
+
+
+def _check(fn, st):
+    if st != SMC_OK:
+        raise SMCError(fn, st)
+
+
+def make_config(B, N, V, T_max, logits_dtype, kappa, seed, kv_tensors=0, kv_H=0, kv_S=0, kv_D=0, kv_elem_bytes=2):
+    dt = {"bf16": SMC_BF16, "f32": SMC_F32}.get(logits_dtype, logits_dtype)
+    return smc_config(B, N, V, T_max, dt, 0, float(kappa), int(seed) & 0xFFFFFFFFFFFFFFFF, kv_tensors, kv_H, kv_S,
+                      kv_D, kv_elem_bytes, 0)
+
+
+# ---- one function per C entry point, same names --------------------------------------------------------------
+def smc_workspace_bytes(cfg):
+    return int(lib().smc_workspace_bytes(C.byref(cfg)))
+
+
+def smc_init(cfg, d_workspace, workspace_bytes, hip_stream=None):
+    ctx = C.c_void_p()
+    _check("smc_init", lib().smc_init(C.byref(cfg), _ptr(d_workspace), workspace_bytes, hip_stream, C.byref(ctx)))
+    return ctx
+
+
+def smc_destroy(ctx):
+    _check("smc_destroy", lib().smc_destroy(ctx))
+
+
+def smc_kv_bind(ctx, bufA, bufB, d_histA=None, d_histB=None):
+    n = len(bufA)
+    A = (C.c_void_p * max(n, 1))(*[_ptr(t) for t in bufA])
+    Bp = (C.c_void_p * max(n, 1))(*[_ptr(t) for t in bufB])
+    _check("smc_kv_bind", lib().smc_kv_bind(ctx, A if n else None, Bp if n else None, _ptr(d_histA), _ptr(d_histB)))
+
+
+def smc_step(ctx, d_logits, row_stride_elems, t, alpha_t, alpha_prev, tau_t, d_tokens_out):
+    _check("smc_step", lib().smc_step(ctx, _ptr(d_logits), row_stride_elems, t, alpha_t, alpha_prev, tau_t,
+                                      _ptr(d_tokens_out)))
+
+
+def smc_ess(ctx, d_ess_out, d_lognormw_out=None):
+    _check("smc_ess", lib().smc_ess(ctx, _ptr(d_ess_out), _ptr(d_lognormw_out)))
+
+
+def smc_resample(ctx, t, d_anc_out, d_resampled_out, d_ess_out=None):
+    _check("smc_resample", lib().smc_resample(ctx, t, _ptr(d_anc_out), _ptr(d_resampled_out), _ptr(d_ess_out)))
+
+
+def smc_kv_reindex(ctx, d_anc, d_resampled, valid_len, t):
+    _check("smc_kv_reindex", lib().smc_kv_reindex(ctx, _ptr(d_anc), _ptr(d_resampled), valid_len, t))
+
+
+def smc_ess_from(ctx, d_logW, d_ess_out, d_lognormw_out=None):
+    _check("smc_ess_from", lib().smc_ess_from(ctx, _ptr(d_logW), _ptr(d_ess_out), _ptr(d_lognormw_out)))
+
+
+def smc_resample_from(ctx, d_logW_inout, t, d_anc_out, d_resampled_out, d_ess_out=None):
+    _check("smc_resample_from", lib().smc_resample_from(ctx, _ptr(d_logW_inout), t, _ptr(d_anc_out),
+                                                        _ptr(d_resampled_out), _ptr(d_ess_out)))
+
+
+def smc_get_state(ctx, h_logW=None, h_cumlogp=None, h_parity=None):
+    _check("smc_get_state", lib().smc_get_state(ctx, _ptr(h_logW), _ptr(h_cumlogp), _ptr(h_parity)))
+
+
+def smc_set_state(ctx, h_logW=None, h_cumlogp=None):
+    _check("smc_set_state", lib().smc_set_state(ctx, _ptr(h_logW), _ptr(h_cumlogp)))
+
+
+def smc_get_diag(ctx, h_delta=None, h_logZ1=None, h_logZb=None, h_second=None, h_gap=None, h_counters=None):
+    _check("smc_get_diag", lib().smc_get_diag(ctx, _ptr(h_delta), _ptr(h_logZ1), _ptr(h_logZb), _ptr(h_second),
+                                              _ptr(h_gap), _ptr(h_counters)))
+
+
+def smc_set_tuning(ctx, n_split=0, dense=0):
+    _check("smc_set_tuning", lib().smc_set_tuning(ctx, n_split, dense))
+
+
+def smc_status_str(status):
+    return lib().smc_status_str(status).decode()

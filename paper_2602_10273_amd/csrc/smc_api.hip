@@ -1,0 +1,264 @@
+// Host side of libpower_smc: argument validation, workspace layout, kernel launches.  No device allocation.
+#include <math.h>
+#include <new>
+#include <string.h>
+
+#include "smc_internal.hpp"
+
+using namespace psmc;
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t up(size_t x) { return (x + kAlign - 1) & ~(kAlign - 1); }
+inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+
+smc_status check_config(const smc_config* c)
+{
+    if (!c) return SMC_E_NULL;
+    if (c->B < 1 || c->N < 1 || c->V < 1 || c->T_max < 1) return SMC_E_SHAPE;
+    if (c->N > SMC_MAX_PARTICLES) return SMC_E_SHAPE;
+    if ((int64_t)c->B * c->N > (int64_t)1 << 24) return SMC_E_SHAPE;
+    if (c->T_max % 4 != 0) return SMC_E_ALIGN;
+    if (c->logits_dtype != SMC_BF16 && c->logits_dtype != SMC_F32) return SMC_E_DTYPE;
+    if (!(c->kappa >= 0.0 && c->kappa <= 1.0)) return SMC_E_RANGE;
+    if (c->kv_tensors < 0 || c->kv_tensors > SMC_MAX_KV_TENSORS) return SMC_E_SHAPE;
+    if (c->kv_tensors > 0) {
+        if (c->kv_H < 1 || c->kv_S < 1 || c->kv_D < 1) return SMC_E_SHAPE;
+        if (c->kv_elem_bytes != 1 && c->kv_elem_bytes != 2 && c->kv_elem_bytes != 4) return SMC_E_DTYPE;
+        if (((int64_t)c->kv_D * c->kv_elem_bytes) % 16 != 0) return SMC_E_ALIGN;
+    }
+    return SMC_OK;
+}
+
+// Walks the workspace layout; with base == nullptr only the size is computed.
+size_t layout(const smc_config* c, char* base, Workspace* w)
+{
+    const size_t R = (size_t)c->B * c->N;
+    const size_t mask_words = ((size_t)c->N + 63) / 64;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { char* p = base ? base + off : nullptr; off += up(bytes); return p; };
+    char* p;
+    p = take(R * 8); if (w) w->logW = (double*)p;
+    p = take(R * 8); if (w) w->cumlogp = (double*)p;
+    p = take((size_t)c->B * 4); if (w) w->parity = (int32_t*)p;
+    p = take(R * kMaxSplit * sizeof(Partial)); if (w) w->partials = (Partial*)p;
+    p = take(R * 8); if (w) w->d_delta = (double*)p;
+    p = take(R * 8); if (w) w->d_logZ1 = (double*)p;
+    p = take(R * 8); if (w) w->d_logZb = (double*)p;
+    p = take(R * 8); if (w) w->d_gap = (double*)p;
+    p = take(R * 4); if (w) w->d_second = (int32_t*)p;
+    p = take(sizeof(Counters)); if (w) w->counters = (Counters*)p;
+    p = take(sizeof(GatherPlan)); if (w) w->plan = (GatherPlan*)p;
+    p = take(R * 4); if (w) w->grp_src = (int32_t*)p;
+    p = take(R * 4); if (w) w->grp_base = (int32_t*)p;
+    p = take(R * mask_words * 8); if (w) w->grp_mask = (unsigned long long*)p;
+    p = take((size_t)(c->kv_tensors > 0 ? c->kv_tensors : 1) * sizeof(void*)); if (w) w->kvA = (void**)p;
+    p = take((size_t)(c->kv_tensors > 0 ? c->kv_tensors : 1) * sizeof(void*)); if (w) w->kvB = (void**)p;
+    p = take(2 * sizeof(void*)); if (w) w->histAB = (void**)p;
+    return off;
+}
+
+int auto_split(int R, int V, int dtype)
+{
+    // enough workgroups to fill 256 CUs several times over, but no slice shorter than 4 tiles
+    const int epv = dtype == SMC_BF16 ? 8 : 4;
+    const int tiles = ((V + epv - 1) / epv + kVocabThreads - 1) / kVocabThreads;
+    int s = (2048 + R - 1) / R;
+    if (s > tiles / 4) s = tiles / 4;
+    if (s > kMaxSplit) s = kMaxSplit;
+    if (s < 1) s = 1;
+    return s;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* smc_status_str(smc_status s)
+{
+    switch (s) {
+        case SMC_OK: return "ok";
+        case SMC_E_NULL: return "null pointer";
+        case SMC_E_SHAPE: return "bad shape";
+        case SMC_E_DTYPE: return "bad dtype";
+        case SMC_E_ALIGN: return "bad alignment";
+        case SMC_E_RANGE: return "value out of range";
+        case SMC_E_STATE: return "bad state";
+        case SMC_E_HIP: return "HIP error";
+    }
+    return "unknown";
+}
+
+size_t smc_workspace_bytes(const smc_config* cfg)
+{
+    if (check_config(cfg) != SMC_OK) return 0;
+    return layout(cfg, nullptr, nullptr);
+}
+
+smc_status smc_init(const smc_config* cfg, void* d_workspace, size_t workspace_bytes, void* hip_stream, smc_ctx** out_ctx)
+{
+    if (!out_ctx) return SMC_E_NULL;
+    *out_ctx = nullptr;
+    smc_status st = check_config(cfg);
+    if (st != SMC_OK) return st;
+    if (!d_workspace) return SMC_E_NULL;
+    if (((uintptr_t)d_workspace & (kAlign - 1)) != 0) return SMC_E_ALIGN;
+    if (workspace_bytes < layout(cfg, nullptr, nullptr)) return SMC_E_SHAPE;
+
+    smc_ctx* c = new (std::nothrow) smc_ctx();
+    if (!c) return SMC_E_STATE;
+    c->cfg = *cfg;
+    c->stream = (hipStream_t)hip_stream;
+    c->R = cfg->B * cfg->N;
+    layout(cfg, (char*)d_workspace, &c->ws);
+    c->n_split = auto_split(c->R, cfg->V, cfg->logits_dtype);
+    c->dense = 0;
+    c->mask_words = (cfg->N + 63) / 64;
+    c->kv_bound = 0;
+    c->hist_bound = 0;
+    int dev = 0, cus = 256;
+    if (hipGetDevice(&dev) == hipSuccess) {
+        int v = 0;
+        if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) cus = v;
+    } else {
+        (void)hipGetLastError();
+        delete c;
+        return SMC_E_HIP;
+    }
+    c->gather_grid = cus * 8;
+    if (launch_init_state(c) != hipSuccess) { delete c; return SMC_E_HIP; }
+    *out_ctx = c;
+    return SMC_OK;
+}
+
+smc_status smc_destroy(smc_ctx* ctx)
+{
+    if (!ctx) return SMC_E_NULL;
+    const hipError_t e = hipStreamSynchronize(ctx->stream);
+    delete ctx;
+    return e == hipSuccess ? SMC_OK : SMC_E_HIP;
+}
+
+smc_status smc_kv_bind(smc_ctx* ctx, void* const* h_bufA, void* const* h_bufB, int32_t* d_histA, int32_t* d_histB)
+{
+    if (!ctx) return SMC_E_NULL;
+    const int n = ctx->cfg.kv_tensors;
+    if (n > 0) {
+        if (!h_bufA || !h_bufB) return SMC_E_NULL;
+        for (int i = 0; i < n; ++i) {
+            if (!h_bufA[i] || !h_bufB[i]) return SMC_E_NULL;
+            if (!aligned16(h_bufA[i]) || !aligned16(h_bufB[i])) return SMC_E_ALIGN;
+        }
+    }
+    if ((d_histA == nullptr) != (d_histB == nullptr)) return SMC_E_NULL;
+    if (d_histA && (!aligned16(d_histA) || !aligned16(d_histB))) return SMC_E_ALIGN;
+    if (hipStreamSynchronize(ctx->stream) != hipSuccess) return SMC_E_HIP;
+    if (n > 0) {
+        if (hipMemcpy(ctx->ws.kvA, h_bufA, (size_t)n * sizeof(void*), hipMemcpyHostToDevice) != hipSuccess) return SMC_E_HIP;
+        if (hipMemcpy(ctx->ws.kvB, h_bufB, (size_t)n * sizeof(void*), hipMemcpyHostToDevice) != hipSuccess) return SMC_E_HIP;
+    }
+    void* hh[2] = {d_histA, d_histB};
+    if (hipMemcpy(ctx->ws.histAB, hh, sizeof(hh), hipMemcpyHostToDevice) != hipSuccess) return SMC_E_HIP;
+    ctx->kv_bound = n > 0;
+    ctx->hist_bound = d_histA != nullptr;
+    return SMC_OK;
+}
+
+smc_status smc_step(smc_ctx* ctx, const void* d_logits, int64_t row_stride_elems, int32_t t, double alpha_t,
+                    double alpha_prev, double tau_t, int32_t* d_tokens_out)
+{
+    if (!ctx || !d_logits || !d_tokens_out) return SMC_E_NULL;
+    const int esz = ctx->cfg.logits_dtype == SMC_BF16 ? 2 : 4;
+    if (row_stride_elems < ctx->cfg.V) return SMC_E_SHAPE;
+    if (!aligned16(d_logits) || (row_stride_elems * esz) % 16 != 0) return SMC_E_ALIGN;
+    if (t < 1 || t > ctx->cfg.T_max) return SMC_E_RANGE;
+    if (!(alpha_t > 0.0) || !(alpha_prev >= 0.0) || !isfinite(alpha_t) || !isfinite(alpha_prev)) return SMC_E_RANGE;
+    if (!isfinite(tau_t)) return SMC_E_RANGE;
+    const double beta = tau_t <= 0.0 ? alpha_t : 1.0 / tau_t;
+    if (!(beta > 0.0) || !isfinite(beta) || beta > 1.0e4) return SMC_E_RANGE;
+    return launch_vocab_pass(ctx, d_logits, row_stride_elems, t, alpha_t, alpha_prev, beta, d_tokens_out) == hipSuccess
+               ? SMC_OK : SMC_E_HIP;
+}
+
+smc_status smc_ess_from(smc_ctx* ctx, const double* d_logW, double* d_ess_out, double* d_lognormw_out)
+{
+    if (!ctx || !d_logW || !d_ess_out) return SMC_E_NULL;
+    return launch_ess(ctx, d_logW, d_ess_out, d_lognormw_out) == hipSuccess ? SMC_OK : SMC_E_HIP;
+}
+
+smc_status smc_ess(smc_ctx* ctx, double* d_ess_out, double* d_lognormw_out)
+{
+    if (!ctx) return SMC_E_NULL;
+    return smc_ess_from(ctx, ctx->ws.logW, d_ess_out, d_lognormw_out);
+}
+
+smc_status smc_resample_from(smc_ctx* ctx, double* d_logW_inout, int32_t t, int32_t* d_anc_out, int32_t* d_resampled_out,
+                             double* d_ess_out)
+{
+    if (!ctx || !d_logW_inout || !d_anc_out || !d_resampled_out) return SMC_E_NULL;
+    if (t < 1) return SMC_E_RANGE;
+    return launch_resample(ctx, d_logW_inout, t, d_anc_out, d_resampled_out, d_ess_out) == hipSuccess ? SMC_OK : SMC_E_HIP;
+}
+
+smc_status smc_resample(smc_ctx* ctx, int32_t t, int32_t* d_anc_out, int32_t* d_resampled_out, double* d_ess_out)
+{
+    if (!ctx) return SMC_E_NULL;
+    return smc_resample_from(ctx, ctx->ws.logW, t, d_anc_out, d_resampled_out, d_ess_out);
+}
+
+smc_status smc_kv_reindex(smc_ctx* ctx, const int32_t* d_anc, const int32_t* d_resampled, int32_t valid_len, int32_t t)
+{
+    if (!ctx || !d_anc || !d_resampled) return SMC_E_NULL;
+    if (t < 0 || t > ctx->cfg.T_max) return SMC_E_RANGE;
+    if (valid_len < 0 || (ctx->cfg.kv_tensors > 0 && valid_len > ctx->cfg.kv_S)) return SMC_E_RANGE;
+    if (ctx->cfg.kv_tensors > 0 && valid_len > 0 && !ctx->kv_bound) return SMC_E_STATE;
+    return launch_reindex(ctx, d_anc, d_resampled, valid_len, t) == hipSuccess ? SMC_OK : SMC_E_HIP;
+}
+
+smc_status smc_get_state(smc_ctx* ctx, double* h_logW, double* h_cumlogp, int32_t* h_parity)
+{
+    if (!ctx) return SMC_E_NULL;
+    if (hipStreamSynchronize(ctx->stream) != hipSuccess) return SMC_E_HIP;
+    const size_t R = ctx->R;
+    if (h_logW && hipMemcpy(h_logW, ctx->ws.logW, R * 8, hipMemcpyDeviceToHost) != hipSuccess) return SMC_E_HIP;
+    if (h_cumlogp && hipMemcpy(h_cumlogp, ctx->ws.cumlogp, R * 8, hipMemcpyDeviceToHost) != hipSuccess) return SMC_E_HIP;
+    if (h_parity && hipMemcpy(h_parity, ctx->ws.parity, (size_t)ctx->cfg.B * 4, hipMemcpyDeviceToHost) != hipSuccess)
+        return SMC_E_HIP;
+    return SMC_OK;
+}
+
+smc_status smc_set_state(smc_ctx* ctx, const double* h_logW, const double* h_cumlogp)
+{
+    if (!ctx) return SMC_E_NULL;
+    if (hipStreamSynchronize(ctx->stream) != hipSuccess) return SMC_E_HIP;
+    const size_t R = ctx->R;
+    if (h_logW && hipMemcpy(ctx->ws.logW, h_logW, R * 8, hipMemcpyHostToDevice) != hipSuccess) return SMC_E_HIP;
+    if (h_cumlogp && hipMemcpy(ctx->ws.cumlogp, h_cumlogp, R * 8, hipMemcpyHostToDevice) != hipSuccess) return SMC_E_HIP;
+    return SMC_OK;
+}
+
+smc_status smc_get_diag(smc_ctx* ctx, double* h_delta, double* h_logZ1, double* h_logZb, int32_t* h_second, double* h_gap,
+                        uint64_t* h_counters)
+{
+    if (!ctx) return SMC_E_NULL;
+    if (hipStreamSynchronize(ctx->stream) != hipSuccess) return SMC_E_HIP;
+    const size_t R = ctx->R;
+    auto get = [&](void* h, const void* d, size_t n) { return !h || hipMemcpy(h, d, n, hipMemcpyDeviceToHost) == hipSuccess; };
+    if (!get(h_delta, ctx->ws.d_delta, R * 8) || !get(h_logZ1, ctx->ws.d_logZ1, R * 8) ||
+        !get(h_logZb, ctx->ws.d_logZb, R * 8) || !get(h_second, ctx->ws.d_second, R * 4) ||
+        !get(h_gap, ctx->ws.d_gap, R * 8) || !get(h_counters, ctx->ws.counters, sizeof(Counters)))
+        return SMC_E_HIP;
+    return SMC_OK;
+}
+
+smc_status smc_set_tuning(smc_ctx* ctx, int32_t n_split, int32_t dense)
+{
+    if (!ctx) return SMC_E_NULL;
+    if (n_split < 0 || n_split > kMaxSplit) return SMC_E_RANGE;
+    ctx->n_split = n_split == 0 ? auto_split(ctx->R, ctx->cfg.V, ctx->cfg.logits_dtype) : n_split;
+    ctx->dense = dense != 0;
+    return SMC_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,89 @@
+// Internal declarations shared by the HIP translation units of libpower_smc (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "power_smc.h"
+
+namespace psmc {
+
+constexpr int kWave = 64;
+constexpr int kMaxSplit = 32;          // workgroups per row in the vocabulary pass (finalize uses 2 lanes per split)
+constexpr int kVocabThreads = 256;
+
+// Bounds of the Gumbel variate g = -log(-log u), u = (x + 1/2)/2^32 over all 32-bit words x:
+// g in [-log(33 log 2), ~33 log 2] = [-3.12999.., 22.87385..].  Rounded outwards.
+constexpr float kGumbelMin = -3.1300f;
+constexpr float kGumbelMax = 22.8740f;
+// Slack added to every "cannot win" test: covers fp32 rounding of keys, and keeps every entry whose key is
+// within this distance of the winner among the scored candidates.
+constexpr float kKeyMargin = 0.01f;
+
+// One workgroup's summary of its slice of a row.
+//   sum_v exp(l_v)        = s1 * 2^M1        (M1, Mb integer-valued floats)
+//   sum_v exp(beta * l_v) = sb * 2^Mb
+//   two best candidates of the Gumbel-max draw by fp32 key, as (logit, gumbel, index); index < 0: none
+struct alignas(16) Partial {
+    float M1, s1, Mb, sb;
+    float l1, g1; int32_t i1; float l2;
+    float g2; int32_t i2; int32_t pad0, pad1;
+};
+static_assert(sizeof(Partial) == 48, "Partial layout");
+
+struct Counters {                 // diagnostics accumulated by smc_step
+    unsigned long long bad_rows, scored, drains, seen;
+};
+
+// Groups of rows that share one ancestor, built by the plan kernel for the gather kernels.
+struct GatherPlan {
+    int32_t n_groups;             // number of (ancestor, descendants) groups over all resampled prompts
+    int32_t bad_anc;              // ancestors outside their prompt's row range (ignored rows)
+    int32_t pad[2];
+};
+
+struct Workspace {                // device pointers carved out of the caller's workspace
+    double* logW;                 // [R]
+    double* cumlogp;              // [R]
+    int32_t* parity;              // [B]
+    Partial* partials;            // [R * kMaxSplit]
+    double* d_delta;              // [R] diagnostics of the last step
+    double* d_logZ1;              // [R]
+    double* d_logZb;              // [R]
+    double* d_gap;                // [R]
+    int32_t* d_second;            // [R]
+    Counters* counters;
+    GatherPlan* plan;
+    int32_t* grp_src;             // [R] ancestor row of each group
+    int32_t* grp_base;            // [R] first row of the group's prompt
+    unsigned long long* grp_mask; // [R * mask_words] descendants of each group as a bit set over the prompt's rows
+    void** kvA;                   // [kv_tensors]
+    void** kvB;                   // [kv_tensors]
+    void** histAB;                // [2]
+};
+
+}  // namespace psmc
+
+struct smc_ctx {
+    smc_config cfg;
+    hipStream_t stream;
+    psmc::Workspace ws;
+    int R;
+    int n_split;                  // current split of a row over workgroups
+    int dense;                    // score every entry (no candidate filter)
+    int mask_words;               // 64-bit words per descendant bit set = ceil(N/64)
+    int kv_bound;
+    int hist_bound;
+    int gather_grid;              // workgroups of the persistent gather kernel
+};
+
+namespace psmc {
+
+// launchers (each enqueues on ctx->stream; returns hipGetLastError())
+hipError_t launch_init_state(smc_ctx* c);
+hipError_t launch_vocab_pass(smc_ctx* c, const void* logits, int64_t row_stride, int t, double alpha_t,
+                             double alpha_prev, double beta, int32_t* tokens_out);
+hipError_t launch_ess(smc_ctx* c, const double* logW, double* ess_out, double* lognormw_out);
+hipError_t launch_resample(smc_ctx* c, double* logW, int t, int32_t* anc, int32_t* resampled, double* ess_out);
+hipError_t launch_reindex(smc_ctx* c, const int32_t* anc, const int32_t* resampled, int valid_len, int t);
+
+}  // namespace psmc

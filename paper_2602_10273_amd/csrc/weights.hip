@@ -1,0 +1,127 @@
+// Per-prompt weight normalisation, ESS (Eq. "ess") and ESS-triggered systematic resampling
+// (Alg. 1; Sec. 7 implementation details) for gfx950.  O(R) work in fp64: one wave per prompt.
+//
+// The sums that decide discrete outcomes (ESS < kappa*N, cumulative weights against the resampling positions)
+// are accumulated in particle order by one lane, so that they round like a plain left-to-right loop.
+#include "device_rng.hpp"
+#include "smc_internal.hpp"
+
+namespace psmc {
+
+namespace {
+
+// log-sum-exp of x_i and of 2 x_i over one prompt, particle order.  Returns on every lane.
+// sh_a / sh_b: LDS scratch of N doubles each.
+__device__ void prompt_lse(const double* __restrict__ lw, int N, double* sh_a, double* sh_b, double& L1, double& L2)
+{
+    const int lane = threadIdx.x;
+    double mx = -INFINITY;
+    for (int i = lane; i < N; i += kWave) mx = fmax(mx, lw[i]);
+    mx = wave_max_f64(mx);
+    for (int i = lane; i < N; i += kWave) {
+        sh_a[i] = exp(lw[i] - mx);
+        sh_b[i] = exp(2.0 * lw[i] - 2.0 * mx);
+    }
+    __syncthreads();
+    double s1 = 0.0, s2 = 0.0;
+    if (lane == 0) {
+        for (int i = 0; i < N; ++i) { s1 += sh_a[i]; s2 += sh_b[i]; }
+    }
+    s1 = __shfl(s1, 0); s2 = __shfl(s2, 0);
+    L1 = mx + log(s1);
+    L2 = 2.0 * mx + log(s2);
+    __syncthreads();
+}
+
+}  // namespace
+
+// a3: ESS and normalised log-weights.
+__global__ __launch_bounds__(kWave) void ess_kernel(const double* __restrict__ logW, int N, double* __restrict__ ess_out,
+                                                    double* __restrict__ lognormw_out)
+{
+    __shared__ double sh_a[SMC_MAX_PARTICLES], sh_b[SMC_MAX_PARTICLES];
+    const int b = blockIdx.x, lane = threadIdx.x;
+    const double* lw = logW + (int64_t)b * N;
+    double L1, L2;
+    prompt_lse(lw, N, sh_a, sh_b, L1, L2);
+    if (lane == 0) ess_out[b] = exp(2.0 * L1 - L2);
+    if (lognormw_out)
+        for (int i = lane; i < N; i += kWave) lognormw_out[(int64_t)b * N + i] = lw[i] - L1;
+}
+
+// a3 + a4: trigger, offset u0 from the Philox stream (domain 1), ancestors A_i = min{ j : C_j >= (u0 + i)/N }
+// with C the running sum of the normalised weights in particle order, weights of resampled prompts reset.
+__global__ __launch_bounds__(kWave) void resample_kernel(double* __restrict__ logW, int N, double kappa, uint32_t key0,
+                                                         uint32_t key1, uint32_t step, int32_t* __restrict__ anc,
+                                                         int32_t* __restrict__ resampled, double* __restrict__ ess_out)
+{
+    __shared__ double sh_a[SMC_MAX_PARTICLES], sh_b[SMC_MAX_PARTICLES];
+    const int b = blockIdx.x, lane = threadIdx.x;
+    double* lw = logW + (int64_t)b * N;
+    double L1, L2;
+    prompt_lse(lw, N, sh_a, sh_b, L1, L2);
+    const double ess = exp(2.0 * L1 - L2);
+    if (lane == 0 && ess_out) ess_out[b] = ess;
+    const bool fire = ess < kappa * (double)N;           // strict; false for NaN
+    if (lane == 0) resampled[b] = fire ? 1 : 0;
+    if (!fire) {
+        for (int i = lane; i < N; i += kWave) anc[(int64_t)b * N + i] = b * N + i;
+        return;
+    }
+    for (int i = lane; i < N; i += kWave) sh_a[i] = exp(lw[i] - L1);
+    __syncthreads();
+    if (lane == 0) {
+        double c = 0.0;
+        for (int j = 0; j < N; ++j) { c += sh_a[j]; sh_b[j] = c; }
+    }
+    __syncthreads();
+    const U4 blk = philox4x32_10(0u, (uint32_t)b, step, 1u, key0, key1);
+    const double u0 = ((double)blk.x + 0.5) * 0x1p-32;
+    for (int i = lane; i < N; i += kWave) {
+        const double p = (u0 + (double)i) / (double)N;
+        // first j with C_j >= p (C is non-decreasing); N-1 if rounding leaves none
+        int lo = 0, hi = N - 1;
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (sh_b[mid] >= p) hi = mid; else lo = mid + 1;
+        }
+        anc[(int64_t)b * N + i] = b * N + lo;
+        lw[i] = 0.0;
+    }
+}
+
+// Alg. 1 initialisation: W~ = 1, empty prefixes; all prompts live in buffer A; diagnostics cleared.
+__global__ void init_state_kernel(double* logW, double* cumlogp, int32_t* parity, int R, int B, Counters* counters,
+                                  GatherPlan* plan)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < R) { logW[i] = 0.0; cumlogp[i] = 0.0; }
+    if (i < B) parity[i] = 0;
+    if (i == 0) {
+        counters->bad_rows = 0; counters->scored = 0; counters->drains = 0; counters->seen = 0;
+        plan->n_groups = 0; plan->bad_anc = 0;
+    }
+}
+
+hipError_t launch_init_state(smc_ctx* c)
+{
+    const int n = c->R > c->cfg.B ? c->R : c->cfg.B;
+    hipLaunchKernelGGL(init_state_kernel, dim3((n + 255) / 256), dim3(256), 0, c->stream, c->ws.logW, c->ws.cumlogp,
+                       c->ws.parity, c->R, c->cfg.B, c->ws.counters, c->ws.plan);
+    return hipGetLastError();
+}
+
+hipError_t launch_ess(smc_ctx* c, const double* logW, double* ess_out, double* lognormw_out)
+{
+    hipLaunchKernelGGL(ess_kernel, dim3(c->cfg.B), dim3(kWave), 0, c->stream, logW, c->cfg.N, ess_out, lognormw_out);
+    return hipGetLastError();
+}
+
+hipError_t launch_resample(smc_ctx* c, double* logW, int t, int32_t* anc, int32_t* resampled, double* ess_out)
+{
+    hipLaunchKernelGGL(resample_kernel, dim3(c->cfg.B), dim3(kWave), 0, c->stream, logW, c->cfg.N, c->cfg.kappa,
+                       (uint32_t)c->cfg.seed, (uint32_t)(c->cfg.seed >> 32), (uint32_t)t, anc, resampled, ess_out);
+    return hipGetLastError();
+}
+
+}  // namespace psmc

@@ -1,0 +1,120 @@
+"""Device-memory plumbing around the C ABI: a Session owns the torch buffers a context needs and forwards calls.
+
+No arithmetic of the method happens here -- every step runs in the HIP kernels behind `binding`.
+"""
+import numpy as np
+import torch
+
+from . import binding as smc
+
+
+class Session:
+    def __init__(self, B, N, V, T_max, dtype, kappa, seed, kv_geom=None, kv=None, with_hist=True, device="cuda",
+                 stream=None):
+        """kv_geom = (kv_tensors, H, S, D) allocates zeroed double buffers; kv = list of [R,H,S,D] bf16/uint16
+        tensors (numpy or torch) to copy into buffer A instead."""
+        self.B, self.N, self.V, self.T_max, self.R = B, N, V, T_max, B * N
+        self.dtype, self.device = dtype, device
+        dev = torch.device(device)
+        self.kvA, self.kvB = [], []
+        if kv is not None:
+            for t in kv:
+                a = torch.as_tensor(np.ascontiguousarray(t).view(np.int16)) if isinstance(t, np.ndarray) else t
+                a = a.to(dev).contiguous()
+                self.kvA.append(a)
+                self.kvB.append(torch.zeros_like(a))
+            kv_geom = (len(kv),) + tuple(self.kvA[0].shape[1:])
+        elif kv_geom is not None:
+            n, H, S, D = kv_geom
+            for _ in range(n):
+                self.kvA.append(torch.zeros((self.R, H, S, D), dtype=torch.bfloat16, device=dev))
+                self.kvB.append(torch.zeros((self.R, H, S, D), dtype=torch.bfloat16, device=dev))
+        n, H, S, D = kv_geom if kv_geom is not None else (0, 0, 0, 0)
+        self.kv_geom = (n, H, S, D)
+        self.cfg = smc.make_config(B, N, V, T_max, dtype, kappa, seed, n, H, S, D, 2)
+        nbytes = smc.smc_workspace_bytes(self.cfg)
+        if nbytes == 0:
+            raise ValueError("invalid configuration")
+        self.workspace = torch.empty(nbytes + 256, dtype=torch.uint8, device=dev)
+        base = self.workspace.data_ptr()
+        self._ws_ptr = (base + 255) & ~255
+        self.stream = stream
+        sptr = stream.cuda_stream if stream is not None else torch.cuda.current_stream(dev).cuda_stream
+        self.ctx = smc.smc_init(self.cfg, self._ws_ptr, nbytes, sptr)
+        self.tokens = torch.zeros(self.R, dtype=torch.int32, device=dev)
+        self.ess = torch.zeros(B, dtype=torch.float64, device=dev)
+        self.lognormw = torch.zeros(self.R, dtype=torch.float64, device=dev)
+        self.anc = torch.zeros(self.R, dtype=torch.int32, device=dev)
+        self.resampled = torch.zeros(B, dtype=torch.int32, device=dev)
+        self.histA = self.histB = None
+        if with_hist:
+            self.histA = torch.zeros((self.R, T_max), dtype=torch.int32, device=dev)
+            self.histB = torch.zeros((self.R, T_max), dtype=torch.int32, device=dev)
+        if n > 0 or with_hist:
+            smc.smc_kv_bind(self.ctx, self.kvA, self.kvB, self.histA, self.histB)
+
+    def close(self):
+        if self.ctx is not None:
+            smc.smc_destroy(self.ctx)
+            self.ctx = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # ---- forwards -----------------------------------------------------------------------------------------
+    def step(self, logits, t, alpha_t, alpha_prev, tau_t=-1.0):
+        smc.smc_step(self.ctx, logits, logits.stride(0), t, alpha_t, alpha_prev, tau_t, self.tokens)
+
+    def compute_ess(self):
+        smc.smc_ess(self.ctx, self.ess, self.lognormw)
+
+    def resample(self, t):
+        smc.smc_resample(self.ctx, t, self.anc, self.resampled, self.ess)
+
+    def reindex(self, valid_len, t, anc=None, resampled=None):
+        smc.smc_kv_reindex(self.ctx, self.anc if anc is None else anc,
+                           self.resampled if resampled is None else resampled, valid_len, t)
+
+    # ---- inspection ---------------------------------------------------------------------------------------
+    def state(self):
+        logW = np.empty(self.R, np.float64); cum = np.empty(self.R, np.float64); par = np.empty(self.B, np.int32)
+        smc.smc_get_state(self.ctx, logW, cum, par)
+        return logW, cum, par
+
+    def set_state(self, logW=None, cumlogp=None):
+        smc.smc_set_state(self.ctx, None if logW is None else np.ascontiguousarray(logW, np.float64),
+                          None if cumlogp is None else np.ascontiguousarray(cumlogp, np.float64))
+
+    def diag(self):
+        R = self.R
+        d = dict(delta=np.empty(R), logZ1=np.empty(R), logZb=np.empty(R), second=np.empty(R, np.int32),
+                 gap=np.empty(R), counters=np.zeros(4, np.uint64))
+        smc.smc_get_diag(self.ctx, d["delta"], d["logZ1"], d["logZb"], d["second"], d["gap"], d["counters"])
+        return d
+
+    def live_hist(self):
+        """[R, T_max] numpy: each prompt's rows taken from its live buffer."""
+        _, _, par = self.state()
+        A, Bh = self.histA.cpu().numpy(), self.histB.cpu().numpy()
+        sel = np.repeat(par, self.N).astype(bool)
+        return np.where(sel[:, None], Bh, A)
+
+    def live_kv(self, tensor, rows=None):
+        """numpy uint16 view of the live rows of one KV tensor (all rows, or the given ones)."""
+        _, _, par = self.state()
+        rows = np.arange(self.R) if rows is None else np.asarray(rows)
+        out = []
+        for r in rows:
+            src = self.kvB[tensor] if par[r // self.N] else self.kvA[tensor]
+            out.append(src[int(r)].view(torch.int16).cpu().numpy().view(np.uint16))
+        return np.stack(out)
+
+
+def to_device_logits(x, dtype, device="cuda"):
+    """numpy logits (uint16 bf16 bits or float32) -> torch tensor on the device with the same bits."""
+    if dtype == "bf16":
+        return torch.as_tensor(np.ascontiguousarray(x).view(np.int16)).to(device).view(torch.bfloat16)
+    return torch.as_tensor(np.ascontiguousarray(x, np.float32)).to(device)

@@ -1,0 +1,205 @@
+"""Component parity, HIP path vs CPU oracle, through the C ABI (needs an MI355X).
+
+Bars: tokens and ancestors bit-exact (a token may differ only where the oracle's two best Gumbel keys are closer
+than 1e-6; such rows are counted and must be rare), reindexed bytes bit-exact, log-weights / ESS within 1e-4 abs.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import reference as orc
+from paper_2602_10273_amd import synth
+from paper_2602_10273_amd.harness import Session, to_device_logits
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-4
+NEAR_TIE = 1e-6
+
+
+def check_step(w, seed, t, alpha_t, alpha_prev, tau, n_split=0, dense=0, logits=None, stride_pad=0):
+    from paper_2602_10273_amd import binding as smc
+    x = synth.logits_numpy(w, t, seed) if logits is None else logits
+    if stride_pad:
+        pad = np.zeros((w.R, stride_pad), x.dtype)
+        xs = np.concatenate([x, pad], axis=1)
+    else:
+        xs = x
+    o = orc.OracleSMC(w.B, w.N, w.V, 8, w.kappa, seed, w.dtype)
+    rng = np.random.default_rng(seed + 1)
+    o.logW[:] = rng.standard_normal(w.R); o.cumlogp[:] = -rng.random(w.R) * 5
+    s = Session(w.B, w.N, w.V, 8, w.dtype, w.kappa, seed)
+    s.set_state(o.logW, o.cumlogp)
+    smc.smc_set_tuning(s.ctx, n_split, dense)
+    want = o.step(xs, t, alpha_t, alpha_prev, tau, row_stride=xs.shape[1])
+    xd = to_device_logits(xs, w.dtype)
+    s.step(xd, t, alpha_t, alpha_prev, tau)
+    got = s.tokens.cpu().numpy()
+    logW, cum, _ = s.state()
+    d = s.diag()
+    tie = want["gap"] < NEAR_TIE
+    mism = got != want["tokens"]
+    assert not np.any(mism & ~tie), f"token mismatch outside near-ties: rows {np.nonzero(mism & ~tie)[0][:8]}"
+    assert np.all(got[mism] == want["second"][mism])            # a near-tie may only flip to the runner-up
+    assert tie.sum() <= max(1, w.R // 64)
+    ok = ~mism
+    assert np.abs(d["delta"] - want["delta"])[ok].max() < TOL
+    assert np.abs(logW - o.logW)[ok].max() < TOL
+    assert np.abs(cum - o.cumlogp)[ok].max() < TOL
+    assert np.array_equal(s.live_hist()[:, t - 1], got)
+    assert d["counters"][0] == 0
+    res = dict(tokens=got, delta=d["delta"], counters=d["counters"], ties=int(tie.sum()))
+    s.close()
+    return res
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("V", [8, 257, 5000, 40000])
+def test_step_matches_oracle_small(dtype, V):
+    w = synth.scaled(synth.WORKLOADS["cfg2"], B=3, N=4, V=V, dtype=dtype)
+    pad = (-V) % (8 if dtype == "bf16" else 4)
+    for dense in (1, 0):
+        check_step(w, seed=5, t=3, alpha_t=4.0, alpha_prev=4.0, tau=-1.0, dense=dense, stride_pad=pad)
+
+
+@pytest.mark.parametrize("name,V", [("cfg2", 152064), ("cfg3", 128256), ("cfg4", 152064), ("cfg5", 152064)])
+def test_step_matches_oracle_full_vocab(name, V):
+    """Full vocabulary width of every workload on a reduced number of rows; lazy and dense scoring agree."""
+    base = synth.WORKLOADS[name]
+    w = synth.scaled(base, B=2, N=8)
+    a = base.alpha
+    r1 = check_step(w, seed=1, t=2, alpha_t=a, alpha_prev=a, tau=-1.0)
+    r2 = check_step(w, seed=1, t=2, alpha_t=a, alpha_prev=a, tau=-1.0, dense=1)
+    assert np.array_equal(r1["tokens"], r2["tokens"])
+    assert r1["counters"][1] < r2["counters"][3]        # the lazy pass scored fewer entries than it saw
+    for ns in (1, 3, 32):
+        r3 = check_step(w, seed=1, t=2, alpha_t=a, alpha_prev=a, tau=-1.0, n_split=ns)
+        assert np.array_equal(r1["tokens"], r3["tokens"])
+
+
+@pytest.mark.parametrize("alpha_t,alpha_prev,tau", [(1.0, 1.0, -1.0), (1.0234375, 1.0, -1.0), (2.5, 2.4765625, -1.0),
+                                                     (4.0, 4.0, 0.5), (4.0, 3.0, 1.0), (6.0, 6.0, -1.0), (3.0, 3.0, 0.3)])
+def test_step_schedules_and_temperatures(alpha_t, alpha_prev, tau):
+    """Bridging stages (non-integer exponents, boundary term) and proposals other than tau = 1/alpha."""
+    for name in ("cfg4", "cfg2"):
+        w = synth.scaled(synth.WORKLOADS[name], B=2, N=4, V=20000 + 8)
+        check_step(w, seed=9, t=5, alpha_t=alpha_t, alpha_prev=alpha_prev, tau=tau)
+
+
+def test_step_degenerate_rows():
+    V = 4096 + 24
+    w = synth.scaled(synth.WORKLOADS["cfg4"], B=1, N=6, V=V)
+    x = synth.logits_numpy(w, 1, 0)
+    x[0, :] = 1.5                                   # flat row: every entry can win
+    x[1, :] = -80.0; x[1, 777] = 60.0               # one-hot
+    x[2, :] = np.linspace(-30, 30, V)               # ascending: the running maximum rises all the way
+    x[3, :] = np.linspace(30, -30, V)               # descending
+    x[4, :] = 1000.0 + x[4, :]                      # large offset
+    x[5, :] = -1000.0 + 1e-3 * x[5, :]              # large negative, tiny spread
+    res = check_step(w, seed=2, t=1, alpha_t=4.0, alpha_prev=4.0, tau=-1.0, logits=x)
+    assert res["tokens"][1] == 777
+
+
+def test_ess_and_resample_match_oracle():
+    from paper_2602_10273_amd import binding as smc
+    rng = np.random.default_rng(0)
+    for (B, N, kappa) in [(1, 4, 0.5), (16, 8, 0.5), (8, 16, 0.5), (64, 32, 0.5), (4, 64, 0.7), (3, 100, 0.9),
+                          (2, 1024, 0.6), (5, 1, 0.5)]:
+        s = Session(B, N, 64, 8, "f32", kappa, seed=123, with_hist=False)
+        for scale in (0.1, 1.0, 5.0, 40.0):
+            logW = rng.standard_normal(B * N) * scale
+            if N >= 4:
+                logW[:N] = 0.3                         # uniform prompt
+            d = torch.as_tensor(logW).cuda()
+            smc.smc_ess_from(s.ctx, d, s.ess, s.lognormw)
+            e_ref, lnw_ref = orc.ess(logW, B, N)
+            assert np.abs(s.ess.cpu().numpy() - e_ref).max() < 1e-9 * N
+            assert np.abs(s.lognormw.cpu().numpy() - lnw_ref).max() < 1e-12
+            for t in (1, 7):
+                d2 = d.clone()
+                smc.smc_resample_from(s.ctx, d2, t, s.anc, s.resampled, s.ess)
+                anc_ref, flag_ref, e2, lw_ref = orc.resample(logW, B, N, kappa, 123, t)
+                near = np.abs(e_ref - kappa * N) < 1e-9
+                assert np.array_equal(s.resampled.cpu().numpy()[~near], flag_ref[~near])
+                assert np.array_equal(s.anc.cpu().numpy(), anc_ref)          # bit-exact ancestors
+                assert np.array_equal(d2.cpu().numpy(), lw_ref)
+        s.close()
+
+
+def test_resample_degenerate_weights():
+    from paper_2602_10273_amd import binding as smc
+    B, N = 3, 8
+    s = Session(B, N, 64, 8, "f32", 0.5, seed=1, with_hist=False)
+    logW = np.zeros(B * N)
+    logW[0:N] = [0, -np.inf, -np.inf, -np.inf, -np.inf, -np.inf, -np.inf, -np.inf]
+    logW[N:2 * N] = [-800, -900, -1000, -800, -2000, -800, -800.5, -801]
+    logW[2 * N:] = 700.0
+    d = torch.as_tensor(logW).cuda()
+    smc.smc_resample_from(s.ctx, d, 3, s.anc, s.resampled, s.ess)
+    anc_ref, flag_ref, e_ref, lw_ref = orc.resample(logW, B, N, 0.5, 1, 3)
+    assert np.array_equal(s.anc.cpu().numpy(), anc_ref) and np.array_equal(s.resampled.cpu().numpy(), flag_ref)
+    assert np.allclose(s.ess.cpu().numpy(), e_ref, rtol=1e-12)
+    assert list(s.anc.cpu().numpy()[:N]) == [0] * N
+    s.close()
+
+
+@pytest.mark.parametrize("B,N,H,S,D,valid", [(3, 4, 2, 6, 16, 6), (3, 4, 2, 6, 16, 4), (4, 8, 4, 300, 128, 300),
+                                              (4, 8, 4, 300, 128, 173), (2, 64, 2, 40, 64, 40), (2, 100, 1, 33, 8, 20)])
+def test_reindex_bytes_exact(B, N, H, S, D, valid):
+    rng = np.random.default_rng(7)
+    R = B * N
+    w = synth.scaled(synth.WORKLOADS["cfg2"], B=B, N=N, H=H, S=S, D=D, layers=2)
+    kv = synth.kv_numpy(w, seed=3)
+    T_max = 16
+    s = Session(B, N, 32, T_max, "f32", 0.5, 1, kv=kv)
+    hist0 = rng.integers(0, 32, size=(R, T_max)).astype(np.int32)
+    s.histA.copy_(torch.as_tensor(hist0))
+    o = orc.OracleSMC(B, N, 32, T_max, 0.5, 1, "f32", kv=[k.copy() for k in kv])
+    o.hist[:] = hist0
+    cum = rng.standard_normal(R); o.cumlogp[:] = cum; s.set_state(None, cum)
+    for it in range(3):                                     # several rounds: parity flips back and forth
+        anc = np.arange(R, dtype=np.int32)
+        flag = (rng.random(B) < 0.7).astype(np.int32)
+        if it == 0:
+            flag[0] = 1
+        for b in range(B):
+            if it == 1 and b == 0:
+                anc[b * N:(b + 1) * N] = b * N + rng.permutation(N)                 # permutation
+            else:
+                anc[b * N:(b + 1) * N] = b * N + np.sort(rng.integers(0, N, N))     # duplicates
+        # poison the inactive buffers: stale bytes must never be read as live data
+        _, _, par = s.state()
+        for b in range(B):
+            for ten in range(len(kv)):
+                (s.kvA if par[b] else s.kvB)[ten][b * N:(b + 1) * N].fill_(-21846 if s.kvA[ten].dtype == torch.int16 else 0)
+        t = 5 + it
+        # what a step does before a reindex: column t-1 of the live history receives this step's tokens
+        col = rng.integers(0, 32, size=R).astype(np.int32)
+        o.hist[:, t - 1] = col
+        cold = torch.as_tensor(col).cuda()
+        for b in range(B):
+            (s.histB if par[b] else s.histA)[b * N:(b + 1) * N, t - 1] = cold[b * N:(b + 1) * N]
+        s.reindex(valid, t, torch.as_tensor(anc).cuda(), torch.as_tensor(flag).cuda())
+        o.reindex(anc, flag, valid, t)
+        _, cum_g, par2 = s.state()
+        assert np.array_equal(par2, par ^ flag)
+        assert np.array_equal(cum_g, o.cumlogp)
+        assert np.array_equal(s.live_hist()[:, :t], o.hist[:, :t])
+        for ten in range(len(kv)):
+            got = s.live_kv(ten)
+            assert np.array_equal(got[:, :, :valid], o.kv[ten][:, :, :valid])
+    s.close()
+
+
+def test_reindex_rejects_foreign_ancestors_without_touching_memory():
+    B, N = 2, 4
+    w = synth.scaled(synth.WORKLOADS["cfg2"], B=B, N=N, H=1, S=4, D=8, layers=1)
+    kv = synth.kv_numpy(w, seed=3)
+    s = Session(B, N, 32, 8, "f32", 0.5, 1, kv=kv)
+    anc = np.array([0, 0, 7, -3, 4, 5, 6, 7], np.int32)       # rows 2,3 point outside prompt 0
+    flag = np.array([1, 0], np.int32)
+    s.reindex(4, 1, torch.as_tensor(anc).cuda(), torch.as_tensor(flag).cuda())
+    got = s.live_kv(0)
+    assert np.array_equal(got[0], kv[0][0]) and np.array_equal(got[1], kv[0][0])
+    assert np.all(got[2] == 0) and np.all(got[3] == 0)        # skipped rows stay as the (zeroed) inactive buffer
+    s.close()
