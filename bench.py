@@ -1,0 +1,201 @@
+#!/usr/bin/env python3
+"""Throughput of the Power-SMC per-token step on one MI355X.
+
+One "step" is one pass of the whole hot path over one batch of synthetic logits with the KV cache resident in
+HBM: smc_step (boundary reweight, vocabulary pass, increment) -> smc_resample (ESS, trigger, ancestors) ->
+smc_kv_reindex (KV / history / cumulative-log-p gather for the prompts that resampled).  Resampling fires
+whenever the weights say so; how often is an observed quantity and is reported.
+
+Prints ONE JSON line.  `value` is particle-steps/s over the timed steps.  `roofline` describes the kernel that
+took the most time in a second, instrumented run of the same number of steps (HIP events recorded by the library
+on its own stream around each launch); `roofline_other` the other dominant kernel.  `cpu_baseline` times the CPU
+oracle on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=0, help="timed steps (0: per-workload default)")
+    ap.add_argument("--warmup", type=int, default=4)
+    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kv", action="store_true", help="vocabulary pass + weights only (no cache bound)")
+    ap.add_argument("--n-split", type=int, default=0)
+    return ap.parse_args()
+
+
+def cpu_baseline(w, seed, gpu_resample_frac):
+    """The oracle as it stands, on the host cores: a few full-width steps on all rows, plus the KV gather of one
+    prompt's rows scaled to the number of prompts that resample per step."""
+    import numpy as np
+    from oracle import reference as orc
+    from paper_2602_10273_amd import synth
+
+    threads = orc.threads()
+    o = orc.OracleSMC(w.B, w.N, w.V, 8, w.kappa, seed, w.dtype)
+    n_steps = 2 if w.R * w.V > 1e8 else 3
+    x = [synth.logits_torch(w, 1000 + i, seed, device="cpu") for i in range(n_steps)]
+    if w.dtype == "bf16":
+        import torch
+        x = [t.view(torch.int16).numpy().view(np.uint16) for t in x]
+    else:
+        x = [t.numpy() for t in x]
+    t0 = time.perf_counter()
+    n_res = 0
+    for i in range(n_steps):
+        o.step(x[i], i + 1, w.alpha_at(i + 1), w.alpha_at(i), -1.0)
+        _, flag, _ = o.resample(i + 1)
+        n_res += int(flag.sum())
+    t_step = (time.perf_counter() - t0) / n_steps
+    # KV gather: one prompt (N rows) of a few tensors, timed and scaled linearly to all tensors
+    n_t = max(1, min(w.kv_tensors, int(1.5e9 // (w.N * w.kv_row_bytes))))
+    rng = np.random.default_rng(seed)
+    src = [rng.integers(0, 65535, size=(w.N, w.H, w.S, w.D), dtype=np.uint16) for _ in range(n_t)]
+    dst = [np.empty_like(a) for a in src]
+    anc = np.sort(rng.integers(0, w.N, w.N)).astype(np.int32)
+    flag = np.ones(1, np.int32)
+    t0 = time.perf_counter()
+    for a, d in zip(src, dst):
+        orc.gather_kv(a, anc, flag, w.N, w.S, d)
+    t_gather_prompt = (time.perf_counter() - t0) * (w.kv_tensors / n_t)
+    t_total = t_step + t_gather_prompt * gpu_resample_frac * w.B
+    return {
+        "value": w.R / t_total, "unit": "particle-steps/s", "cores": threads, "kind": "oracle",
+        "sample": (f"{n_steps} full-width steps (vocabulary pass + ESS + resampling) on all {w.R} rows; KV gather of one "
+                   f"prompt ({w.N} rows x {n_t} of {w.kv_tensors} tensors) scaled to all tensors and to the "
+                   f"{gpu_resample_frac * w.B:.2f} prompts/step that resampled on the GPU"),
+        "step_s": t_step, "gather_prompt_s": t_gather_prompt,
+    }
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (the path shards by prompt with no communication); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    from paper_2602_10273_amd import binding as smc
+    from paper_2602_10273_amd import synth
+    from paper_2602_10273_amd.harness import Session
+
+    w = synth.WORKLOADS[args.workload]
+    K = args.steps or {"cfg2": 48, "cfg3": 16, "cfg4": 12, "cfg5": 16}[args.workload]
+    W = args.warmup
+    dev = "cuda"
+    torch.cuda.set_device(0)
+    T_max = (W + 2 * K + 8 + 3) // 4 * 4
+
+    kv_geom = None if args.no_kv else (w.kv_tensors, w.H, w.S, w.D)
+    s = Session(w.B, w.N, w.V, T_max, w.dtype, w.kappa, args.seed, kv_geom=kv_geom)
+    if args.n_split:
+        smc.smc_set_tuning(s.ctx, args.n_split, 0)
+    if not args.no_kv:
+        g = torch.Generator(device=dev); g.manual_seed(args.seed + 12345)
+        for t in s.kvA:
+            t.normal_(generator=g)
+    n_ring = 4 if w.dtype == "f32" else 16       # distinct logits buffers: more bytes than the 256 MB last-level cache
+    ring = [synth.logits_torch(w, i, args.seed) for i in range(n_ring)]
+    torch.cuda.synchronize()
+
+    step_no = [0]
+
+    def one_step():
+        step_no[0] += 1
+        t = step_no[0]
+        s.step(ring[t % n_ring], t, w.alpha_at(t), w.alpha_at(t - 1), -1.0)
+        s.resample(t)
+        s.reindex(w.S, t)
+
+    for _ in range(W):
+        one_step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(K):
+        one_step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    # ---- instrumented run of the same length: per-kernel event timing + what was gathered -------------------
+    anc_log = torch.zeros((K, w.R), dtype=torch.int32, device=dev)
+    flag_log = torch.zeros((K, w.B), dtype=torch.int32, device=dev)
+    smc.smc_profile_enable(s.ctx, 1)
+    for i in range(K):
+        step_no[0] += 1
+        t = step_no[0]
+        s.step(ring[t % n_ring], t, w.alpha_at(t), w.alpha_at(t - 1), -1.0)
+        s.resample(t)
+        anc_log[i].copy_(s.anc); flag_log[i].copy_(s.resampled)
+        s.reindex(w.S, t)
+    ms_vocab, n_vocab = smc.smc_profile_read(s.ctx, 0)
+    ms_gather, n_gather = smc.smc_profile_read(s.ctx, 1)
+    smc.smc_profile_enable(s.ctx, 0)
+    anc_h = anc_log.cpu().numpy().reshape(K, w.B, w.N)
+    flag_h = flag_log.cpu().numpy()
+    esz = 2 if w.dtype == "bf16" else 4
+    vocab_bytes = float(w.R) * w.V * esz                              # per launch: every logit read once
+    uniq = np.array([[len(np.unique(anc_h[i, b])) for b in range(w.B)] for i in range(K)])
+    rows_moved = ((uniq + w.N) * flag_h).sum()                        # unique ancestors read + N rows written
+    gather_bytes_total = float(rows_moved) * w.kv_row_bytes * w.kv_tensors
+    resample_frac = float(flag_h.mean())
+
+    def roof(name, total_bytes, ms, launches):
+        if launches == 0 or ms <= 0:
+            return {"kernel": name, "bound": "hbm", "achieved": 0.0, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                    "frac": 0.0, "traffic": None, "launches": int(launches)}
+        gbps = total_bytes / (ms * 1e-3) / 1e9
+        return {"kernel": name, "bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": gbps / HBM_PEAK_GBPS, "traffic": None, "launches": int(launches),
+                "avg_launch_ms": ms / launches, "algorithmic_bytes_per_launch": total_bytes / launches}
+
+    r_vocab = roof("vocab_pass_kernel", vocab_bytes * n_vocab, ms_vocab, n_vocab)
+    r_gather = roof("gather_kernel", gather_bytes_total, ms_gather, n_gather if not args.no_kv else 0)
+    dominant, other = (r_gather, r_vocab) if ms_gather >= ms_vocab else (r_vocab, r_gather)
+
+    # plain device copy as a second, measured denominator
+    a = torch.empty(1 << 30, dtype=torch.uint8, device=dev); b = torch.empty_like(a)
+    b.copy_(a); torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(4):
+        b.copy_(a)
+    e1.record(); torch.cuda.synchronize()
+    copy_gbps = 4 * 2 * a.numel() / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del a, b
+
+    out = {
+        "metric": "particle-steps/s (SMC step + KV reindex), 1 MI355X",
+        "value": w.R * K / elapsed, "unit": "particle-steps/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": elapsed / K * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name, "B": w.B, "N": w.N, "V": w.V, "logits_dtype": w.dtype, "alpha": w.alpha,
+                   "kappa": w.kappa, "kv": None if args.no_kv else f"{w.layers}x2 tensors [{w.R},{w.H},{w.S},{w.D}] bf16 x2 buffers",
+                   "valid_len": w.S, "resampled_prompt_fraction": resample_frac,
+                   "logits_ring": n_ring},
+        "roofline": dominant, "roofline_other": other,
+        "device_copy_GBps": copy_gbps,
+    }
+    s.close()
+    del s
+    torch.cuda.empty_cache()
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, args.seed, resample_frac if not args.no_kv else 0.0)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

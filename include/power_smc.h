@@ -127,13 +127,21 @@ smc_status smc_set_state(smc_ctx* ctx, const double* h_logW, const double* h_cum
 /* Synchronous per-row diagnostics of the last smc_step (host arrays of R entries, any may be NULL):
  * increment a2, log Z_1 = LSE(l), log Z_beta = LSE(l/tau), runner-up token, key gap between winner and
  * runner-up (in fp64), and h_counters[4] = {rows with non-finite sums, candidates scored, candidate-queue
- * drains, vocabulary entries seen}. */
+ * drains, vocabulary entries seen}, all of that one step. */
 smc_status smc_get_diag(smc_ctx* ctx, double* h_delta, double* h_logZ1, double* h_logZb, int32_t* h_second,
                         double* h_gap, uint64_t* h_counters);
 
-/* Tuning knobs (defaults chosen at smc_init): number of workgroups a row is split over in the vocabulary pass
- * (1..32; 0 = automatic) and whether every entry is scored (dense = 1) instead of only those that can win. */
-smc_status smc_set_tuning(smc_ctx* ctx, int32_t n_split, int32_t dense);
+/* Tuning knobs of the vocabulary pass (defaults chosen at smc_init): n_split = workgroups a row is split over
+ * (1..32; 0 = automatic); dense = 1 scores every entry instead of only those that can win (dense = 0, the default);
+ * wg_waves = waves per workgroup, 4 or 16 (0 = automatic).  Every setting returns the same tokens. */
+smc_status smc_set_tuning(smc_ctx* ctx, int32_t n_split, int32_t dense, int32_t wg_waves);
+
+/* Optional timing of the two dominant kernels.  While enabled, a pair of HIP events is recorded on the context's
+ * stream around every launch of kind 0 (the vocabulary-pass kernel of smc_step) and kind 1 (the KV gather kernel of
+ * smc_kv_reindex).  smc_profile_read synchronises the stream, returns the summed elapsed milliseconds and the number
+ * of launches of that kind since the last read, and clears them.  Events are host objects; no device memory is used. */
+smc_status smc_profile_enable(smc_ctx* ctx, int32_t enable);
+smc_status smc_profile_read(smc_ctx* ctx, int32_t kind, double* h_total_ms, int64_t* h_launches);
 
 const char* smc_status_str(smc_status s);
 

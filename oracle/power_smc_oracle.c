@@ -21,6 +21,19 @@
 #include <math.h>
 #include <stdint.h>
 #include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* threads the row loops run on (1 without OpenMP) */
+int orc_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
 
 /* ------------------------------------------------------------------ Philox4x32-10
  * Salmon, Moraes, Dror, Shaw, "Parallel random numbers: as easy as 1, 2, 3" (SC'11):
@@ -212,6 +225,7 @@ void orc_gather_kv(const void* src, void* dst, const int32_t* anc, const int32_t
 {
     int64_t head_stride = (int64_t)S * D * elem_bytes, row_stride = head_stride * H;
     int64_t n = (int64_t)valid_len * D * elem_bytes;
+#pragma omp parallel for schedule(static)
     for (int32_t k = 0; k < R; ++k) {
         if (!resampled[k / N]) continue;
         for (int32_t h = 0; h < H; ++h)

@@ -39,6 +39,10 @@ def _p(a):
     return a.ctypes.data_as(C.c_void_p) if a is not None else None
 
 
+def threads():
+    return int(lib().orc_threads())
+
+
 def philox4x32_10(ctr, key):
     c = (C.c_uint32 * 4)(*[int(x) for x in ctr])
     k = (C.c_uint32 * 2)(*[int(x) for x in key])

@@ -178,6 +178,7 @@ hipError_t launch_reindex(smc_ctx* c, const int32_t* anc, const int32_t* resampl
         int64_t copy_bytes = (int64_t)valid_len * pos_bytes;
         if (valid_len == cfg.kv_S) { n_chunks = 1; copy_bytes = row_stride; }       // whole row is contiguous
         const int slabs = (int)((copy_bytes + kSlabBytes - 1) / kSlabBytes);
+        ScopedKernelTimer timer(c, 1);
         hipLaunchKernelGGL((gather_kernel<true>), dim3(c->gather_grid), dim3(kGatherThreads), 0, c->stream,
                            (void* const*)w.kvA, (void* const*)w.kvB, w.parity, cfg.N, cfg.kv_tensors, n_chunks, row_stride,
                            head_stride, copy_bytes, slabs, c->mask_words, w.plan, w.grp_src, w.grp_base, w.grp_mask);

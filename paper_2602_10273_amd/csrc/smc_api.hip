@@ -48,7 +48,7 @@ size_t layout(const smc_config* c, char* base, Workspace* w)
     p = take(R * 8); if (w) w->d_logZb = (double*)p;
     p = take(R * 8); if (w) w->d_gap = (double*)p;
     p = take(R * 4); if (w) w->d_second = (int32_t*)p;
-    p = take(sizeof(Counters)); if (w) w->counters = (Counters*)p;
+    p = take(R * 12); if (w) w->d_rowstat = (int32_t*)p;
     p = take(sizeof(GatherPlan)); if (w) w->plan = (GatherPlan*)p;
     p = take(R * 4); if (w) w->grp_src = (int32_t*)p;
     p = take(R * 4); if (w) w->grp_base = (int32_t*)p;
@@ -59,16 +59,20 @@ size_t layout(const smc_config* c, char* base, Workspace* w)
     return off;
 }
 
-int auto_split(int R, int V, int dtype)
+// Launch shape of the vocabulary pass.  Few rows: big workgroups (16 waves share their bound through LDS) and just
+// enough slices per row to put about one workgroup on each of the 256 CUs.  Many rows: 4-wave workgroups, one per row.
+void auto_shape(int R, int V, int dtype, int* wg_waves, int* n_split)
 {
-    // enough workgroups to fill 256 CUs several times over, but no slice shorter than 4 tiles
     const int epv = dtype == SMC_BF16 ? 8 : 4;
-    const int tiles = ((V + epv - 1) / epv + kVocabThreads - 1) / kVocabThreads;
-    int s = (2048 + R - 1) / R;
-    if (s > tiles / 4) s = tiles / 4;
+    const int nvec = (V + epv - 1) / epv;
+    if (R >= 1024) { *wg_waves = 4; *n_split = 1; return; }
+    *wg_waves = 16;
+    const int tiles = (nvec + 1023) / 1024;
+    int s = (256 + R - 1) / R;
+    if (s > tiles) s = tiles;
     if (s > kMaxSplit) s = kMaxSplit;
     if (s < 1) s = 1;
-    return s;
+    *n_split = s;
 }
 
 }  // namespace
@@ -112,11 +116,13 @@ smc_status smc_init(const smc_config* cfg, void* d_workspace, size_t workspace_b
     c->stream = (hipStream_t)hip_stream;
     c->R = cfg->B * cfg->N;
     layout(cfg, (char*)d_workspace, &c->ws);
-    c->n_split = auto_split(c->R, cfg->V, cfg->logits_dtype);
+    auto_shape(c->R, cfg->V, cfg->logits_dtype, &c->wg_waves, &c->n_split);
     c->dense = 0;
     c->mask_words = (cfg->N + 63) / 64;
     c->kv_bound = 0;
     c->hist_bound = 0;
+    c->profiling = 0;
+    c->ev_used[0] = c->ev_used[1] = 0;
     int dev = 0, cus = 256;
     if (hipGetDevice(&dev) == hipSuccess) {
         int v = 0;
@@ -136,6 +142,8 @@ smc_status smc_destroy(smc_ctx* ctx)
 {
     if (!ctx) return SMC_E_NULL;
     const hipError_t e = hipStreamSynchronize(ctx->stream);
+    for (auto& pool : ctx->ev_pool)
+        for (hipEvent_t ev : pool) (void)hipEventDestroy(ev);
     delete ctx;
     return e == hipSuccess ? SMC_OK : SMC_E_HIP;
 }
@@ -247,17 +255,58 @@ smc_status smc_get_diag(smc_ctx* ctx, double* h_delta, double* h_logZ1, double* 
     auto get = [&](void* h, const void* d, size_t n) { return !h || hipMemcpy(h, d, n, hipMemcpyDeviceToHost) == hipSuccess; };
     if (!get(h_delta, ctx->ws.d_delta, R * 8) || !get(h_logZ1, ctx->ws.d_logZ1, R * 8) ||
         !get(h_logZb, ctx->ws.d_logZb, R * 8) || !get(h_second, ctx->ws.d_second, R * 4) ||
-        !get(h_gap, ctx->ws.d_gap, R * 8) || !get(h_counters, ctx->ws.counters, sizeof(Counters)))
+        !get(h_gap, ctx->ws.d_gap, R * 8))
         return SMC_E_HIP;
+    if (h_counters) {
+        std::vector<int32_t> st(3 * R);
+        if (hipMemcpy(st.data(), ctx->ws.d_rowstat, 3 * R * 4, hipMemcpyDeviceToHost) != hipSuccess) return SMC_E_HIP;
+        h_counters[0] = h_counters[1] = h_counters[2] = 0;
+        for (size_t r = 0; r < R; ++r) {
+            h_counters[0] += (uint64_t)st[3 * r]; h_counters[1] += (uint64_t)st[3 * r + 1]; h_counters[2] += (uint64_t)st[3 * r + 2];
+        }
+        h_counters[3] = (uint64_t)R * (uint64_t)ctx->cfg.V;
+    }
     return SMC_OK;
 }
 
-smc_status smc_set_tuning(smc_ctx* ctx, int32_t n_split, int32_t dense)
+smc_status smc_profile_enable(smc_ctx* ctx, int32_t enable)
+{
+    if (!ctx) return SMC_E_NULL;
+    if (hipStreamSynchronize(ctx->stream) != hipSuccess) return SMC_E_HIP;
+    ctx->profiling = enable != 0;
+    ctx->ev_used[0] = ctx->ev_used[1] = 0;
+    return SMC_OK;
+}
+
+smc_status smc_profile_read(smc_ctx* ctx, int32_t kind, double* h_total_ms, int64_t* h_launches)
+{
+    if (!ctx || !h_total_ms || !h_launches) return SMC_E_NULL;
+    if (kind < 0 || kind > 1) return SMC_E_RANGE;
+    if (hipStreamSynchronize(ctx->stream) != hipSuccess) return SMC_E_HIP;
+    double total = 0.0;
+    const size_t n = ctx->ev_used[kind] / 2;
+    for (size_t i = 0; i < n; ++i) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, ctx->ev_pool[kind][2 * i], ctx->ev_pool[kind][2 * i + 1]) != hipSuccess) return SMC_E_HIP;
+        total += ms;
+    }
+    *h_total_ms = total;
+    *h_launches = (int64_t)n;
+    ctx->ev_used[kind] = 0;
+    return SMC_OK;
+}
+
+smc_status smc_set_tuning(smc_ctx* ctx, int32_t n_split, int32_t dense, int32_t wg_waves)
 {
     if (!ctx) return SMC_E_NULL;
     if (n_split < 0 || n_split > kMaxSplit) return SMC_E_RANGE;
-    ctx->n_split = n_split == 0 ? auto_split(ctx->R, ctx->cfg.V, ctx->cfg.logits_dtype) : n_split;
-    ctx->dense = dense != 0;
+    if (wg_waves != 0 && wg_waves != 4 && wg_waves != 16) return SMC_E_RANGE;
+    int aw, as;
+    auto_shape(ctx->R, ctx->cfg.V, ctx->cfg.logits_dtype, &aw, &as);
+    ctx->wg_waves = wg_waves == 0 ? aw : wg_waves;
+    ctx->n_split = n_split == 0 ? (wg_waves == 0 || wg_waves == aw ? as : 1) : n_split;
+    if (dense < 0 || dense > 1) return SMC_E_RANGE;
+    ctx->dense = dense;
     return SMC_OK;
 }
 

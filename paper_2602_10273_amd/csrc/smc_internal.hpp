@@ -3,13 +3,14 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <vector>
+
 #include "power_smc.h"
 
 namespace psmc {
 
 constexpr int kWave = 64;
 constexpr int kMaxSplit = 32;          // workgroups per row in the vocabulary pass (finalize uses 2 lanes per split)
-constexpr int kVocabThreads = 256;
 
 // Bounds of the Gumbel variate g = -log(-log u), u = (x + 1/2)/2^32 over all 32-bit words x:
 // g in [-log(33 log 2), ~33 log 2] = [-3.12999.., 22.87385..].  Rounded outwards.
@@ -26,13 +27,9 @@ constexpr float kKeyMargin = 0.01f;
 struct alignas(16) Partial {
     float M1, s1, Mb, sb;
     float l1, g1; int32_t i1; float l2;
-    float g2; int32_t i2; int32_t pad0, pad1;
+    float g2; int32_t i2; int32_t n_scored, n_drains;   // diagnostics: candidates scored / ring drains in this slice
 };
 static_assert(sizeof(Partial) == 48, "Partial layout");
-
-struct Counters {                 // diagnostics accumulated by smc_step
-    unsigned long long bad_rows, scored, drains, seen;
-};
 
 // Groups of rows that share one ancestor, built by the plan kernel for the gather kernels.
 struct GatherPlan {
@@ -51,7 +48,7 @@ struct Workspace {                // device pointers carved out of the caller's 
     double* d_logZb;              // [R]
     double* d_gap;                // [R]
     int32_t* d_second;            // [R]
-    Counters* counters;
+    int32_t* d_rowstat;           // [3*R] per row: non-finite flag, candidates scored, ring drains
     GatherPlan* plan;
     int32_t* grp_src;             // [R] ancestor row of each group
     int32_t* grp_base;            // [R] first row of the group's prompt
@@ -69,14 +66,38 @@ struct smc_ctx {
     psmc::Workspace ws;
     int R;
     int n_split;                  // current split of a row over workgroups
-    int dense;                    // score every entry (no candidate filter)
+    int dense;                    // 1: score every vocabulary entry (no candidate filter)
+    int wg_waves;                 // waves per workgroup of the vocabulary pass: 4 or 16
     int mask_words;               // 64-bit words per descendant bit set = ceil(N/64)
     int kv_bound;
     int hist_bound;
     int gather_grid;              // workgroups of the persistent gather kernel
+    // optional per-kernel timing: event pairs recorded around launches of kind 0 (vocab pass) and 1 (KV gather)
+    int profiling;
+    std::vector<hipEvent_t> ev_pool[2];   // [2*i] start, [2*i+1] stop
+    size_t ev_used[2];
 };
 
 namespace psmc {
+
+// Records a start/stop event pair around one kernel launch while profiling is on.
+struct ScopedKernelTimer {
+    smc_ctx* c; int kind; hipEvent_t stop = nullptr;
+    ScopedKernelTimer(smc_ctx* ctx, int k) : c(ctx), kind(k)
+    {
+        if (!c->profiling) return;
+        auto& pool = c->ev_pool[kind];
+        if (c->ev_used[kind] + 2 > pool.size()) {
+            hipEvent_t a, b;
+            if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) return;
+            pool.push_back(a); pool.push_back(b);
+        }
+        hipEventRecord(pool[c->ev_used[kind]], c->stream);
+        stop = pool[c->ev_used[kind] + 1];
+        c->ev_used[kind] += 2;
+    }
+    ~ScopedKernelTimer() { if (stop) hipEventRecord(stop, c->stream); }
+};
 
 // launchers (each enqueues on ctx->stream; returns hipGetLastError())
 hipError_t launch_init_state(smc_ctx* c);

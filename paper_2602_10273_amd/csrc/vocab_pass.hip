@@ -5,14 +5,17 @@
 // from which the row finalizer forms log p(y), log q(y) and the increment alpha log p(y) - log q(y).
 //
 // The work is HBM-bound streaming; there is no contraction here, hence no MFMA.  A row is split over
-// n_split workgroups of 256 threads; every thread streams 16-byte vectors.  The two sums are kept per lane
+// n_split workgroups of 256 or 1024 threads; every thread streams 16-byte vectors.  The two sums are kept per lane
 // against a wave-uniform power-of-two reference, so a rising running maximum rescales them exactly.
 //
 // Exact lazy Gumbel-max: g is bounded, g in [kGumbelMin, kGumbelMax].  An entry whose best possible key
 // beta*l_v + kGumbelMax is below a key that some entry is already known to reach cannot be the argmax, so it
-// draws no random number.  The threshold on l_v ("thr") only ever rises.  Entries at or above it are compacted
-// (ballot + mbcnt) into a per-wave LDS ring and scored 64 at a time with Philox.  The result is the same
-// argmax as scoring every entry.  The "dense" instantiation scores every entry in place.
+// draws no random number.  The threshold on l_v ("thr") only ever rises; it comes from the wave's running maximum,
+// from keys already scored, and from one LDS word per workgroup that all its waves raise with an LDS atomic max
+// and read without waiting -- a stale value only makes the filter more conservative, never wrong.  Entries at or
+// above thr are compacted (ballot + mbcnt) into a per-wave LDS ring; scoring is deferred to the end of the slice,
+// when the bound is known best, and runs 64 entries at a time with Philox.  The result is the same argmax as
+// scoring every entry.  The "dense" instantiation scores every entry in place.
 #include "device_rng.hpp"
 #include "smc_internal.hpp"
 
@@ -21,7 +24,6 @@ namespace psmc {
 namespace {
 
 constexpr float kLog2e = 1.4426950408889634f;
-constexpr int kRing = 128;                     // entries per wave ring (count stays below 128: drained at >= 64)
 
 template <int DT> struct Elems;
 template <> struct Elems<SMC_BF16> { static constexpr int kPerVec = 8; using Scalar = uint16_t; };
@@ -88,25 +90,123 @@ struct LaneTop2 {
     }
 };
 
+// Best two of one candidate per lane (index < 0: none) by fp32 key relative to `ref`; ties to the lower lane.
+// Returns the lanes holding the best and the runner-up (-1: none).  `ka` / `kb` are the lane's first and second key.
+__device__ __forceinline__ void wave_best_two(float ka, float kb, bool has_a, int& lane_best, int& lane_second,
+                                              bool& second_is_b)
+{
+    const float NEG = -3.4e38f;
+    const int lane = lane_id();
+    ka = has_a ? ka : NEG;
+    const float best = wave_max_f32(ka);
+    const unsigned long long who = __ballot(ka == best && has_a);
+    lane_best = who ? __ffsll((long long)who) - 1 : -1;
+    const float mine = lane == lane_best ? kb : ka;
+    const float k2 = wave_max_f32(mine);
+    const unsigned long long who2 = __ballot(mine == k2 && k2 > NEG);
+    lane_second = who2 ? __ffsll((long long)who2) - 1 : -1;
+    second_is_b = lane_second == lane_best;
+}
+
+// Workgroup summary: per-wave sums (each against its own power-of-two reference) and per-lane best-two candidates
+// are merged and written as this slice's Partial.  m_wave is the wave's reference for comparing keys across lanes.
+template <int NW>
+__device__ __forceinline__ void block_epilogue(float beta, float m_wave, float M1, float Mb, float s1, float sb,
+                                               const LaneTop2 top, unsigned long long n_scored,
+                                               unsigned long long n_drains, Partial* __restrict__ out)
+{
+    static_assert(2 * NW <= kWave, "one wave merges two candidates per wave");
+    __shared__ float red_f[NW][5];
+    __shared__ float red_cl[NW][2], red_cg[NW][2];
+    __shared__ int32_t red_ci[NW][2];
+    __shared__ uint32_t red_n[NW][2];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const float NEG = -3.4e38f;
+
+    s1 = wave_sum_f32(s1);
+    sb = wave_sum_f32(sb);
+    {
+        const float ka = fmaf(beta, top.a.l - m_wave, top.a.g);
+        const float kb = top.b.i >= 0 ? fmaf(beta, top.b.l - m_wave, top.b.g) : NEG;
+        int lb, l2; bool sec_b;
+        wave_best_two(ka, kb, top.a.i >= 0, lb, l2, sec_b);
+        if (lane == lb) { red_cl[wave][0] = top.a.l; red_cg[wave][0] = top.a.g; red_ci[wave][0] = top.a.i; }
+        if (lane == l2) {
+            red_cl[wave][1] = sec_b ? top.b.l : top.a.l; red_cg[wave][1] = sec_b ? top.b.g : top.a.g;
+            red_ci[wave][1] = sec_b ? top.b.i : top.a.i;
+        }
+        unsigned long long sc = n_scored;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) sc += __shfl_xor(sc, o);
+        if (lane == 0) {
+            if (lb < 0) red_ci[wave][0] = -1;
+            if (l2 < 0) red_ci[wave][1] = -1;
+            red_f[wave][0] = M1; red_f[wave][1] = s1; red_f[wave][2] = Mb; red_f[wave][3] = sb; red_f[wave][4] = m_wave;
+            red_n[wave][0] = (uint32_t)sc; red_n[wave][1] = (uint32_t)n_drains;
+        }
+    }
+    __syncthreads();
+    if (wave == 0) {
+        // sums: lane w < NW holds wave w
+        const bool hw = lane < NW;
+        const float wM1 = hw ? red_f[lane][0] : -INFINITY, wMb = hw ? red_f[lane][2] : -INFINITY;
+        const float gM1 = wave_max_f32(wM1), gMb = wave_max_f32(wMb);
+        const float gm = wave_max_f32(hw ? red_f[lane][4] : -3.0e38f);
+        const float t1 = wave_sum_f32(hw ? red_f[lane][1] * fast_exp2(wM1 - gM1) : 0.f);
+        const float tb = wave_sum_f32(hw ? red_f[lane][3] * fast_exp2(wMb - gMb) : 0.f);
+        uint32_t nsc = hw ? red_n[lane][0] : 0u, ndr = hw ? red_n[lane][1] : 0u;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) { nsc += __shfl_xor(nsc, o); ndr += __shfl_xor(ndr, o); }
+        // candidates: lane c < 2*NW holds candidate (c & 1) of wave (c >> 1)
+        const bool hc = lane < 2 * NW;
+        const float cl = hc ? red_cl[lane >> 1][lane & 1] : 0.f, cg = hc ? red_cg[lane >> 1][lane & 1] : 0.f;
+        const int32_t ci = hc ? red_ci[lane >> 1][lane & 1] : -1;
+        const float key = fmaf(beta, cl - gm, cg);
+        int lb, l2; bool sec_b;
+        wave_best_two(key, NEG, ci >= 0, lb, l2, sec_b);
+        const int sb_lane = lb < 0 ? 0 : lb, s2_lane = (l2 < 0 || sec_b) ? 0 : l2;
+        const float l1v = __shfl(cl, sb_lane), g1v = __shfl(cg, sb_lane); const int32_t i1v = __shfl(ci, sb_lane);
+        const float l2v = __shfl(cl, s2_lane), g2v = __shfl(cg, s2_lane); const int32_t i2v = __shfl(ci, s2_lane);
+        if (lane == 0) {
+            Partial p;
+            p.M1 = gM1; p.s1 = t1; p.Mb = gMb; p.sb = tb;
+            p.l1 = l1v; p.g1 = g1v; p.i1 = lb < 0 ? -1 : i1v;
+            p.l2 = l2v; p.g2 = g2v; p.i2 = (l2 < 0 || sec_b) ? -1 : i2v;
+            p.n_scored = (int32_t)nsc; p.n_drains = (int32_t)ndr;
+            *out = p;
+        }
+    }
+}
+
+// order-preserving map float -> int for atomicMax on a shared lower bound
+__device__ __forceinline__ int enc_bound(float f) { const int i = __float_as_int(f); return i >= 0 ? i : i ^ 0x7FFFFFFF; }
+__device__ __forceinline__ float dec_bound(int i) { return __int_as_float(i >= 0 ? i : i ^ 0x7FFFFFFF); }
+
 }  // namespace
 
 // P > 0: beta is the integer P (sum of e^P by multiplication); P == 0: generic beta (second exp2).
-template <int DT, int P, bool DENSE>
-__global__ __launch_bounds__(kVocabThreads) void vocab_pass_kernel(
+// DENSE: every entry is scored in place (no filter, no ring) -- the plain definition, kept for cross-checks.
+// NW: waves per workgroup (4 or 16).
+template <int DT, int P, bool DENSE, int NW>
+__global__ __launch_bounds__(NW * kWave) void vocab_pass_kernel(
     const void* __restrict__ logits, int64_t row_stride_bytes, int V, float beta, uint32_t key0, uint32_t key1,
-    uint32_t step, int n_split, int vecs_per_split, Partial* __restrict__ partials, Counters* __restrict__ counters)
+    uint32_t step, int n_split, int vecs_per_split, Partial* __restrict__ partials)
 {
     constexpr int EPV = Elems<DT>::kPerVec;
     constexpr int UNROLL = 4;
-    __shared__ uint32_t ring_idx[kVocabThreads / kWave][kRing];
-    __shared__ float ring_val[kVocabThreads / kWave][kRing];
-    __shared__ float red_f[kVocabThreads / kWave][4];
-    __shared__ Cand red_c[kVocabThreads / kWave][2];
+    constexpr int THREADS = NW * kWave;
+    constexpr int kRing = 1024;                        // candidate ring entries per wave (power of two)
+    static_assert(kRing >= 2 * EPV * kWave, "a full vector of candidates must fit beside a partly filled ring");
+    __shared__ uint32_t ring_idx[DENSE ? 1 : NW][DENSE ? 1 : kRing];
+    __shared__ float ring_val[DENSE ? 1 : NW][DENSE ? 1 : kRing];
+    __shared__ int wg_bound;                           // best "cannot win below this" bound of the whole workgroup
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int split = blockIdx.x % n_split;
     const uint32_t row = blockIdx.x / n_split;
     const char* rowp = (const char*)logits + (int64_t)row * row_stride_bytes;
+    if (tid == 0) wg_bound = enc_bound(-INFINITY);
+    __syncthreads();
 
     const int nvec_full = V / EPV;                      // vectors wholly inside the row
     const int nvec = (V + EPV - 1) / EPV;
@@ -120,11 +220,14 @@ __global__ __launch_bounds__(kVocabThreads) void vocab_pass_kernel(
     float m = -3.0e38f;            // running max of the logits seen by this wave
     float M1 = -INFINITY, Mb = -INFINITY;   // power-of-two references (integers): M1 >= m*log2e, Mb >= m*beta*log2e
     float thr = -3.4e38f;          // entries below thr cannot win
+    float published = -3.4e38f;    // what this wave last wrote to the row's shared bound
     float c1 = 0.f, cb = 0.f;      // c1 = M1 - m*log2e, cb = Mb - m*beta*log2e, both >= 0
     float s1 = 0.f, sb = 0.f;      // per-lane sums relative to the references
     int q_head = 0, q_count = 0;
     unsigned long long n_scored = 0, n_drains = 0;
     LaneTop2 top; top.init();
+
+    auto lower = [](float b) { return b - fabsf(b) * 4e-7f; };    // a few ulps down: never drop a possible winner
 
     auto raise_max = [&](float nm) {                    // nm > m, wave-uniform
         nm = uniform(nm);
@@ -137,35 +240,63 @@ __global__ __launch_bounds__(kVocabThreads) void vocab_pass_kernel(
         // fp32 rounding of the SMALL quantity (x-m), not of the large products x*log2e
         c1 = (float)((double)nM1 - (double)nm * 1.4426950408889634074);
         cb = (float)((double)nMb - (double)nm * (double)beta * 1.4426950408889634074);
-        const float bound = m - window;
-        thr = fmaxf(thr, bound - fabsf(bound) * 4e-7f);   // a few ulps down: the test must never drop a possible winner
+        thr = fmaxf(thr, lower(m - window));
     };
 
-    auto score = [&](uint32_t idx, float xv) {          // one candidate on this lane
-        const U4 blk = philox4x32_10(idx >> 2, row, step, 0u, key0, key1);
-        const float g = gumbel_f32(pick_word(blk, idx & 3u));
-        top.offer(beta, xv, g, (int32_t)idx);
+    auto publish = [&]() {                              // let the other waves of the workgroup use this wave's bound
+        if (thr > published) {
+            if (lane == 0) atomicMax(&wg_bound, enc_bound(thr));
+            published = thr;
+        }
+    };
+    auto adopt = [&]() {                                // and take theirs (no waiting: stale is only conservative)
+        const int seen = __hip_atomic_load(&wg_bound, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        thr = fmaxf(thr, uniform(dec_bound(seen)));
     };
 
-    auto tighten = [&]() {                              // raise thr from the keys reached so far
-        float bound = top.a.i >= 0 ? top.a.l + (top.a.g - kGumbelMax - kKeyMargin) / beta : -3.4e38f;
-        bound = uniform(wave_max_f32(bound));
-        thr = fmaxf(thr, bound - fabsf(bound) * 4e-7f);
-    };
-
-    auto drain = [&](int n) {                           // score n <= 64 ring entries
+    // Scores up to 64 ring entries (those still at or above thr) and tightens thr from the keys reached.
+    auto drain = [&](int n) {
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // ring writes of other lanes, same wave
         __builtin_amdgcn_wave_barrier();
         if (lane < n) {
             const int slot = (q_head + lane) & (kRing - 1);
-            const uint32_t idx = ring_idx[wave][slot];
-            const float xv = ring_val[wave][slot];
-            if (xv >= thr) { score(idx, xv); ++n_scored; }
+            const uint32_t idx = ring_idx[DENSE ? 0 : wave][slot];
+            const float xv = ring_val[DENSE ? 0 : wave][slot];
+            if (xv >= thr) {
+                const U4 blk = philox4x32_10(idx >> 2, row, step, 0u, key0, key1);
+                top.offer(beta, xv, gumbel_f32(pick_word(blk, idx & 3u)), (int32_t)idx);
+                ++n_scored;
+            }
         }
         q_head = (q_head + n) & (kRing - 1);
         q_count -= n;
         ++n_drains;
-        tighten();
+        float bound = top.a.i >= 0 ? top.a.l + (top.a.g - kGumbelMax - kKeyMargin) / beta : -3.4e38f;
+        bound = uniform(wave_max_f32(bound));
+        thr = fmaxf(thr, lower(bound));
+    };
+
+    // Drops ring entries that have fallen below thr, keeping the order of the rest.
+    auto compact = [&]() {
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        int kept = 0;
+        for (int base = 0; base < q_count; base += kWave) {
+            const int src = (q_head + base + lane) & (kRing - 1);
+            const bool in = base + lane < q_count;
+            const uint32_t idx = in ? ring_idx[DENSE ? 0 : wave][src] : 0u;
+            const float xv = in ? ring_val[DENSE ? 0 : wave][src] : 0.f;
+            const bool keep = in && xv >= thr;
+            const unsigned long long mk = __ballot(keep);
+            __builtin_amdgcn_wave_barrier();            // all lanes have read this chunk before any lane overwrites it
+            if (keep) {
+                const int dst = (q_head + kept + mask_rank(mk)) & (kRing - 1);
+                ring_idx[DENSE ? 0 : wave][dst] = idx;
+                ring_val[DENSE ? 0 : wave][dst] = xv;
+            }
+            kept += __popcll(mk);
+        }
+        q_count = kept;
     };
 
     auto process = [&](const float (&x)[EPV], int v0) {
@@ -185,17 +316,21 @@ __global__ __launch_bounds__(kVocabThreads) void vocab_pass_kernel(
                 }
             }
         } else {
+            // Scoring is deferred: entries that may still win are only queued here.  By the time the queue is
+            // scored the row's bound is far better than what this wave knows now, and most entries drop out.
+            if (q_count > kRing - EPV * kWave) {                             // rare: make room for one more vector
+                compact();
+                while (q_count > kRing - EPV * kWave) drain(min(q_count, kWave));
+            }
+            // The row's shared bound can lift thr above this wave's own maximum, so the gate into the slow path is
+            // min(thr, m): it must also catch every entry that raises m (the sums below need x <= m).
 #pragma unroll
             for (int j = 0; j < EPV; ++j) {
-                const bool hit = x[j] >= thr;
+                const bool hit = x[j] >= fminf(thr, m);
                 const unsigned long long mk = __ballot(hit);
                 if (mk) {                                                   // wave-uniform
-                    if (__ballot(x[j] > m)) {
-                        const float nm = wave_max_f32(x[j]);
-                        raise_max(nm);
-                    }
-                    // re-test against the possibly raised threshold, then compact into the ring
-                    const bool keep = x[j] >= thr;
+                    if (__ballot(x[j] > m)) raise_max(wave_max_f32(x[j]));
+                    const bool keep = x[j] >= thr;                          // against the possibly raised threshold
                     const unsigned long long mk2 = __ballot(keep);
                     if (keep) {
                         const int slot = (q_head + q_count + mask_rank(mk2)) & (kRing - 1);
@@ -203,7 +338,6 @@ __global__ __launch_bounds__(kVocabThreads) void vocab_pass_kernel(
                         ring_val[wave][slot] = x[j];
                     }
                     q_count += __popcll(mk2);
-                    if (q_count >= kWave) drain(kWave);
                 }
             }
         }
@@ -232,11 +366,11 @@ __global__ __launch_bounds__(kVocabThreads) void vocab_pass_kernel(
 
     // main stream: UNROLL vectors per thread in flight
     bool first = true;
-    for (int base = vec_begin; base < vec_end; base += kVocabThreads * UNROLL) {
+    for (int base = vec_begin; base < vec_end; base += THREADS * UNROLL) {
         float x[UNROLL][EPV];
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
-            const int vi = base + u * kVocabThreads + tid;
+            const int vi = base + u * THREADS + tid;
             if (vi < vec_end) load_vec(vi, x[u]);
             else {
 #pragma unroll
@@ -252,70 +386,26 @@ __global__ __launch_bounds__(kVocabThreads) void vocab_pass_kernel(
                 for (int j = 0; j < EPV; ++j) vm = fmaxf(vm, x[u][j]);
             vm = wave_max_f32(vm);
             if (vm > m) raise_max(vm);
+            if constexpr (!DENSE) { publish(); adopt(); }
         }
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
-            if (base + u * kVocabThreads + (wave << 6) < vec_end)          // wave-uniform: wave has data
-                process(x[u], (base + u * kVocabThreads + tid) * EPV);
+            if (base + u * THREADS + (wave << 6) < vec_end)                // wave-uniform: wave has data
+                process(x[u], (base + u * THREADS + tid) * EPV);
         }
+        if constexpr (!DENSE) { publish(); adopt(); }
     }
     if constexpr (!DENSE) {
-        while (q_count > 0) drain(min(q_count, kWave));
+        // every wave has streamed its share: the workgroup's bound now reflects the maximum of the whole slice
+        __syncthreads();
+        adopt();
+        while (q_count > 0) {
+            compact();
+            if (q_count > 0) { drain(min(q_count, kWave)); publish(); adopt(); }
+        }
     }
 
-    // ---- wave summary
-    s1 = wave_sum_f32(s1);
-    sb = wave_sum_f32(sb);
-    // wave top-2 by fp32 key relative to the wave max
-    const float NEG = -3.4e38f;
-    const float ka = top.a.i >= 0 ? fmaf(beta, top.a.l - m, top.a.g) : NEG;
-    const float kb = top.b.i >= 0 ? fmaf(beta, top.b.l - m, top.b.g) : NEG;
-    const float best = wave_max_f32(ka);
-    const unsigned long long who = __ballot(ka == best && top.a.i >= 0);
-    const int wlane = who ? __ffsll((long long)who) - 1 : -1;
-    const float k2 = wave_max_f32(lane == wlane ? kb : ka);
-    const unsigned long long who2 = __ballot((lane == wlane ? kb : ka) == k2 && k2 > NEG);
-    const int wlane2 = who2 ? __ffsll((long long)who2) - 1 : -1;
-    if (lane == wlane) red_c[wave][0] = top.a;
-    if (lane == wlane2) red_c[wave][1] = (lane == wlane) ? top.b : top.a;
-    if (lane == 0) {
-        if (wlane < 0) red_c[wave][0] = Cand{0.f, 0.f, -1};
-        if (wlane2 < 0) red_c[wave][1] = Cand{0.f, 0.f, -1};
-        red_f[wave][0] = M1; red_f[wave][1] = s1; red_f[wave][2] = Mb; red_f[wave][3] = sb;
-    }
-    // counters: one atomic per wave
-    {
-        unsigned long long sc = n_scored;
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) sc += __shfl_xor(sc, o);
-        if (lane == 0 && counters) {
-            atomicAdd(&counters->scored, sc);
-            atomicAdd(&counters->drains, n_drains);
-        }
-    }
-    __syncthreads();
-    if (tid == 0) {
-        constexpr int NW = kVocabThreads / kWave;
-        float gM1 = red_f[0][0], gMb = red_f[0][2];
-        for (int w = 1; w < NW; ++w) { gM1 = fmaxf(gM1, red_f[w][0]); gMb = fmaxf(gMb, red_f[w][2]); }
-        float t1 = 0.f, tb = 0.f;
-        for (int w = 0; w < NW; ++w) {
-            t1 += red_f[w][1] * fast_exp2(red_f[w][0] - gM1);
-            tb += red_f[w][3] * fast_exp2(red_f[w][2] - gMb);
-        }
-        LaneTop2 t; t.init();
-        for (int w = 0; w < NW; ++w)
-            for (int k = 0; k < 2; ++k) {
-                const Cand c = red_c[w][k];
-                if (c.i >= 0) t.offer(beta, c.l, c.g, c.i);
-            }
-        Partial p;
-        p.M1 = gM1; p.s1 = t1; p.Mb = gMb; p.sb = tb;
-        p.l1 = t.a.l; p.g1 = t.a.g; p.i1 = t.a.i; p.l2 = t.b.l; p.g2 = t.b.g; p.i2 = t.b.i;
-        p.pad0 = 0; p.pad1 = 0;
-        partials[(int64_t)row * kMaxSplit + split] = p;
-        if (counters && split == 0) atomicAdd(&counters->seen, (unsigned long long)V);
-    }
+    block_epilogue<NW>(beta, m, M1, Mb, s1, sb, top, n_scored, n_drains, partials + (int64_t)row * kMaxSplit + split);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -329,7 +419,7 @@ __global__ __launch_bounds__(kWave) void finalize_rows_kernel(
     double* __restrict__ logW, double* __restrict__ cumlogp, const int32_t* __restrict__ parity,
     int32_t* const* __restrict__ histAB, int T_max, int32_t* __restrict__ tokens_out, double* __restrict__ d_delta,
     double* __restrict__ d_logZ1, double* __restrict__ d_logZb, double* __restrict__ d_gap,
-    int32_t* __restrict__ d_second, Counters* __restrict__ counters)
+    int32_t* __restrict__ d_second, int32_t* __restrict__ d_rowstat)
 {
     const int lane = threadIdx.x;
     const uint32_t row = blockIdx.x;
@@ -346,9 +436,15 @@ __global__ __launch_bounds__(kWave) void finalize_rows_kernel(
     const double logZ1 = gM1 * LN2 + log(S1);
     const double logZb = gMb * LN2 + log(Sb);
 
+    int32_t nsc = 0, ndr = 0;
+    if (lane < n_split) { nsc = pp[lane].n_scored; ndr = pp[lane].n_drains; }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) { nsc += __shfl_xor(nsc, o); ndr += __shfl_xor(ndr, o); }
+
     // finalists: lane c -> candidate (c & 1) of split (c >> 1)
     int32_t idx = -1;
     if (lane < 2 * n_split) idx = (lane & 1) ? pp[lane >> 1].i2 : pp[lane >> 1].i1;
+    if (idx >= V) idx = -1;                            // never read outside the row, whatever the partial holds
     double key = -INFINITY, lv = 0.0;
     if (idx >= 0) {
         lv = (double)load_scalar<DT>(rowp, idx);
@@ -388,23 +484,23 @@ __global__ __launch_bounds__(kWave) void finalize_rows_kernel(
         d_delta[row] = delta; d_logZ1[row] = logZ1; d_logZb[row] = logZb;
         d_gap[row] = k1 - k2;
         d_second[row] = cand2 == 0x7FFFFFFF ? -1 : cand2;
-        if (!ok) atomicAdd(&counters->bad_rows, 1ull);
+        d_rowstat[3 * row] = ok ? 0 : 1; d_rowstat[3 * row + 1] = nsc; d_rowstat[3 * row + 2] = ndr;
     }
 }
 
 // ------------------------------------------------------------------------------------------------
-template <int DT, bool DENSE>
+template <int DT, bool DENSE, int NW>
 static hipError_t launch_k1(smc_ctx* c, const void* logits, int64_t row_stride_bytes, int t, float betaf,
                             int n_split, int vecs_per_split)
 {
-    const dim3 grid((unsigned)(c->R * n_split)), block(kVocabThreads);
+    const dim3 grid((unsigned)(c->R * n_split)), block(NW * kWave);
     const uint32_t k0 = (uint32_t)c->cfg.seed, k1 = (uint32_t)(c->cfg.seed >> 32);
     const int V = c->cfg.V;
-    Partial* pa = c->ws.partials; Counters* cn = c->ws.counters;
+    Partial* pa = c->ws.partials;
     int P = 0;
     if (betaf == floorf(betaf) && betaf >= 1.f && betaf <= 8.f && betaf != 7.f) P = (int)betaf;
-#define PSMC_LAUNCH(PP) hipLaunchKernelGGL((vocab_pass_kernel<DT, PP, DENSE>), grid, block, 0, c->stream, logits, \
-                                           row_stride_bytes, V, betaf, k0, k1, (uint32_t)t, n_split, vecs_per_split, pa, cn)
+#define PSMC_LAUNCH(PP) hipLaunchKernelGGL((vocab_pass_kernel<DT, PP, DENSE, NW>), grid, block, 0, c->stream, logits, \
+                                           row_stride_bytes, V, betaf, k0, k1, (uint32_t)t, n_split, vecs_per_split, pa)
     switch (P) {
         case 1: PSMC_LAUNCH(1); break;
         case 2: PSMC_LAUNCH(2); break;
@@ -427,22 +523,29 @@ hipError_t launch_vocab_pass(smc_ctx* c, const void* logits, int64_t row_stride,
     const int epv = 16 / esz;
     const int64_t row_stride_bytes = row_stride * esz;
     const int nvec = (c->cfg.V + epv - 1) / epv;
+    // workgroup size: 16 waves when there are few rows (the waves of a workgroup share their bound through LDS),
+    // 4 waves when rows alone fill the chip
+    const int nw = c->wg_waves;
+    const int threads = nw * kWave;
     // split a row into n_split contiguous runs of whole "tiles" (one vector per thread)
     int n_split = c->n_split;
-    int tiles = (nvec + kVocabThreads - 1) / kVocabThreads;
+    const int tiles = (nvec + threads - 1) / threads;
     if (n_split > tiles) n_split = tiles;
     const int tiles_per_split = (tiles + n_split - 1) / n_split;
     n_split = (tiles + tiles_per_split - 1) / tiles_per_split;
-    const int vecs_per_split = tiles_per_split * kVocabThreads;
+    const int vecs_per_split = tiles_per_split * threads;
 
     hipError_t e;
     const float betaf = (float)beta;
-    if (dt == SMC_BF16)
-        e = c->dense ? launch_k1<SMC_BF16, true>(c, logits, row_stride_bytes, t, betaf, n_split, vecs_per_split)
-                     : launch_k1<SMC_BF16, false>(c, logits, row_stride_bytes, t, betaf, n_split, vecs_per_split);
-    else
-        e = c->dense ? launch_k1<SMC_F32, true>(c, logits, row_stride_bytes, t, betaf, n_split, vecs_per_split)
-                     : launch_k1<SMC_F32, false>(c, logits, row_stride_bytes, t, betaf, n_split, vecs_per_split);
+    {
+        ScopedKernelTimer timer(c, 0);
+#define PSMC_GO(DT, DENSE)                                                                                  \
+    (nw == 16 ? launch_k1<DT, DENSE, 16>(c, logits, row_stride_bytes, t, betaf, n_split, vecs_per_split)    \
+              : launch_k1<DT, DENSE, 4>(c, logits, row_stride_bytes, t, betaf, n_split, vecs_per_split))
+        if (dt == SMC_BF16) e = c->dense ? PSMC_GO(SMC_BF16, true) : PSMC_GO(SMC_BF16, false);
+        else e = c->dense ? PSMC_GO(SMC_F32, true) : PSMC_GO(SMC_F32, false);
+#undef PSMC_GO
+    }
     if (e != hipSuccess) return e;
 
     const uint32_t k0 = (uint32_t)c->cfg.seed, k1 = (uint32_t)(c->cfg.seed >> 32);
@@ -452,12 +555,12 @@ hipError_t launch_vocab_pass(smc_ctx* c, const void* logits, int64_t row_stride,
         hipLaunchKernelGGL((finalize_rows_kernel<SMC_BF16>), dim3(c->R), dim3(kWave), 0, c->stream, logits,
                            row_stride_bytes, c->cfg.V, c->cfg.N, beta, alpha_t, alpha_prev, k0, k1, (uint32_t)t, n_split,
                            w.partials, w.logW, w.cumlogp, w.parity, hist, c->cfg.T_max, tokens_out, w.d_delta,
-                           w.d_logZ1, w.d_logZb, w.d_gap, w.d_second, w.counters);
+                           w.d_logZ1, w.d_logZb, w.d_gap, w.d_second, w.d_rowstat);
     else
         hipLaunchKernelGGL((finalize_rows_kernel<SMC_F32>), dim3(c->R), dim3(kWave), 0, c->stream, logits,
                            row_stride_bytes, c->cfg.V, c->cfg.N, beta, alpha_t, alpha_prev, k0, k1, (uint32_t)t, n_split,
                            w.partials, w.logW, w.cumlogp, w.parity, hist, c->cfg.T_max, tokens_out, w.d_delta,
-                           w.d_logZ1, w.d_logZb, w.d_gap, w.d_second, w.counters);
+                           w.d_logZ1, w.d_logZb, w.d_gap, w.d_second, w.d_rowstat);
     return hipGetLastError();
 }
 

@@ -91,14 +91,13 @@ __global__ __launch_bounds__(kWave) void resample_kernel(double* __restrict__ lo
 }
 
 // Alg. 1 initialisation: W~ = 1, empty prefixes; all prompts live in buffer A; diagnostics cleared.
-__global__ void init_state_kernel(double* logW, double* cumlogp, int32_t* parity, int R, int B, Counters* counters,
+__global__ void init_state_kernel(double* logW, double* cumlogp, int32_t* parity, int R, int B, int32_t* rowstat,
                                   GatherPlan* plan)
 {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < R) { logW[i] = 0.0; cumlogp[i] = 0.0; }
+    if (i < R) { logW[i] = 0.0; cumlogp[i] = 0.0; rowstat[3 * i] = 0; rowstat[3 * i + 1] = 0; rowstat[3 * i + 2] = 0; }
     if (i < B) parity[i] = 0;
     if (i == 0) {
-        counters->bad_rows = 0; counters->scored = 0; counters->drains = 0; counters->seen = 0;
         plan->n_groups = 0; plan->bad_anc = 0;
     }
 }
@@ -107,7 +106,7 @@ hipError_t launch_init_state(smc_ctx* c)
 {
     const int n = c->R > c->cfg.B ? c->R : c->cfg.B;
     hipLaunchKernelGGL(init_state_kernel, dim3((n + 255) / 256), dim3(256), 0, c->stream, c->ws.logW, c->ws.cumlogp,
-                       c->ws.parity, c->R, c->cfg.B, c->ws.counters, c->ws.plan);
+                       c->ws.parity, c->R, c->cfg.B, c->ws.d_rowstat, c->ws.plan);
     return hipGetLastError();
 }
 

@@ -17,7 +17,7 @@ TOL = 1e-4
 NEAR_TIE = 1e-6
 
 
-def check_step(w, seed, t, alpha_t, alpha_prev, tau, n_split=0, dense=0, logits=None, stride_pad=0):
+def check_step(w, seed, t, alpha_t, alpha_prev, tau, n_split=0, dense=0, logits=None, stride_pad=0, wg_waves=0):
     from paper_2602_10273_amd import binding as smc
     x = synth.logits_numpy(w, t, seed) if logits is None else logits
     if stride_pad:
@@ -30,7 +30,7 @@ def check_step(w, seed, t, alpha_t, alpha_prev, tau, n_split=0, dense=0, logits=
     o.logW[:] = rng.standard_normal(w.R); o.cumlogp[:] = -rng.random(w.R) * 5
     s = Session(w.B, w.N, w.V, 8, w.dtype, w.kappa, seed)
     s.set_state(o.logW, o.cumlogp)
-    smc.smc_set_tuning(s.ctx, n_split, dense)
+    smc.smc_set_tuning(s.ctx, n_split, dense, wg_waves)
     want = o.step(xs, t, alpha_t, alpha_prev, tau, row_stride=xs.shape[1])
     xd = to_device_logits(xs, w.dtype)
     s.step(xd, t, alpha_t, alpha_prev, tau)
@@ -58,8 +58,9 @@ def check_step(w, seed, t, alpha_t, alpha_prev, tau, n_split=0, dense=0, logits=
 def test_step_matches_oracle_small(dtype, V):
     w = synth.scaled(synth.WORKLOADS["cfg2"], B=3, N=4, V=V, dtype=dtype)
     pad = (-V) % (8 if dtype == "bf16" else 4)
-    for dense in (1, 0):
-        check_step(w, seed=5, t=3, alpha_t=4.0, alpha_prev=4.0, tau=-1.0, dense=dense, stride_pad=pad)
+    for mode in (1, 0):                # every entry scored / only entries that can win
+        for ww in (4, 16):
+            check_step(w, seed=5, t=3, alpha_t=4.0, alpha_prev=4.0, tau=-1.0, dense=mode, stride_pad=pad, wg_waves=ww)
 
 
 @pytest.mark.parametrize("name,V", [("cfg2", 152064), ("cfg3", 128256), ("cfg4", 152064), ("cfg5", 152064)])
@@ -72,8 +73,8 @@ def test_step_matches_oracle_full_vocab(name, V):
     r2 = check_step(w, seed=1, t=2, alpha_t=a, alpha_prev=a, tau=-1.0, dense=1)
     assert np.array_equal(r1["tokens"], r2["tokens"])
     assert r1["counters"][1] < r2["counters"][3]        # the lazy pass scored fewer entries than it saw
-    for ns in (1, 3, 32):
-        r3 = check_step(w, seed=1, t=2, alpha_t=a, alpha_prev=a, tau=-1.0, n_split=ns)
+    for ns, ww in ((1, 4), (3, 4), (32, 4), (1, 16), (2, 16), (7, 16)):       # launch shapes: slices per row, waves
+        r3 = check_step(w, seed=1, t=2, alpha_t=a, alpha_prev=a, tau=-1.0, n_split=ns, wg_waves=ww)
         assert np.array_equal(r1["tokens"], r3["tokens"])
 
 
@@ -83,7 +84,8 @@ def test_step_schedules_and_temperatures(alpha_t, alpha_prev, tau):
     """Bridging stages (non-integer exponents, boundary term) and proposals other than tau = 1/alpha."""
     for name in ("cfg4", "cfg2"):
         w = synth.scaled(synth.WORKLOADS[name], B=2, N=4, V=20000 + 8)
-        check_step(w, seed=9, t=5, alpha_t=alpha_t, alpha_prev=alpha_prev, tau=tau)
+        for mode in (0, 1):
+            check_step(w, seed=9, t=5, alpha_t=alpha_t, alpha_prev=alpha_prev, tau=tau, dense=mode)
 
 
 def test_step_degenerate_rows():
@@ -96,8 +98,9 @@ def test_step_degenerate_rows():
     x[3, :] = np.linspace(30, -30, V)               # descending
     x[4, :] = 1000.0 + x[4, :]                      # large offset
     x[5, :] = -1000.0 + 1e-3 * x[5, :]              # large negative, tiny spread
-    res = check_step(w, seed=2, t=1, alpha_t=4.0, alpha_prev=4.0, tau=-1.0, logits=x)
-    assert res["tokens"][1] == 777
+    for mode, ww in ((0, 4), (0, 16), (1, 4)):
+        res = check_step(w, seed=2, t=1, alpha_t=4.0, alpha_prev=4.0, tau=-1.0, logits=x, dense=mode, wg_waves=ww)
+        assert res["tokens"][1] == 777
 
 
 def test_ess_and_resample_match_oracle():
