@@ -162,8 +162,20 @@ def main():
                 "frac": gbps / HBM_PEAK_GBPS, "traffic": None, "launches": int(launches),
                 "avg_launch_ms": ms / launches, "algorithmic_bytes_per_launch": total_bytes / launches}
 
+    # HBM traffic per launch: measured offline with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (calibrated on a copy of
+    # known size) as a multiple of the algorithmic bytes; the committed ratio is applied to this run's bytes.
+    ratios = {}
+    try:
+        ratios = json.load(open(os.path.join(ROOT, "profiles", "hbm_traffic_ratio.json"))).get(args.workload, {})
+    except OSError:
+        pass
+
     r_vocab = roof("vocab_pass_kernel", vocab_bytes * n_vocab, ms_vocab, n_vocab)
     r_gather = roof("gather_kernel", gather_bytes_total, ms_gather, n_gather if not args.no_kv else 0)
+    for r in (r_vocab, r_gather):
+        if r["kernel"] in ratios and r.get("algorithmic_bytes_per_launch"):
+            r["traffic"] = ratios[r["kernel"]] * r["algorithmic_bytes_per_launch"]
+            r["traffic_source"] = "profiles/hbm_traffic_ratio.json x algorithmic bytes of this run"
     dominant, other = (r_gather, r_vocab) if ms_gather >= ms_vocab else (r_vocab, r_gather)
 
     # plain device copy as a second, measured denominator

@@ -136,6 +136,11 @@ smc_status smc_get_diag(smc_ctx* ctx, double* h_delta, double* h_logZ1, double* 
  * wg_waves = waves per workgroup, 4 or 16 (0 = automatic).  Every setting returns the same tokens. */
 smc_status smc_set_tuning(smc_ctx* ctx, int32_t n_split, int32_t dense, int32_t wg_waves);
 
+/* Tuning knobs of the KV gather: persistent workgroups per compute unit (1..64) and the kernel variant
+ * (0..10: 16-byte vectors in flight per thread in {8,4,16,2} crossed with non-temporal loads/stores on or off;
+ * the default is 4 workgroups per compute unit and variant 4).  Every setting moves the same bytes. */
+smc_status smc_set_gather_tuning(smc_ctx* ctx, int32_t wgs_per_cu, int32_t variant);
+
 /* Optional timing of the two dominant kernels.  While enabled, a pair of HIP events is recorded on the context's
  * stream around every launch of kind 0 (the vocabulary-pass kernel of smc_step) and kind 1 (the KV gather kernel of
  * smc_kv_reindex).  smc_profile_read synchronises the stream, returns the summed elapsed milliseconds and the number

@@ -7,7 +7,7 @@
 // every descendant, so a reindex moves (unique ancestors + N) rows per prompt, the least the method allows.
 //
 //   plan_kernel    : one wave per prompt, builds the groups (ancestor row, bit set of descendants).
-//   gather_kernel  : persistent grid-stride loop over (group, tensor, head chunk, 32 KiB slab).
+//   gather_kernel  : persistent grid-stride loop over (group, tensor, head chunk, slab of 8..64 KiB).
 //   commit_kernel  : cumulative log p gathered the same way, parity flipped, plan cleared for the next call.
 #include "device_rng.hpp"
 #include "smc_internal.hpp"
@@ -16,8 +16,6 @@ namespace psmc {
 
 namespace {
 constexpr int kGatherThreads = 256;
-constexpr int kVecPerThread = 8;                                   // 16-byte vectors in flight per thread
-constexpr int kSlabBytes = kGatherThreads * kVecPerThread * 16;    // 32 KiB per workgroup iteration
 typedef unsigned int vec16 __attribute__((ext_vector_type(4)));    // one 16-byte global load / store
 }  // namespace
 
@@ -85,13 +83,17 @@ __global__ __launch_bounds__(kWave) void plan_kernel(const int32_t* __restrict__
 // One launch copies `n_tensors` tensors of identical geometry.  Row r of a tensor starts at r*row_stride bytes;
 // of each of its `n_chunks` chunks (chunk_stride bytes apart) the first `copy_bytes` bytes are copied.
 // copy_bytes is a multiple of 16; the last vector of a chunk may be cut at `chunk_limit` bytes (history rows).
-template <bool NT>
+// VPT: 16-byte vectors in flight per thread (a workgroup iteration moves a slab of 256*VPT*16 bytes);
+// NT_LD / NT_ST: non-temporal loads / stores.
+template <int VPT, bool NT_LD, bool NT_ST>
 __global__ __launch_bounds__(kGatherThreads) void gather_kernel(
     void* const* __restrict__ bufA, void* const* __restrict__ bufB, const int32_t* __restrict__ parity, int N,
     int n_tensors, int n_chunks, int64_t row_stride, int64_t chunk_stride, int64_t copy_bytes, int slabs_per_chunk,
     int mask_words, const GatherPlan* __restrict__ plan, const int32_t* __restrict__ grp_src,
     const int32_t* __restrict__ grp_base, const unsigned long long* __restrict__ grp_mask)
 {
+    constexpr int kVecPerThread = VPT;
+    constexpr int kSlabBytes = kGatherThreads * VPT * 16;
     const int n_groups = plan->n_groups;
     const int64_t per_group = (int64_t)n_tensors * n_chunks * slabs_per_chunk;
     const int64_t total = per_group * n_groups;
@@ -118,7 +120,7 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(
         for (int u = 0; u < kVecPerThread; ++u) {
             const int64_t o = ((int64_t)u * kGatherThreads + tid) * 16;
             if (o < left) {
-                if constexpr (NT) v[u] = __builtin_nontemporal_load((const vec16*)(s + o));
+                if constexpr (NT_LD) v[u] = __builtin_nontemporal_load((const vec16*)(s + o));
                 else v[u] = *(const vec16*)(s + o);
             }
         }
@@ -132,7 +134,7 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(
                 for (int u = 0; u < kVecPerThread; ++u) {
                     const int64_t o = ((int64_t)u * kGatherThreads + tid) * 16;
                     if (o < left) {
-                        if constexpr (NT) __builtin_nontemporal_store(v[u], (vec16*)(d + o));
+                        if constexpr (NT_ST) __builtin_nontemporal_store(v[u], (vec16*)(d + o));
                         else *(vec16*)(d + o) = v[u];
                     }
                 }
@@ -160,6 +162,39 @@ __global__ __launch_bounds__(kWave) void commit_kernel(const int32_t* __restrict
     if (lane == 0) parity[b] ^= 1;
 }
 
+template <int VPT, bool NT_LD, bool NT_ST>
+static void launch_gather(smc_ctx* c, void* const* bufA, void* const* bufB, int n_tensors, int n_chunks, int64_t row_stride,
+                          int64_t chunk_stride, int64_t copy_bytes)
+{
+    constexpr int64_t slab = (int64_t)kGatherThreads * VPT * 16;
+    const int slabs = (int)((copy_bytes + slab - 1) / slab);
+    auto& w = c->ws;
+    hipLaunchKernelGGL((gather_kernel<VPT, NT_LD, NT_ST>), dim3(c->gather_grid), dim3(kGatherThreads), 0, c->stream, bufA, bufB,
+                       w.parity, c->cfg.N, n_tensors, n_chunks, row_stride, chunk_stride, copy_bytes, slabs, c->mask_words,
+                       w.plan, w.grp_src, w.grp_base, w.grp_mask);
+}
+
+static void launch_gather_variant(smc_ctx* c, int variant, void* const* bufA, void* const* bufB, int n_tensors, int n_chunks,
+                                  int64_t row_stride, int64_t chunk_stride, int64_t copy_bytes)
+{
+#define PSMC_G(V, L, S) launch_gather<V, L, S>(c, bufA, bufB, n_tensors, n_chunks, row_stride, chunk_stride, copy_bytes)
+    switch (variant) {
+        case 0: PSMC_G(8, true, true); break;
+        case 1: PSMC_G(8, false, true); break;
+        case 2: PSMC_G(8, false, false); break;
+        case 3: PSMC_G(4, true, true); break;
+        case 4: PSMC_G(4, false, true); break;
+        case 5: PSMC_G(4, false, false); break;
+        case 6: PSMC_G(16, true, true); break;
+        case 7: PSMC_G(16, false, true); break;
+        case 8: PSMC_G(16, false, false); break;
+        case 9: PSMC_G(2, true, true); break;
+        case 10: PSMC_G(2, false, false); break;
+        default: PSMC_G(8, true, true); break;
+    }
+#undef PSMC_G
+}
+
 hipError_t launch_reindex(smc_ctx* c, const int32_t* anc, const int32_t* resampled, int valid_len, int t)
 {
     const auto& cfg = c->cfg;
@@ -177,20 +212,16 @@ hipError_t launch_reindex(smc_ctx* c, const int32_t* anc, const int32_t* resampl
         int n_chunks = cfg.kv_H;
         int64_t copy_bytes = (int64_t)valid_len * pos_bytes;
         if (valid_len == cfg.kv_S) { n_chunks = 1; copy_bytes = row_stride; }       // whole row is contiguous
-        const int slabs = (int)((copy_bytes + kSlabBytes - 1) / kSlabBytes);
         ScopedKernelTimer timer(c, 1);
-        hipLaunchKernelGGL((gather_kernel<true>), dim3(c->gather_grid), dim3(kGatherThreads), 0, c->stream,
-                           (void* const*)w.kvA, (void* const*)w.kvB, w.parity, cfg.N, cfg.kv_tensors, n_chunks, row_stride,
-                           head_stride, copy_bytes, slabs, c->mask_words, w.plan, w.grp_src, w.grp_base, w.grp_mask);
+        launch_gather_variant(c, c->gather_variant, (void* const*)w.kvA, (void* const*)w.kvB, cfg.kv_tensors, n_chunks,
+                              row_stride, head_stride, copy_bytes);
     }
     if (have_hist) {
         const int64_t row_stride = (int64_t)cfg.T_max * 4;
         int64_t copy_bytes = (((int64_t)t * 4) + 15) & ~15ll;                       // whole 16-byte vectors
         if (copy_bytes > row_stride) copy_bytes = row_stride;
-        const int slabs = (int)((copy_bytes + kSlabBytes - 1) / kSlabBytes);
-        hipLaunchKernelGGL((gather_kernel<false>), dim3(c->gather_grid), dim3(kGatherThreads), 0, c->stream,
-                           (void* const*)w.histAB, (void* const*)(w.histAB + 1), w.parity, cfg.N, 1, 1, row_stride,
-                           row_stride, copy_bytes, slabs, c->mask_words, w.plan, w.grp_src, w.grp_base, w.grp_mask);
+        launch_gather<4, false, false>(c, (void* const*)w.histAB, (void* const*)(w.histAB + 1), 1, 1, row_stride, row_stride,
+                                       copy_bytes);
     }
     hipLaunchKernelGGL(commit_kernel, dim3(cfg.B), dim3(kWave), 0, c->stream, anc, resampled, cfg.N, w.cumlogp, w.parity,
                        w.plan);

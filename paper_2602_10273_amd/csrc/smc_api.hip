@@ -132,7 +132,9 @@ smc_status smc_init(const smc_config* cfg, void* d_workspace, size_t workspace_b
         delete c;
         return SMC_E_HIP;
     }
-    c->gather_grid = cus * 8;
+    c->gather_grid = cus * 4;             // measured: any of 4..32 persistent workgroups per CU reaches the copy plateau
+    c->gather_variant = 4;                // 4 vectors per thread, plain loads, non-temporal stores
+    c->n_cus = cus;
     if (launch_init_state(c) != hipSuccess) { delete c; return SMC_E_HIP; }
     *out_ctx = c;
     return SMC_OK;
@@ -266,6 +268,15 @@ smc_status smc_get_diag(smc_ctx* ctx, double* h_delta, double* h_logZ1, double* 
         }
         h_counters[3] = (uint64_t)R * (uint64_t)ctx->cfg.V;
     }
+    return SMC_OK;
+}
+
+smc_status smc_set_gather_tuning(smc_ctx* ctx, int32_t wgs_per_cu, int32_t variant)
+{
+    if (!ctx) return SMC_E_NULL;
+    if (wgs_per_cu < 1 || wgs_per_cu > 64 || variant < 0 || variant > 10) return SMC_E_RANGE;
+    ctx->gather_grid = ctx->n_cus * wgs_per_cu;
+    ctx->gather_variant = variant;
     return SMC_OK;
 }
 

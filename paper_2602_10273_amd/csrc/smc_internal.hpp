@@ -72,6 +72,8 @@ struct smc_ctx {
     int kv_bound;
     int hist_bound;
     int gather_grid;              // workgroups of the persistent gather kernel
+    int gather_variant;           // vectors per thread / non-temporal choice of the gather kernel
+    int n_cus;
     // optional per-kernel timing: event pairs recorded around launches of kind 0 (vocab pass) and 1 (KV gather)
     int profiling;
     std::vector<hipEvent_t> ev_pool[2];   // [2*i] start, [2*i+1] stop
