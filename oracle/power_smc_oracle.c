@@ -60,7 +60,7 @@ void orc_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t ou
 
 /* Random word of vocabulary entry v of row r at step t: word (v mod 4) of the block with
  * counter (v div 4, r, t, domain) and key (seed low, seed high).  domain 0 = token draw,
- * 1 = resampling offset (then v = 0 and r is the prompt index). */
+ * 1 = resampling offset, 2 = final output draw (for both v = 0 and r is the prompt index). */
 uint32_t orc_random_word(uint64_t seed, uint32_t t, uint32_t r, uint32_t v, uint32_t domain)
 {
     uint32_t ctr[4] = { v >> 2, r, t, domain };
@@ -141,13 +141,18 @@ void orc_vocab_row(const void* logits, int dtype, int32_t V, double beta, double
     res[5] = best - second;
 }
 
-/* Steps a0..a2 for all R rows: boundary reweight (Sec. 5.3), sample, increment, bookkeeping.
+/* Steps a0..a2 for all R rows: boundary reweight (Sec. 5.3), sample, increment, bookkeeping, and the absorbing
+ * terminated state (Alg. 1 "if done ... else ..."; App. D).
  *   logits [R, row_stride] of dtype; logW, cumlogp [R] in/out; hist [R, T_max] (column t-1 written);
- *   tokens, second [R], gap [R], delta [R] out (second/gap/delta may be NULL). */
+ *   tokens, second [R], gap [R], delta [R] out (second/gap/delta may be NULL).
+ *   eos_id >= 0 with done != NULL: a particle with done[r] != 0 emits eos_id and keeps its weight (increment 1);
+ *   a particle that samples eos_id becomes done.  The stage-boundary reweight acts on every particle, terminated
+ *   or not: it re-targets the whole prefix distribution from exponent alpha_{t-1} to alpha_t (App. B). */
 void orc_step(const void* logits, int dtype, int64_t row_stride, int32_t R, int32_t V,
               double alpha_t, double alpha_prev, double beta, uint64_t seed, int32_t t,
               double* logW, double* cumlogp, int32_t* hist, int32_t T_max,
-              int32_t* tokens, int32_t* second, double* gap, double* delta)
+              int32_t* tokens, int32_t* second, double* gap, double* delta,
+              int32_t eos_id, int32_t* done)
 {
     int esz = dtype == 0 ? 2 : (dtype == 1 ? 4 : 8);
 #pragma omp parallel for schedule(dynamic, 1)
@@ -155,6 +160,14 @@ void orc_step(const void* logits, int dtype, int64_t row_stride, int32_t R, int3
         const void* row = (const char*)logits + (int64_t)r * row_stride * esz;
         int32_t o[2]; double res[6];
         logW[r] += (alpha_t - alpha_prev) * cumlogp[r];           /* stage boundary, prefix y_{1:t-1} */
+        if (done && eos_id >= 0 && done[r]) {                      /* absorbing: y_t = EOS, weight kept */
+            tokens[r] = eos_id;
+            if (hist) hist[(int64_t)r * T_max + (t - 1)] = eos_id;
+            if (second) second[r] = -1;
+            if (gap) gap[r] = INFINITY;
+            if (delta) delta[r] = 0.0;
+            continue;
+        }
         orc_vocab_row(row, dtype, V, beta, alpha_t, seed, t, r, -1, o, res);
         logW[r] += res[4];
         cumlogp[r] += res[2];
@@ -163,6 +176,7 @@ void orc_step(const void* logits, int dtype, int64_t row_stride, int32_t R, int3
         if (second) second[r] = o[1];
         if (gap) gap[r] = res[5];
         if (delta) delta[r] = res[4];
+        if (done && eos_id >= 0 && o[0] == eos_id) done[r] = 1;
     }
 }
 
@@ -234,14 +248,32 @@ void orc_gather_kv(const void* src, void* dst, const int32_t* anc, const int32_t
     }
 }
 
-/* Same gather for the small per-particle state: token history (first t columns), cumulative log p. */
+/* Same gather for the small per-particle state: token history (first t columns), cumulative log p, and the
+ * termination flags (Alg. 1: done^(k) <- done^(A_k); done_src / done_dst may be NULL). */
 void orc_gather_state(const int32_t* hist_src, int32_t* hist_dst, int32_t T_max, int32_t t,
                       const double* cum_src, double* cum_dst,
-                      const int32_t* anc, const int32_t* resampled, int32_t R, int32_t N)
+                      const int32_t* anc, const int32_t* resampled, int32_t R, int32_t N,
+                      const int32_t* done_src, int32_t* done_dst)
 {
     for (int32_t k = 0; k < R; ++k) {
-        if (!resampled[k / N]) { cum_dst[k] = cum_src[k]; continue; }
+        if (!resampled[k / N]) { cum_dst[k] = cum_src[k]; if (done_src) done_dst[k] = done_src[k]; continue; }
         memcpy(hist_dst + (int64_t)k * T_max, hist_src + (int64_t)anc[k] * T_max, (size_t)t * 4);
         cum_dst[k] = cum_src[anc[k]];
+        if (done_src) done_dst[k] = done_src[anc[k]];
+    }
+}
+
+/* Output of Alg. 1: I ~ Categorical(W_T) per prompt, by inversion of the cumulative normalised weights with one
+ * uniform from the Philox stream (domain 2): I = min{ j : sum_{k<=j} W_k >= u }, N-1 if rounding leaves none.
+ * choice[b] is the global row index b*N + I. */
+void orc_final_draw(const double* logW, int32_t B, int32_t N, uint64_t seed, int32_t t, int32_t* choice)
+{
+    for (int32_t b = 0; b < B; ++b) {
+        const double* lw = logW + (int64_t)b * N;
+        double L1 = orc_logsumexp(lw, N, 1.0);
+        double u = orc_uniform(orc_random_word(seed, (uint32_t)t, (uint32_t)b, 0, 2));
+        double c = 0.0; int32_t pick = N - 1;
+        for (int32_t j = 0; j < N; ++j) { c += exp(lw[j] - L1); if (c >= u) { pick = j; break; } }
+        choice[b] = b * N + pick;
     }
 }

@@ -111,6 +111,13 @@ def resample(logW, B, N, kappa, seed, t):
     return anc, flag, e, lw
 
 
+def final_draw(logW, B, N, seed, t):
+    logW = np.ascontiguousarray(logW, np.float64)
+    out = np.empty(B, np.int32)
+    lib().orc_final_draw(_p(logW), C.c_int32(B), C.c_int32(N), C.c_uint64(int(seed)), C.c_int32(t), _p(out))
+    return out
+
+
 def gather_kv(src, anc, resampled, N, valid_len, dst=None):
     """src: [R,H,S,D] array (any 1/2/4/8-byte dtype). Returns dst with resampled prompts' rows gathered."""
     R, H, S, D = src.shape
@@ -126,7 +133,7 @@ def gather_kv(src, anc, resampled, N, valid_len, dst=None):
 class OracleSMC:
     """Algorithm 1 for B independent prompts, state held in fp64 / numpy, one call per step of the path."""
 
-    def __init__(self, B, N, V, T_max, kappa, seed, dtype="f32", kv=None):
+    def __init__(self, B, N, V, T_max, kappa, seed, dtype="f32", kv=None, eos_id=-1):
         self.B, self.N, self.V, self.T_max, self.R = B, N, V, T_max, B * N
         self.kappa, self.seed, self.dtype = float(kappa), int(seed), dtype
         self.logW = np.zeros(self.R, np.float64)          # Alg. 1: W~_0 = 1
@@ -134,6 +141,8 @@ class OracleSMC:
         self.hist = np.zeros((self.R, T_max), np.int32)   # prefixes y_{1:t}
         self.kv = kv                                      # list of [R,H,S,D] arrays or None
         self.log_Zhat = np.zeros(B, np.float64)           # running log of the normalising-constant estimate
+        self.eos_id = int(eos_id)                         # -1: EOS is not special
+        self.done = np.zeros(self.R, np.int32)            # Alg. 1 termination flags
 
     def step(self, logits, t, alpha_t, alpha_prev, tau_t=-1.0, row_stride=None):
         """a0..a2. logits: [R, >=V] array of self.dtype storage. Returns dict of per-row arrays."""
@@ -146,7 +155,7 @@ class OracleSMC:
         lib().orc_step(_p(logits), C.c_int32(_DT[self.dtype]), C.c_int64(stride), C.c_int32(R), C.c_int32(self.V),
                        C.c_double(alpha_t), C.c_double(alpha_prev), C.c_double(beta), C.c_uint64(self.seed),
                        C.c_int32(t), _p(self.logW), _p(self.cumlogp), _p(self.hist), C.c_int32(self.T_max),
-                       _p(tokens), _p(second), _p(gap), _p(delta))
+                       _p(tokens), _p(second), _p(gap), _p(delta), C.c_int32(self.eos_id), _p(self.done))
         return dict(tokens=tokens, second=second, gap=gap, delta=delta)
 
     def ess(self):
@@ -165,14 +174,19 @@ class OracleSMC:
         L1 = np.array([logsumexp(self.logW[b * self.N:(b + 1) * self.N]) for b in range(self.B)])
         return self.log_Zhat + L1 - np.log(self.N)
 
+    def final_draw(self, t):
+        """Output line of Alg. 1: one particle per prompt drawn from the final weights (global row indices)."""
+        return final_draw(self.logW, self.B, self.N, self.seed, t)
+
     def reindex(self, anc, resampled, valid_len, t):
         """a5: prefixes, cumulative log p and every KV tensor gathered by ancestor for resampled prompts."""
         R, N = self.R, self.N
-        hist2 = self.hist.copy(); cum2 = self.cumlogp.copy()
+        hist2 = self.hist.copy(); cum2 = self.cumlogp.copy(); done2 = self.done.copy()
         anc = np.ascontiguousarray(anc, np.int32); resampled = np.ascontiguousarray(resampled, np.int32)
         lib().orc_gather_state(_p(self.hist), _p(hist2), C.c_int32(self.T_max), C.c_int32(t),
-                               _p(self.cumlogp), _p(cum2), _p(anc), _p(resampled), C.c_int32(R), C.c_int32(N))
-        self.hist, self.cumlogp = hist2, cum2
+                               _p(self.cumlogp), _p(cum2), _p(anc), _p(resampled), C.c_int32(R), C.c_int32(N),
+                               _p(self.done), _p(done2))
+        self.hist, self.cumlogp, self.done = hist2, cum2, done2
         if self.kv is not None:
             new = []
             for ten in self.kv:

@@ -21,6 +21,18 @@
 
 namespace psmc {
 
+#ifdef PSMC_TRACE
+// Debug-only phase timestamps (100 MHz wall clock), 8 slots per wave; never compiled into the shipped library.
+__device__ unsigned long long g_trace[1 << 17];
+#define PSMC_STAMP(k) do { if (lane == 0) g_trace[((blockIdx.x * NW + wave) & 16383) * 8 + (k)] = wall_clock64(); } while (0)
+extern "C" int smc_debug_trace(unsigned long long* h_out, size_t n)
+{
+    return (int)hipMemcpyFromSymbol(h_out, HIP_SYMBOL(g_trace), n * sizeof(unsigned long long));
+}
+#else
+#define PSMC_STAMP(k) do { } while (0)
+#endif
+
 namespace {
 
 constexpr float kLog2e = 1.4426950408889634f;
@@ -197,14 +209,14 @@ __global__ __launch_bounds__(NW * kWave) void vocab_pass_kernel(
     constexpr int THREADS = NW * kWave;
     constexpr int kRing = 1024;                        // candidate ring entries per wave (power of two)
     static_assert(kRing >= 2 * EPV * kWave, "a full vector of candidates must fit beside a partly filled ring");
-    __shared__ uint32_t ring_idx[DENSE ? 1 : NW][DENSE ? 1 : kRing];
-    __shared__ float ring_val[DENSE ? 1 : NW][DENSE ? 1 : kRing];
+    __shared__ uint2 ring[DENSE ? 1 : NW][DENSE ? 1 : kRing];     // (vocabulary index, logit bits)
     __shared__ int wg_bound;                           // best "cannot win below this" bound of the whole workgroup
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int split = blockIdx.x % n_split;
     const uint32_t row = blockIdx.x / n_split;
     const char* rowp = (const char*)logits + (int64_t)row * row_stride_bytes;
+    PSMC_STAMP(0);
     if (tid == 0) wg_bound = enc_bound(-INFINITY);
     __syncthreads();
 
@@ -260,8 +272,9 @@ __global__ __launch_bounds__(NW * kWave) void vocab_pass_kernel(
         __builtin_amdgcn_wave_barrier();
         if (lane < n) {
             const int slot = (q_head + lane) & (kRing - 1);
-            const uint32_t idx = ring_idx[DENSE ? 0 : wave][slot];
-            const float xv = ring_val[DENSE ? 0 : wave][slot];
+            const uint2 ent = ring[DENSE ? 0 : wave][slot];
+            const uint32_t idx = ent.x;
+            const float xv = __uint_as_float(ent.y);
             if (xv >= thr) {
                 const U4 blk = philox4x32_10(idx >> 2, row, step, 0u, key0, key1);
                 top.offer(beta, xv, gumbel_f32(pick_word(blk, idx & 3u)), (int32_t)idx);
@@ -284,15 +297,13 @@ __global__ __launch_bounds__(NW * kWave) void vocab_pass_kernel(
         for (int base = 0; base < q_count; base += kWave) {
             const int src = (q_head + base + lane) & (kRing - 1);
             const bool in = base + lane < q_count;
-            const uint32_t idx = in ? ring_idx[DENSE ? 0 : wave][src] : 0u;
-            const float xv = in ? ring_val[DENSE ? 0 : wave][src] : 0.f;
-            const bool keep = in && xv >= thr;
+            const uint2 ent = in ? ring[DENSE ? 0 : wave][src] : make_uint2(0u, 0u);
+            const bool keep = in && __uint_as_float(ent.y) >= thr;
             const unsigned long long mk = __ballot(keep);
             __builtin_amdgcn_wave_barrier();            // all lanes have read this chunk before any lane overwrites it
             if (keep) {
                 const int dst = (q_head + kept + mask_rank(mk)) & (kRing - 1);
-                ring_idx[DENSE ? 0 : wave][dst] = idx;
-                ring_val[DENSE ? 0 : wave][dst] = xv;
+                ring[DENSE ? 0 : wave][dst] = ent;
             }
             kept += __popcll(mk);
         }
@@ -322,22 +333,22 @@ __global__ __launch_bounds__(NW * kWave) void vocab_pass_kernel(
                 compact();
                 while (q_count > kRing - EPV * kWave) drain(min(q_count, kWave));
             }
-            // The row's shared bound can lift thr above this wave's own maximum, so the gate into the slow path is
-            // min(thr, m): it must also catch every entry that raises m (the sums below need x <= m).
+            // the running maximum first (the sums below need x <= m); thr may sit above m when another wave of the
+            // workgroup has seen a larger logit
+            float vm = x[0];
+#pragma unroll
+            for (int j = 1; j < EPV; ++j) vm = fmaxf(vm, x[j]);
+            if (__ballot(vm > m)) raise_max(wave_max_f32(vm));
 #pragma unroll
             for (int j = 0; j < EPV; ++j) {
-                const bool hit = x[j] >= fminf(thr, m);
+                const bool hit = x[j] >= thr;
                 const unsigned long long mk = __ballot(hit);
                 if (mk) {                                                   // wave-uniform
-                    if (__ballot(x[j] > m)) raise_max(wave_max_f32(x[j]));
-                    const bool keep = x[j] >= thr;                          // against the possibly raised threshold
-                    const unsigned long long mk2 = __ballot(keep);
-                    if (keep) {
-                        const int slot = (q_head + q_count + mask_rank(mk2)) & (kRing - 1);
-                        ring_idx[wave][slot] = (uint32_t)(v0 + j);
-                        ring_val[wave][slot] = x[j];
+                    if (hit) {
+                        const int slot = (q_head + q_count + mask_rank(mk)) & (kRing - 1);
+                        ring[wave][slot] = make_uint2((uint32_t)(v0 + j), __float_as_uint(x[j]));
                     }
-                    q_count += __popcll(mk2);
+                    q_count += __popcll(mk);
                 }
             }
         }
@@ -352,52 +363,83 @@ __global__ __launch_bounds__(NW * kWave) void vocab_pass_kernel(
         }
     };
 
-    auto load_vec = [&](int vi, float (&x)[EPV]) {
-        const int v0 = vi * EPV;
-        if (vi < nvec_full) {
-            const uint4 raw = *(const uint4*)(rowp + (int64_t)vi * 16);
-            unpack<DT>(raw, x);
+    // The main stream covers the vectors that lie wholly inside the row; the ragged last vector of a row (V not a
+    // multiple of the vector width) is handled after it.  Loads are unconditional (clamped address + select) so that
+    // the loop has no divergent branch around a load and the next batch really stays in flight.
+    constexpr uint32_t kPadWord = DT == SMC_BF16 ? 0xFF80FF80u : 0xFF800000u;      // -inf in every element
+    const int full_end = min(vec_end, nvec_full);
+    constexpr int kBatch = THREADS * UNROLL;
+    // A batch that lies wholly inside the slice is loaded without any guard; only the last, partial batch pays for
+    // clamped addresses and selects (which consume the loaded words at once and so cannot stay in flight).
+    auto load_batch = [&](uint4 (&dst)[UNROLL], int b0) {
+        if (b0 + kBatch <= full_end) {                                     // uniform
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) dst[u] = *(const uint4*)(rowp + (int64_t)(b0 + u * THREADS + tid) * 16);
         } else {
 #pragma unroll
-            for (int j = 0; j < EPV; ++j)
-                x[j] = (vi < nvec && v0 + j < V) ? load_scalar<DT>(rowp, v0 + j) : -INFINITY;
+            for (int u = 0; u < UNROLL; ++u) {
+                const int vi = b0 + u * THREADS + tid;
+                const int vc = min(vi, full_end - 1);
+                uint4 r = *(const uint4*)(rowp + (int64_t)vc * 16);
+                const bool pad = vi >= full_end;
+                r.x = pad ? kPadWord : r.x; r.y = pad ? kPadWord : r.y;
+                r.z = pad ? kPadWord : r.z; r.w = pad ? kPadWord : r.w;
+                dst[u] = r;
+            }
         }
     };
 
-    // main stream: UNROLL vectors per thread in flight
+    // while one batch of UNROLL vectors per thread is processed the next is already in flight
+    uint4 cur[UNROLL], nxt[UNROLL];
+    if (vec_begin < full_end) load_batch(cur, vec_begin);
     bool first = true;
-    for (int base = vec_begin; base < vec_end; base += THREADS * UNROLL) {
-        float x[UNROLL][EPV];
-#pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
-            const int vi = base + u * THREADS + tid;
-            if (vi < vec_end) load_vec(vi, x[u]);
-            else {
-#pragma unroll
-                for (int j = 0; j < EPV; ++j) x[u][j] = -INFINITY;
-            }
-        }
-        if (first) {                 // warm start: the max of the first vectors gives a useful threshold at once
+    for (int base = vec_begin; base < full_end; base += kBatch) {
+        if (base + kBatch < full_end) load_batch(nxt, base + kBatch);
+        if (first) {                 // warm start: the max of the workgroup's first batch gives a useful threshold
             first = false;
             float vm = -INFINITY;
 #pragma unroll
-            for (int u = 0; u < UNROLL; ++u)
+            for (int u = 0; u < UNROLL; ++u) {
+                float x[EPV];
+                unpack<DT>(cur[u], x);
 #pragma unroll
-                for (int j = 0; j < EPV; ++j) vm = fmaxf(vm, x[u][j]);
+                for (int j = 0; j < EPV; ++j) vm = fmaxf(vm, x[j]);
+            }
             vm = wave_max_f32(vm);
             if (vm > m) raise_max(vm);
-            if constexpr (!DENSE) { publish(); adopt(); }
+            if constexpr (!DENSE) {
+                publish();
+                __syncthreads();     // reached by every wave: the loop bounds are the same for the whole workgroup
+                adopt();
+            }
+            PSMC_STAMP(1);
         }
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
-            if (base + u * THREADS + (wave << 6) < vec_end)                // wave-uniform: wave has data
-                process(x[u], (base + u * THREADS + tid) * EPV);
+            if (base + u * THREADS + (wave << 6) < full_end) {             // wave-uniform: wave has data
+                float x[EPV];
+                unpack<DT>(cur[u], x);
+                process(x, (base + u * THREADS + tid) * EPV);
+            }
         }
         if constexpr (!DENSE) { publish(); adopt(); }
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) cur[u] = nxt[u];
     }
+    if (nvec > nvec_full && vec_end == nvec && wave == 0) {                // the ragged tail: lane 0 of wave 0
+        float x[EPV];
+#pragma unroll
+        for (int j = 0; j < EPV; ++j) {
+            const int v = nvec_full * EPV + j;
+            x[j] = (lane == 0 && v < V) ? load_scalar<DT>(rowp, v) : -INFINITY;
+        }
+        process(x, nvec_full * EPV);
+    }
+    PSMC_STAMP(2);
     if constexpr (!DENSE) {
         // every wave has streamed its share: the workgroup's bound now reflects the maximum of the whole slice
         __syncthreads();
+        PSMC_STAMP(3);
         adopt();
         while (q_count > 0) {
             compact();
@@ -405,7 +447,9 @@ __global__ __launch_bounds__(NW * kWave) void vocab_pass_kernel(
         }
     }
 
+    PSMC_STAMP(4);
     block_epilogue<NW>(beta, m, M1, Mb, s1, sb, top, n_scored, n_drains, partials + (int64_t)row * kMaxSplit + split);
+    PSMC_STAMP(5);
 }
 
 // ------------------------------------------------------------------------------------------------

@@ -1,0 +1,126 @@
+"""Pins for the oracle's absorbing terminated state (Alg. 1 "if done"; App. D) and final output draw (Alg. 1 "Output")."""
+import numpy as np
+import pytest
+from scipy import stats
+
+from oracle import reference as orc
+from oracle.enumerate import enumerate_power_target
+from paper_2602_10273_amd import synth
+
+W1 = synth.WORKLOADS["cfg1"]
+TABLE = synth.bigram_table(W1.V, W1.sigma, seed=0)
+EOS = 3
+
+
+def run_bigram_eos(B, N, T, alphas, seed, kappa=0.5):
+    w = synth.scaled(W1, B=B, N=N)
+    o = orc.OracleSMC(B, N, w.V, T, kappa, seed, "f32", eos_id=EOS)
+    trace = []
+    for t in range(1, T + 1):
+        prev = np.zeros(w.R, np.int64) if t == 1 else o.hist[:, t - 2]
+        x = synth.logits_numpy(w, t, 0, prev_tokens=prev, table=TABLE)
+        before = (o.logW.copy(), o.cumlogp.copy(), o.done.copy())
+        out = o.step(x, t, alphas[t], alphas[t - 1])
+        trace.append((before, out, o.logW.copy(), o.cumlogp.copy(), o.done.copy()))
+        anc, flag, _ = o.resample(t)
+        o.reindex(anc, flag, 0, t)
+    return o, trace
+
+
+def test_terminated_particles_are_absorbing():
+    T = 6
+    o, trace = run_bigram_eos(50, 4, T, [4.0] * (T + 1), seed=3, kappa=0.0)      # no resampling: follow each row
+    ever_done = np.zeros(o.R, bool)
+    for (lw0, cum0, done0), out, lw1, cum1, done1 in trace:
+        d = done0.astype(bool)
+        assert np.all(out["tokens"][d] == EOS)                         # forced EOS
+        assert np.all(out["delta"][d] == 0.0) and np.array_equal(lw1[d], lw0[d])   # increment 1
+        assert np.array_equal(cum1[d], cum0[d])
+        newly = (~d) & (out["tokens"] == EOS)
+        assert np.array_equal(done1.astype(bool), d | newly)           # EOS sets the flag; it never clears
+        ever_done |= done1.astype(bool)
+    assert ever_done.sum() > 10 and (~ever_done).sum() > 10
+    first = np.argmax(o.hist == EOS, axis=1)
+    for r in np.nonzero(ever_done)[0]:
+        assert np.all(o.hist[r, first[r]:] == EOS)
+
+
+def test_boundary_reweight_reaches_terminated_particles():
+    T = 4
+    alphas = [1.0, 2.0, 3.0, 4.0, 4.0]
+    o, trace = run_bigram_eos(200, 4, T, alphas, seed=5, kappa=0.0)
+    seen = 0
+    for t, ((lw0, cum0, done0), out, lw1, cum1, done1) in enumerate(trace, start=1):
+        d = done0.astype(bool)
+        if d.any():
+            assert np.allclose(lw1[d] - lw0[d], (alphas[t] - alphas[t - 1]) * cum0[d], atol=1e-12)
+            seen += int(d.sum())
+    assert seen > 20
+
+
+def test_done_flags_follow_their_particle_on_resampling():
+    o = orc.OracleSMC(2, 4, 8, 8, 0.5, 1, "f32", eos_id=EOS)
+    o.done[:] = [1, 0, 0, 1, 0, 1, 0, 0]
+    anc = np.array([3, 3, 1, 0, 4, 5, 6, 7], np.int32)
+    o.reindex(anc, np.array([1, 0], np.int32), 0, 1)
+    assert list(o.done) == [1, 1, 0, 1, 0, 1, 0, 0]
+
+
+def test_final_draw_inverts_the_cumulative_weights():
+    N = 5
+    w = np.array([0.1, 0.4, 0.05, 0.25, 0.2])
+    B = 40000
+    logW = np.tile(np.log(w) + 7.0, B)                 # scale-free
+    pick = orc.final_draw(logW, B, N, seed=11, t=9) - np.arange(B) * N
+    counts = np.bincount(pick, minlength=N)
+    chi2 = ((counts - B * w) ** 2 / (B * w)).sum()
+    assert chi2 < stats.chi2.ppf(1 - 1e-5, N - 1)
+    C = np.cumsum(w)
+    for b in range(50):                                # the literal rule with the stream's own uniform
+        u = orc.uniform(orc.random_word(11, 9, b, 0, 2))
+        assert pick[b] == int(np.argmax(C >= u))
+    onehot = np.full(N, -np.inf); onehot[2] = 0.0
+    assert np.all(orc.final_draw(np.tile(onehot, 10), 10, N, 1, 1) - np.arange(10) * N == 2)
+    assert list(orc.final_draw(np.zeros(3), 3, 1, 1, 1)) == [0, 1, 2]
+
+
+@pytest.fixture(scope="module")
+def exact_eos():
+    return enumerate_power_target(TABLE, W1.steps, W1.alpha, eos_id=EOS)
+
+
+def test_enumeration_with_eos(exact_eos):
+    seqs, log_pi, log_Z = exact_eos
+    pi = np.exp(log_pi)
+    assert abs(pi.sum() - 1) < 1e-12
+    bad = np.array([np.any(s[np.argmax(s == EOS):] != EOS) if EOS in s else False for s in seqs[::97]])
+    assert np.all(pi[::97][bad] == 0.0)                # nothing but EOS after EOS
+    _, lp1, lz1 = enumerate_power_target(TABLE, 4, 1.0, eos_id=EOS)
+    assert abs(lz1) < 1e-12                            # alpha = 1: the base model is normalised over padded sequences
+
+
+@pytest.mark.parametrize("schedule", ["constant", "ramp"])
+def test_normalising_constant_unbiased_with_eos(exact_eos, schedule):
+    _, _, log_Z = exact_eos
+    T, a = W1.steps, W1.alpha
+    alphas = [a] * (T + 1) if schedule == "constant" else [1.0, 2.0, 3.0, 4.0, 4.0, 4.0, 4.0]
+    B = 20000
+    o, _ = run_bigram_eos(B, W1.N, T, alphas, seed=23)
+    z = np.exp(o.log_Z_estimate() - log_Z)
+    se = z.std(ddof=1) / np.sqrt(B)
+    assert abs(z.mean() - 1.0) < 4 * se and se < 0.05
+    assert o.done.mean() > 0.05
+
+
+def test_final_draw_returns_the_power_target(exact_eos):
+    seqs, log_pi, _ = exact_eos
+    T = W1.steps
+    B, N = 3000, 128
+    o, _ = run_bigram_eos(B, N, T, [W1.alpha] * (T + 1), seed=31)
+    pick = o.final_draw(T)
+    chosen = o.hist[pick, :T]
+    top = np.argsort(-log_pi)[:4]
+    for s in top:
+        p = np.exp(log_pi[s])
+        freq = np.mean(np.all(chosen == seqs[s][None, :], axis=1))
+        assert abs(freq - p) < 4 * np.sqrt(p * (1 - p) / B) + 0.03 * p      # N = 128: small finite-N bias allowed
