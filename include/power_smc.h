@@ -6,6 +6,7 @@
  *
  *   a0  stage-boundary reweight of exponent bridging (Sec. 5.3, App. B)
  *   a1  draw y ~ q_t = softmax(l / tau_t)                     (Alg. 1 "sample"; Cor. 1)
+ *       (a terminated particle emits EOS and keeps its weight: Alg. 1 "if done", App. D)
  *   a2  log W~ += alpha_t log p(y) - log q_t(y)               (Eq. "inc"; Alg. 1 "update")
  *   a3  W = W~ / sum W~ ,  ESS = 1 / sum W^2   per prompt      (Eq. "ess")
  *   a4  if ESS < kappa N: systematic resampling -> ancestors  (Alg. 1; Sec. 7 implementation details)
@@ -59,7 +60,7 @@ typedef struct {
     int32_t V;             /* vocabulary size                          >= 1 */
     int32_t T_max;         /* capacity of the token history (Alg. 1 input T_max); multiple of 4 */
     int32_t logits_dtype;  /* smc_dtype */
-    int32_t reserved0;
+    int32_t eos_id;        /* end-of-sequence token (absorbing state, App. D); -1: no token terminates a particle */
     double  kappa;         /* resample iff ESS < kappa*N (strict), 0 <= kappa <= 1 (kappa = 0: never) */
     uint64_t seed;         /* Philox key */
     /* KV cache geometry: kv_tensors tensors (2 per layer), each [R, kv_H, kv_S, kv_D] of kv_elem_bytes;
@@ -93,7 +94,9 @@ smc_status smc_kv_bind(smc_ctx* ctx, void* const* h_bufA, void* const* h_bufB, i
  *   alpha_t, alpha_prev: exponents of this and the previous token (equal when not bridging; >= 0).
  *   tau_t: proposal temperature; tau_t <= 0 selects the locally optimal tau = 1/alpha_t of Thm 1 exactly.
  *   d_tokens_out: int32 [R], the sampled tokens y_t.
- * Updates log W~, cumulative log p and column t-1 of the live history in the workspace. */
+ * Updates log W~, cumulative log p and column t-1 of the live history in the workspace.  With eos_id >= 0 a
+ * terminated particle's row is not read at all: it emits eos_id, its increment is 1, and only the stage-boundary
+ * reweight touches its weight; a particle that draws eos_id becomes terminated. */
 smc_status smc_step(smc_ctx* ctx, const void* d_logits, int64_t row_stride_elems, int32_t t, double alpha_t,
                     double alpha_prev, double tau_t, int32_t* d_tokens_out);
 
@@ -107,7 +110,8 @@ smc_status smc_resample(smc_ctx* ctx, int32_t t, int32_t* d_anc_out, int32_t* d_
 
 /* a5: for every prompt b with d_resampled[b] != 0 and every row k of it, copies row d_anc[k] of the live
  * buffer into row k of the other buffer -- the first valid_len (0..kv_S) positions of every head of every KV
- * tensor, the first t columns of the history -- gathers cumulative log p the same way, then flips parity[b].
+ * tensor, the first t columns of the history -- gathers cumulative log p and the termination flags the same way,
+ * then flips parity[b].
  * d_anc entries of a resampled prompt must lie inside that prompt's row range.  Each distinct ancestor row is
  * read once and written to all of its descendants. */
 smc_status smc_kv_reindex(smc_ctx* ctx, const int32_t* d_anc, const int32_t* d_resampled, int32_t valid_len,
@@ -118,6 +122,15 @@ smc_status smc_kv_reindex(smc_ctx* ctx, const int32_t* d_anc, const int32_t* d_r
 smc_status smc_ess_from(smc_ctx* ctx, const double* d_logW, double* d_ess_out, double* d_lognormw_out);
 smc_status smc_resample_from(smc_ctx* ctx, double* d_logW_inout, int32_t t, int32_t* d_anc_out,
                              int32_t* d_resampled_out, double* d_ess_out);
+
+/* Output of Alg. 1: one particle per prompt, I ~ Categorical(W_t), by inversion of the cumulative normalised
+ * weights (particle order) with one uniform of the Philox stream (domain 2, row := prompt, v := 0):
+ * I = min{ j : sum_{k<=j} W_k >= u }.  d_choice_out int32 [B] receives the global row index b*N + I. */
+smc_status smc_final_draw(smc_ctx* ctx, int32_t t, int32_t* d_choice_out);
+
+/* Synchronous access to the termination flags (host int32 [R]; only meaningful with eos_id >= 0). */
+smc_status smc_get_done(smc_ctx* ctx, int32_t* h_done);
+smc_status smc_set_done(smc_ctx* ctx, const int32_t* h_done);
 
 /* Synchronous inspection / teacher forcing (host arrays; any may be NULL to skip):
  * h_logW, h_cumlogp double [R]; h_parity int32 [B]. */

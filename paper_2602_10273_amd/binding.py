@@ -15,13 +15,13 @@ STATUS = {0: "SMC_OK", 1: "SMC_E_NULL", 2: "SMC_E_SHAPE", 3: "SMC_E_DTYPE", 4: "
           6: "SMC_E_STATE", 7: "SMC_E_HIP"}
 
 EXPORTS = ["smc_workspace_bytes", "smc_init", "smc_destroy", "smc_kv_bind", "smc_step", "smc_ess", "smc_resample",
-           "smc_kv_reindex", "smc_ess_from", "smc_resample_from", "smc_get_state", "smc_set_state", "smc_get_diag",
+           "smc_kv_reindex", "smc_final_draw", "smc_get_done", "smc_set_done", "smc_ess_from", "smc_resample_from", "smc_get_state", "smc_set_state", "smc_get_diag",
            "smc_set_tuning", "smc_set_gather_tuning", "smc_profile_enable", "smc_profile_read", "smc_status_str"]
 
 
 class smc_config(C.Structure):
     _fields_ = [("B", C.c_int32), ("N", C.c_int32), ("V", C.c_int32), ("T_max", C.c_int32),
-                ("logits_dtype", C.c_int32), ("reserved0", C.c_int32), ("kappa", C.c_double), ("seed", C.c_uint64),
+                ("logits_dtype", C.c_int32), ("eos_id", C.c_int32), ("kappa", C.c_double), ("seed", C.c_uint64),
                 ("kv_tensors", C.c_int32), ("kv_H", C.c_int32), ("kv_S", C.c_int32), ("kv_D", C.c_int32),
                 ("kv_elem_bytes", C.c_int32), ("reserved1", C.c_int32)]
 
@@ -52,6 +52,9 @@ def lib():
         L.smc_ess.argtypes = [vp, vp, vp]
         L.smc_resample.argtypes = [vp, i32, vp, vp, vp]
         L.smc_kv_reindex.argtypes = [vp, vp, vp, i32, i32]
+        L.smc_final_draw.argtypes = [vp, i32, vp]
+        L.smc_get_done.argtypes = [vp, vp]
+        L.smc_set_done.argtypes = [vp, vp]
         L.smc_ess_from.argtypes = [vp, vp, vp, vp]
         L.smc_resample_from.argtypes = [vp, vp, i32, vp, vp, vp]
         L.smc_get_state.argtypes = [vp, vp, vp, vp]
@@ -86,9 +89,10 @@ def _check(fn, st):
         raise SMCError(fn, st)
 
 
-def make_config(B, N, V, T_max, logits_dtype, kappa, seed, kv_tensors=0, kv_H=0, kv_S=0, kv_D=0, kv_elem_bytes=2):
+def make_config(B, N, V, T_max, logits_dtype, kappa, seed, kv_tensors=0, kv_H=0, kv_S=0, kv_D=0, kv_elem_bytes=2,
+                eos_id=-1):
     dt = {"bf16": SMC_BF16, "f32": SMC_F32}.get(logits_dtype, logits_dtype)
-    return smc_config(B, N, V, T_max, dt, 0, float(kappa), int(seed) & 0xFFFFFFFFFFFFFFFF, kv_tensors, kv_H, kv_S,
+    return smc_config(B, N, V, T_max, dt, int(eos_id), float(kappa), int(seed) & 0xFFFFFFFFFFFFFFFF, kv_tensors, kv_H, kv_S,
                       kv_D, kv_elem_bytes, 0)
 
 
@@ -129,6 +133,18 @@ def smc_resample(ctx, t, d_anc_out, d_resampled_out, d_ess_out=None):
 
 def smc_kv_reindex(ctx, d_anc, d_resampled, valid_len, t):
     _check("smc_kv_reindex", lib().smc_kv_reindex(ctx, _ptr(d_anc), _ptr(d_resampled), valid_len, t))
+
+
+def smc_final_draw(ctx, t, d_choice_out):
+    _check("smc_final_draw", lib().smc_final_draw(ctx, t, _ptr(d_choice_out)))
+
+
+def smc_get_done(ctx, h_done):
+    _check("smc_get_done", lib().smc_get_done(ctx, _ptr(h_done)))
+
+
+def smc_set_done(ctx, h_done):
+    _check("smc_set_done", lib().smc_set_done(ctx, _ptr(h_done)))
 
 
 def smc_ess_from(ctx, d_logW, d_ess_out, d_lognormw_out=None):

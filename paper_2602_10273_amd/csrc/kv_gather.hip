@@ -8,7 +8,7 @@
 //
 //   plan_kernel    : one wave per prompt, builds the groups (ancestor row, bit set of descendants).
 //   gather_kernel  : persistent grid-stride loop over (group, tensor, head chunk, slab of 8..64 KiB).
-//   commit_kernel  : cumulative log p gathered the same way, parity flipped, plan cleared for the next call.
+//   commit_kernel  : cumulative log p and termination flags gathered the same way, parity flipped, plan cleared.
 #include "device_rng.hpp"
 #include "smc_internal.hpp"
 
@@ -145,19 +145,20 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(
 
 // After the gathers: cumulative log p follows its particle, parity flips, the plan is cleared.
 __global__ __launch_bounds__(kWave) void commit_kernel(const int32_t* __restrict__ anc, const int32_t* __restrict__ resampled,
-                                                       int N, double* __restrict__ cumlogp, int32_t* __restrict__ parity,
-                                                       GatherPlan* __restrict__ plan)
+                                                       int N, double* __restrict__ cumlogp, int32_t* __restrict__ done,
+                                                       int32_t* __restrict__ parity, GatherPlan* __restrict__ plan)
 {
     __shared__ double sh[SMC_MAX_PARTICLES];
+    __shared__ int32_t sh_done[SMC_MAX_PARTICLES];
     const int b = blockIdx.x, lane = threadIdx.x;
     if (b == 0 && lane == 0) plan->n_groups = 0;
     if (!resampled[b]) return;
     const int row0 = b * N;
-    for (int k = lane; k < N; k += kWave) sh[k] = cumlogp[row0 + k];
+    for (int k = lane; k < N; k += kWave) { sh[k] = cumlogp[row0 + k]; sh_done[k] = done[row0 + k]; }
     __syncthreads();
     for (int k = lane; k < N; k += kWave) {
         const int a = anc[row0 + k] - row0;
-        if (a >= 0 && a < N) cumlogp[row0 + k] = sh[a];
+        if (a >= 0 && a < N) { cumlogp[row0 + k] = sh[a]; done[row0 + k] = sh_done[a]; }
     }
     if (lane == 0) parity[b] ^= 1;
 }
@@ -223,7 +224,7 @@ hipError_t launch_reindex(smc_ctx* c, const int32_t* anc, const int32_t* resampl
         launch_gather<4, false, false>(c, (void* const*)w.histAB, (void* const*)(w.histAB + 1), 1, 1, row_stride, row_stride,
                                        copy_bytes);
     }
-    hipLaunchKernelGGL(commit_kernel, dim3(cfg.B), dim3(kWave), 0, c->stream, anc, resampled, cfg.N, w.cumlogp, w.parity,
+    hipLaunchKernelGGL(commit_kernel, dim3(cfg.B), dim3(kWave), 0, c->stream, anc, resampled, cfg.N, w.cumlogp, w.done, w.parity,
                        w.plan);
     return hipGetLastError();
 }

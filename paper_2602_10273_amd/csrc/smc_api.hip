@@ -22,6 +22,7 @@ smc_status check_config(const smc_config* c)
     if (c->T_max % 4 != 0) return SMC_E_ALIGN;
     if (c->logits_dtype != SMC_BF16 && c->logits_dtype != SMC_F32) return SMC_E_DTYPE;
     if (!(c->kappa >= 0.0 && c->kappa <= 1.0)) return SMC_E_RANGE;
+    if (c->eos_id < -1 || c->eos_id >= c->V) return SMC_E_RANGE;
     if (c->kv_tensors < 0 || c->kv_tensors > SMC_MAX_KV_TENSORS) return SMC_E_SHAPE;
     if (c->kv_tensors > 0) {
         if (c->kv_H < 1 || c->kv_S < 1 || c->kv_D < 1) return SMC_E_SHAPE;
@@ -42,6 +43,7 @@ size_t layout(const smc_config* c, char* base, Workspace* w)
     p = take(R * 8); if (w) w->logW = (double*)p;
     p = take(R * 8); if (w) w->cumlogp = (double*)p;
     p = take((size_t)c->B * 4); if (w) w->parity = (int32_t*)p;
+    p = take(R * 4); if (w) w->done = (int32_t*)p;
     p = take(R * kMaxSplit * sizeof(Partial)); if (w) w->partials = (Partial*)p;
     p = take(R * 8); if (w) w->d_delta = (double*)p;
     p = take(R * 8); if (w) w->d_logZ1 = (double*)p;
@@ -224,6 +226,27 @@ smc_status smc_kv_reindex(smc_ctx* ctx, const int32_t* d_anc, const int32_t* d_r
     if (valid_len < 0 || (ctx->cfg.kv_tensors > 0 && valid_len > ctx->cfg.kv_S)) return SMC_E_RANGE;
     if (ctx->cfg.kv_tensors > 0 && valid_len > 0 && !ctx->kv_bound) return SMC_E_STATE;
     return launch_reindex(ctx, d_anc, d_resampled, valid_len, t) == hipSuccess ? SMC_OK : SMC_E_HIP;
+}
+
+smc_status smc_final_draw(smc_ctx* ctx, int32_t t, int32_t* d_choice_out)
+{
+    if (!ctx || !d_choice_out) return SMC_E_NULL;
+    if (t < 1) return SMC_E_RANGE;
+    return launch_final_draw(ctx, t, d_choice_out) == hipSuccess ? SMC_OK : SMC_E_HIP;
+}
+
+smc_status smc_get_done(smc_ctx* ctx, int32_t* h_done)
+{
+    if (!ctx || !h_done) return SMC_E_NULL;
+    if (hipStreamSynchronize(ctx->stream) != hipSuccess) return SMC_E_HIP;
+    return hipMemcpy(h_done, ctx->ws.done, (size_t)ctx->R * 4, hipMemcpyDeviceToHost) == hipSuccess ? SMC_OK : SMC_E_HIP;
+}
+
+smc_status smc_set_done(smc_ctx* ctx, const int32_t* h_done)
+{
+    if (!ctx || !h_done) return SMC_E_NULL;
+    if (hipStreamSynchronize(ctx->stream) != hipSuccess) return SMC_E_HIP;
+    return hipMemcpy(ctx->ws.done, h_done, (size_t)ctx->R * 4, hipMemcpyHostToDevice) == hipSuccess ? SMC_OK : SMC_E_HIP;
 }
 
 smc_status smc_get_state(smc_ctx* ctx, double* h_logW, double* h_cumlogp, int32_t* h_parity)

@@ -42,6 +42,7 @@ struct Workspace {                // device pointers carved out of the caller's 
     double* logW;                 // [R]
     double* cumlogp;              // [R]
     int32_t* parity;              // [B]
+    int32_t* done;                // [R] termination flags (Alg. 1)
     Partial* partials;            // [R * kMaxSplit]
     double* d_delta;              // [R] diagnostics of the last step
     double* d_logZ1;              // [R]
@@ -108,5 +109,6 @@ hipError_t launch_vocab_pass(smc_ctx* c, const void* logits, int64_t row_stride,
 hipError_t launch_ess(smc_ctx* c, const double* logW, double* ess_out, double* lognormw_out);
 hipError_t launch_resample(smc_ctx* c, double* logW, int t, int32_t* anc, int32_t* resampled, double* ess_out);
 hipError_t launch_reindex(smc_ctx* c, const int32_t* anc, const int32_t* resampled, int valid_len, int t);
+hipError_t launch_final_draw(smc_ctx* c, int t, int32_t* choice);
 
 }  // namespace psmc

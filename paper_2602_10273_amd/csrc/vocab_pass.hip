@@ -202,7 +202,7 @@ __device__ __forceinline__ float dec_bound(int i) { return __int_as_float(i >= 0
 template <int DT, int P, bool DENSE, int NW>
 __global__ __launch_bounds__(NW * kWave) void vocab_pass_kernel(
     const void* __restrict__ logits, int64_t row_stride_bytes, int V, float beta, uint32_t key0, uint32_t key1,
-    uint32_t step, int n_split, int vecs_per_split, Partial* __restrict__ partials)
+    uint32_t step, int n_split, int vecs_per_split, Partial* __restrict__ partials, const int32_t* __restrict__ done)
 {
     constexpr int EPV = Elems<DT>::kPerVec;
     constexpr int UNROLL = 4;
@@ -216,6 +216,7 @@ __global__ __launch_bounds__(NW * kWave) void vocab_pass_kernel(
     const int split = blockIdx.x % n_split;
     const uint32_t row = blockIdx.x / n_split;
     const char* rowp = (const char*)logits + (int64_t)row * row_stride_bytes;
+    if (done && done[row]) return;                     // terminated particle (App. D): its logits are not read
     PSMC_STAMP(0);
     if (tid == 0) wg_bound = enc_bound(-INFINITY);
     __syncthreads();
@@ -463,10 +464,23 @@ __global__ __launch_bounds__(kWave) void finalize_rows_kernel(
     double* __restrict__ logW, double* __restrict__ cumlogp, const int32_t* __restrict__ parity,
     int32_t* const* __restrict__ histAB, int T_max, int32_t* __restrict__ tokens_out, double* __restrict__ d_delta,
     double* __restrict__ d_logZ1, double* __restrict__ d_logZb, double* __restrict__ d_gap,
-    int32_t* __restrict__ d_second, int32_t* __restrict__ d_rowstat)
+    int32_t* __restrict__ d_second, int32_t* __restrict__ d_rowstat, int eos_id, int32_t* __restrict__ done)
 {
     const int lane = threadIdx.x;
     const uint32_t row = blockIdx.x;
+    if (eos_id >= 0 && done[row]) {                    // absorbing state (Alg. 1 "if done"; App. D): y_t = EOS, increment 1;
+        if (lane == 0) {                               // the stage-boundary reweight still re-targets its prefix (App. B)
+            logW[row] += (alpha_t - alpha_prev) * cumlogp[row];
+            tokens_out[row] = eos_id;
+            if (histAB) {
+                int32_t* h = histAB[parity[row / N]];
+                if (h) h[(int64_t)row * T_max + (step - 1)] = eos_id;
+            }
+            d_delta[row] = 0.0; d_logZ1[row] = 0.0; d_logZb[row] = 0.0; d_gap[row] = INFINITY; d_second[row] = -1;
+            d_rowstat[3 * row] = 0; d_rowstat[3 * row + 1] = 0; d_rowstat[3 * row + 2] = 0;
+        }
+        return;
+    }
     const char* rowp = (const char*)logits + (int64_t)row * row_stride_bytes;
     const Partial* pp = partials + (int64_t)row * kMaxSplit;
 
@@ -529,6 +543,7 @@ __global__ __launch_bounds__(kWave) void finalize_rows_kernel(
         d_gap[row] = k1 - k2;
         d_second[row] = cand2 == 0x7FFFFFFF ? -1 : cand2;
         d_rowstat[3 * row] = ok ? 0 : 1; d_rowstat[3 * row + 1] = nsc; d_rowstat[3 * row + 2] = ndr;
+        if (eos_id >= 0 && ok && tok == eos_id) done[row] = 1;
     }
 }
 
@@ -541,10 +556,11 @@ static hipError_t launch_k1(smc_ctx* c, const void* logits, int64_t row_stride_b
     const uint32_t k0 = (uint32_t)c->cfg.seed, k1 = (uint32_t)(c->cfg.seed >> 32);
     const int V = c->cfg.V;
     Partial* pa = c->ws.partials;
+    const int32_t* dn = c->cfg.eos_id >= 0 ? c->ws.done : nullptr;
     int P = 0;
     if (betaf == floorf(betaf) && betaf >= 1.f && betaf <= 8.f && betaf != 7.f) P = (int)betaf;
 #define PSMC_LAUNCH(PP) hipLaunchKernelGGL((vocab_pass_kernel<DT, PP, DENSE, NW>), grid, block, 0, c->stream, logits, \
-                                           row_stride_bytes, V, betaf, k0, k1, (uint32_t)t, n_split, vecs_per_split, pa)
+                                           row_stride_bytes, V, betaf, k0, k1, (uint32_t)t, n_split, vecs_per_split, pa, dn)
     switch (P) {
         case 1: PSMC_LAUNCH(1); break;
         case 2: PSMC_LAUNCH(2); break;
@@ -599,12 +615,12 @@ hipError_t launch_vocab_pass(smc_ctx* c, const void* logits, int64_t row_stride,
         hipLaunchKernelGGL((finalize_rows_kernel<SMC_BF16>), dim3(c->R), dim3(kWave), 0, c->stream, logits,
                            row_stride_bytes, c->cfg.V, c->cfg.N, beta, alpha_t, alpha_prev, k0, k1, (uint32_t)t, n_split,
                            w.partials, w.logW, w.cumlogp, w.parity, hist, c->cfg.T_max, tokens_out, w.d_delta,
-                           w.d_logZ1, w.d_logZb, w.d_gap, w.d_second, w.d_rowstat);
+                           w.d_logZ1, w.d_logZb, w.d_gap, w.d_second, w.d_rowstat, c->cfg.eos_id, w.done);
     else
         hipLaunchKernelGGL((finalize_rows_kernel<SMC_F32>), dim3(c->R), dim3(kWave), 0, c->stream, logits,
                            row_stride_bytes, c->cfg.V, c->cfg.N, beta, alpha_t, alpha_prev, k0, k1, (uint32_t)t, n_split,
                            w.partials, w.logW, w.cumlogp, w.parity, hist, c->cfg.T_max, tokens_out, w.d_delta,
-                           w.d_logZ1, w.d_logZb, w.d_gap, w.d_second, w.d_rowstat);
+                           w.d_logZ1, w.d_logZb, w.d_gap, w.d_second, w.d_rowstat, c->cfg.eos_id, w.done);
     return hipGetLastError();
 }
 

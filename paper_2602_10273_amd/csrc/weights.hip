@@ -90,12 +90,40 @@ __global__ __launch_bounds__(kWave) void resample_kernel(double* __restrict__ lo
     }
 }
 
+// Output of Alg. 1: I ~ Categorical(W) by inversion of the running sum of the normalised weights (particle order).
+__global__ __launch_bounds__(kWave) void final_draw_kernel(const double* __restrict__ logW, int N, uint32_t key0,
+                                                           uint32_t key1, uint32_t step, int32_t* __restrict__ choice)
+{
+    __shared__ double sh_a[SMC_MAX_PARTICLES], sh_b[SMC_MAX_PARTICLES];
+    const int b = blockIdx.x, lane = threadIdx.x;
+    const double* lw = logW + (int64_t)b * N;
+    double L1, L2;
+    prompt_lse(lw, N, sh_a, sh_b, L1, L2);
+    for (int i = lane; i < N; i += kWave) sh_a[i] = exp(lw[i] - L1);
+    __syncthreads();
+    if (lane == 0) {
+        const U4 blk = philox4x32_10(0u, (uint32_t)b, step, 2u, key0, key1);
+        const double u = ((double)blk.x + 0.5) * 0x1p-32;
+        double c = 0.0;
+        int pick = N - 1;
+        for (int j = 0; j < N; ++j) { c += sh_a[j]; if (c >= u) { pick = j; break; } }
+        choice[b] = b * N + pick;
+    }
+}
+
+hipError_t launch_final_draw(smc_ctx* c, int t, int32_t* choice)
+{
+    hipLaunchKernelGGL(final_draw_kernel, dim3(c->cfg.B), dim3(kWave), 0, c->stream, c->ws.logW, c->cfg.N,
+                       (uint32_t)c->cfg.seed, (uint32_t)(c->cfg.seed >> 32), (uint32_t)t, choice);
+    return hipGetLastError();
+}
+
 // Alg. 1 initialisation: W~ = 1, empty prefixes; all prompts live in buffer A; diagnostics cleared.
-__global__ void init_state_kernel(double* logW, double* cumlogp, int32_t* parity, int R, int B, int32_t* rowstat,
+__global__ void init_state_kernel(double* logW, double* cumlogp, int32_t* parity, int32_t* done, int R, int B, int32_t* rowstat,
                                   GatherPlan* plan)
 {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < R) { logW[i] = 0.0; cumlogp[i] = 0.0; rowstat[3 * i] = 0; rowstat[3 * i + 1] = 0; rowstat[3 * i + 2] = 0; }
+    if (i < R) { logW[i] = 0.0; cumlogp[i] = 0.0; done[i] = 0; rowstat[3 * i] = 0; rowstat[3 * i + 1] = 0; rowstat[3 * i + 2] = 0; }
     if (i < B) parity[i] = 0;
     if (i == 0) {
         plan->n_groups = 0; plan->bad_anc = 0;
@@ -106,7 +134,7 @@ hipError_t launch_init_state(smc_ctx* c)
 {
     const int n = c->R > c->cfg.B ? c->R : c->cfg.B;
     hipLaunchKernelGGL(init_state_kernel, dim3((n + 255) / 256), dim3(256), 0, c->stream, c->ws.logW, c->ws.cumlogp,
-                       c->ws.parity, c->R, c->cfg.B, c->ws.d_rowstat, c->ws.plan);
+                       c->ws.parity, c->ws.done, c->R, c->cfg.B, c->ws.d_rowstat, c->ws.plan);
     return hipGetLastError();
 }
 

@@ -10,7 +10,7 @@ from . import binding as smc
 
 class Session:
     def __init__(self, B, N, V, T_max, dtype, kappa, seed, kv_geom=None, kv=None, with_hist=True, device="cuda",
-                 stream=None):
+                 stream=None, eos_id=-1):
         """kv_geom = (kv_tensors, H, S, D) allocates zeroed double buffers; kv = list of [R,H,S,D] bf16/uint16
         tensors (numpy or torch) to copy into buffer A instead."""
         self.B, self.N, self.V, self.T_max, self.R = B, N, V, T_max, B * N
@@ -31,7 +31,7 @@ class Session:
                 self.kvB.append(torch.zeros((self.R, H, S, D), dtype=torch.bfloat16, device=dev))
         n, H, S, D = kv_geom if kv_geom is not None else (0, 0, 0, 0)
         self.kv_geom = (n, H, S, D)
-        self.cfg = smc.make_config(B, N, V, T_max, dtype, kappa, seed, n, H, S, D, 2)
+        self.cfg = smc.make_config(B, N, V, T_max, dtype, kappa, seed, n, H, S, D, 2, eos_id)
         nbytes = smc.smc_workspace_bytes(self.cfg)
         if nbytes == 0:
             raise ValueError("invalid configuration")
@@ -46,6 +46,7 @@ class Session:
         self.lognormw = torch.zeros(self.R, dtype=torch.float64, device=dev)
         self.anc = torch.zeros(self.R, dtype=torch.int32, device=dev)
         self.resampled = torch.zeros(B, dtype=torch.int32, device=dev)
+        self.choice = torch.zeros(B, dtype=torch.int32, device=dev)
         self.histA = self.histB = None
         if with_hist:
             self.histA = torch.zeros((self.R, T_max), dtype=torch.int32, device=dev)
@@ -77,6 +78,17 @@ class Session:
     def reindex(self, valid_len, t, anc=None, resampled=None):
         smc.smc_kv_reindex(self.ctx, self.anc if anc is None else anc,
                            self.resampled if resampled is None else resampled, valid_len, t)
+
+    def final_draw(self, t):
+        smc.smc_final_draw(self.ctx, t, self.choice)
+
+    def done(self):
+        d = np.empty(self.R, np.int32)
+        smc.smc_get_done(self.ctx, d)
+        return d
+
+    def set_done(self, d):
+        smc.smc_set_done(self.ctx, np.ascontiguousarray(d, np.int32))
 
     # ---- inspection ---------------------------------------------------------------------------------------
     def state(self):

@@ -39,13 +39,14 @@ def _ambiguous_resample(o, lnw, t):
     return out
 
 
-def run_lockstep(w, seed, steps, tau=-1.0, table=None, grow_kv=True, kv_seed=3):
+def run_lockstep(w, seed, steps, tau=-1.0, table=None, grow_kv=True, kv_seed=3, eos_id=-1):
     kv = synth.kv_numpy(w, kv_seed)
     T_max = (steps + 3) // 4 * 4
-    s = Session(w.B, w.N, w.V, T_max, w.dtype, w.kappa, seed, kv=kv)
-    o = orc.OracleSMC(w.B, w.N, w.V, T_max, w.kappa, seed, w.dtype, kv=[k.copy() for k in kv])
+    s = Session(w.B, w.N, w.V, T_max, w.dtype, w.kappa, seed, kv=kv, eos_id=eos_id)
+    o = orc.OracleSMC(w.B, w.N, w.V, T_max, w.kappa, seed, w.dtype, kv=[k.copy() for k in kv], eos_id=eos_id)
     kv_rng = np.random.default_rng([seed, 99])
-    stats = dict(token_ties=0, ess_band=0, pos_band=0, resamples=0, steps=0, max_dw=0.0, max_dess=0.0)
+    stats = dict(token_ties=0, ess_band=0, pos_band=0, resamples=0, steps=0, max_dw=0.0, max_dess=0.0, done=0,
+                 draw_band=0)
     for t in range(1, steps + 1):
         if table is not None:
             prev = np.zeros(w.R, np.int64) if t == 1 else o.hist[:, t - 2]
@@ -97,8 +98,13 @@ def run_lockstep(w, seed, steps, tau=-1.0, table=None, grow_kv=True, kv_seed=3):
                 for b in range(w.B):
                     rows = slice(b * w.N, (b + 1) * w.N)
                     (s.kvB if par[b] else s.kvA)[ten][rows, :, t - 1, :] = nd[rows]
+        done_before_reindex = o.done.copy()
+        if eos_id >= 0 and not dirty:
+            assert np.array_equal(s.done(), o.done), t          # termination flags after the step
         o.reindex(anc_ref, flag_ref, valid, t)
         if dirty:                           # follow the oracle's decisions and state
+            if eos_id >= 0:
+                s.set_done(done_before_reindex)
             s.reindex(valid, t, torch.as_tensor(anc_ref).cuda(), torch.as_tensor(flag_ref).cuda())
             s.set_state(o.logW, o.cumlogp)
             _resync_hist(s, o, t)
@@ -110,7 +116,21 @@ def run_lockstep(w, seed, steps, tau=-1.0, table=None, grow_kv=True, kv_seed=3):
         if t % 8 == 0 or t == steps:
             for ten in range(len(kv)):
                 assert np.array_equal(s.live_kv(ten)[:, :, :valid], o.kv[ten][:, :, :valid]), (t, ten)
+        if eos_id >= 0:
+            assert np.array_equal(s.done(), o.done), t          # ... and after they followed their ancestors
         stats["steps"] += 1
+    stats["done"] = int(o.done.sum())
+    # output of Alg. 1: one particle per prompt from the final weights
+    pick_ref = o.final_draw(steps)
+    s.final_draw(steps)
+    pick = s.choice.cpu().numpy()
+    _, lnw_ref = o.ess()
+    for b in range(w.B):
+        if pick[b] != pick_ref[b]:
+            C = np.cumsum(np.exp(lnw_ref[b * w.N:(b + 1) * w.N]))
+            u = orc.uniform(orc.random_word(seed, steps, b, 0, 2))
+            assert np.abs(C - u).min() < 1e-5, (b, pick[b], pick_ref[b])
+            stats["draw_band"] += 1
     s.close()
     return stats
 
@@ -141,6 +161,18 @@ def test_reduced_workloads_lockstep(name, kw, steps):
     print(name, st)
     assert st["resamples"] > 0
     assert st["token_ties"] + st["ess_band"] + st["pos_band"] <= 2
+
+
+def test_eos_absorbing_state_lockstep():
+    """Terminated particles: forced EOS, weight kept, flags gathered by ancestor (Alg. 1 'if done'; App. D)."""
+    w1 = synth.WORKLOADS["cfg1"]
+    table = synth.bigram_table(w1.V, w1.sigma, seed=0)
+    st = run_lockstep(synth.scaled(w1, B=400), 77, w1.steps, table=table, eos_id=3)
+    assert st["done"] > 100 and st["resamples"] > 10
+    # a wider vocabulary with an exponent ramp (the boundary reweight reaches terminated particles too)
+    w = synth.scaled(synth.WORKLOADS["cfg4"], B=8, N=16, V=264, layers=1, H=1, S=32, D=32, ramp=16)
+    st = run_lockstep(w, seed=2, steps=32, eos_id=5)
+    assert st["done"] > 0
 
 
 def test_off_optimal_proposal_lockstep():
