@@ -108,6 +108,13 @@ smc_status smc_ess(smc_ctx* ctx, double* d_ess_out, double* d_lognormw_out);
  * d_ess_out double [B] nullable.  Resets log W~ to 0 for resampled prompts (Alg. 1 "reset"). */
 smc_status smc_resample(smc_ctx* ctx, int32_t t, int32_t* d_anc_out, int32_t* d_resampled_out, double* d_ess_out);
 
+/* Resampling scheme used by smc_resample / smc_resample_from: 0 = systematic (the paper's, Sec. 7; default),
+ * 1 = stratified, 2 = multinomial, 3 = residual -- the other unbiased schemes App. E names, in their textbook form.
+ * Uniform u_i is word i of the prompt's Philox stream of domain 1; positions are (u_0+i)/N, (u_i+i)/N, u_i; residual
+ * resampling places floor(N w_j) copies of each j in index order and draws the rest multinomially from the
+ * residual weights. */
+smc_status smc_set_resampler(smc_ctx* ctx, int32_t scheme);
+
 /* a5: for every prompt b with d_resampled[b] != 0 and every row k of it, copies row d_anc[k] of the live
  * buffer into row k of the other buffer -- the first valid_len (0..kv_S) positions of every head of every KV
  * tensor, the first t columns of the history -- gathers cumulative log p and the termination flags the same way,

@@ -205,11 +205,58 @@ void orc_systematic(const double* w, int32_t N, double u0, int32_t* A)
     }
 }
 
-/* Step a4 for B prompts: trigger ESS < kappa*N (strict), offset u0 from the Philox stream (domain 1),
- * ancestors as global row indices, weights of resampled prompts reset to 1 (logW = 0).
- * Prompts that do not resample get the identity.  scratch_w: N doubles. */
+/* First index whose running sum reaches p (sums taken left to right); n-1 if rounding leaves none. */
+static int32_t invert_cumulative(const double* w, int32_t n, double p)
+{
+    double c = 0.0;
+    for (int32_t j = 0; j < n; ++j) { c += w[j]; if (c >= p) return j; }
+    return n - 1;
+}
+
+/* The resampling schemes App. E names as equally valid (all unbiased: E[#copies of j] = N w_j), in their textbook
+ * form (Doucet & Johansen's tutorial, the reference App. E cites).  u_i is the uniform of word i of the prompt's
+ * resampling stream (Philox domain 1, row := prompt b).
+ *   0 systematic : p_i = (u_0 + i)/N                      (Sec. 7; one uniform)
+ *   1 stratified : p_i = (u_i + i)/N                      (one uniform per stratum)
+ *   2 multinomial: p_i = u_i                               (N independent draws, ancestors in draw order)
+ *   3 residual   : floor(N w_j) copies of each j in index order, then the remaining N - sum floor(.) ancestors are
+ *                  multinomial draws p_i = u_i from the residual weights (N w_j - floor(N w_j)) / remaining
+ * A_i = first index whose running sum of the weights used reaches p_i. */
+void orc_resample_scheme(const double* w, int32_t N, int32_t scheme, uint64_t seed, int32_t t, int32_t b,
+                         int32_t* A, double* scratch)
+{
+    if (scheme == 0) {
+        orc_systematic(w, N, orc_uniform(orc_random_word(seed, (uint32_t)t, (uint32_t)b, 0, 1)), A);
+    } else if (scheme == 1 || scheme == 2) {
+        for (int32_t i = 0; i < N; ++i) {
+            double u = orc_uniform(orc_random_word(seed, (uint32_t)t, (uint32_t)b, (uint32_t)i, 1));
+            double p = scheme == 1 ? (u + (double)i) / (double)N : u;
+            A[i] = invert_cumulative(w, N, p);
+        }
+    } else {
+        int32_t k = 0;
+        for (int32_t j = 0; j < N; ++j) {
+            double nw = (double)N * w[j];
+            int32_t copies = (int32_t)floor(nw);
+            scratch[j] = nw - (double)copies;
+            for (int32_t c = 0; c < copies && k < N; ++c) A[k++] = j;
+        }
+        int32_t rest = N - k;
+        if (rest > 0) {
+            for (int32_t j = 0; j < N; ++j) scratch[j] /= (double)rest;
+            for (int32_t i = 0; i < rest; ++i) {
+                double u = orc_uniform(orc_random_word(seed, (uint32_t)t, (uint32_t)b, (uint32_t)i, 1));
+                A[k++] = invert_cumulative(scratch, N, u);
+            }
+        }
+    }
+}
+
+/* Step a4 for B prompts: trigger ESS < kappa*N (strict), ancestors by the chosen scheme (0 = the paper's
+ * systematic resampling) as global row indices, weights of resampled prompts reset to 1 (logW = 0).
+ * Prompts that do not resample get the identity.  scratch_w: 2N doubles. */
 void orc_resample(double* logW, int32_t B, int32_t N, double kappa, uint64_t seed, int32_t t,
-                  int32_t* anc, int32_t* resampled, double* ess_out, double* scratch_w)
+                  int32_t* anc, int32_t* resampled, double* ess_out, double* scratch_w, int32_t scheme)
 {
     for (int32_t b = 0; b < B; ++b) {
         double* lw = logW + (int64_t)b * N;
@@ -220,8 +267,7 @@ void orc_resample(double* logW, int32_t B, int32_t N, double kappa, uint64_t see
         if (ess < kappa * (double)N) {
             int32_t A[N];
             for (int32_t i = 0; i < N; ++i) scratch_w[i] = exp(lw[i] - L1);
-            double u0 = orc_uniform(orc_random_word(seed, (uint32_t)t, (uint32_t)b, 0, 1));
-            orc_systematic(scratch_w, N, u0, A);
+            orc_resample_scheme(scratch_w, N, scheme, seed, t, b, A, scratch_w + N);
             for (int32_t i = 0; i < N; ++i) { anc[(int64_t)b * N + i] = b * N + A[i]; lw[i] = 0.0; }
             resampled[b] = 1;
         } else {

@@ -99,15 +99,28 @@ def systematic(w, u0):
     return A
 
 
-def resample(logW, B, N, kappa, seed, t):
+SCHEMES = {"systematic": 0, "stratified": 1, "multinomial": 2, "residual": 3}
+
+
+def resample_scheme(w, scheme, seed, t, b):
+    """Ancestors (local indices) of one prompt with normalised weights w under the named scheme."""
+    w = np.ascontiguousarray(w, dtype=np.float64)
+    A = np.empty(w.size, np.int32)
+    scratch = np.empty(w.size, np.float64)
+    lib().orc_resample_scheme(_p(w), C.c_int32(w.size), C.c_int32(SCHEMES.get(scheme, scheme)), C.c_uint64(int(seed)),
+                              C.c_int32(t), C.c_int32(b), _p(A), _p(scratch))
+    return A
+
+
+def resample(logW, B, N, kappa, seed, t, scheme=0):
     """Returns (anc[R] global rows, resampled[B], ess[B], logW after reset)."""
     lw = np.array(logW, dtype=np.float64).copy()
     anc = np.empty(B * N, np.int32)
     flag = np.empty(B, np.int32)
     e = np.empty(B, np.float64)
-    scratch = np.empty(N, np.float64)
+    scratch = np.empty(2 * N, np.float64)
     lib().orc_resample(_p(lw), C.c_int32(B), C.c_int32(N), C.c_double(kappa), C.c_uint64(int(seed)),
-                       C.c_int32(t), _p(anc), _p(flag), _p(e), _p(scratch))
+                       C.c_int32(t), _p(anc), _p(flag), _p(e), _p(scratch), C.c_int32(SCHEMES.get(scheme, scheme)))
     return anc, flag, e, lw
 
 
@@ -133,7 +146,7 @@ def gather_kv(src, anc, resampled, N, valid_len, dst=None):
 class OracleSMC:
     """Algorithm 1 for B independent prompts, state held in fp64 / numpy, one call per step of the path."""
 
-    def __init__(self, B, N, V, T_max, kappa, seed, dtype="f32", kv=None, eos_id=-1):
+    def __init__(self, B, N, V, T_max, kappa, seed, dtype="f32", kv=None, eos_id=-1, scheme="systematic"):
         self.B, self.N, self.V, self.T_max, self.R = B, N, V, T_max, B * N
         self.kappa, self.seed, self.dtype = float(kappa), int(seed), dtype
         self.logW = np.zeros(self.R, np.float64)          # Alg. 1: W~_0 = 1
@@ -141,6 +154,7 @@ class OracleSMC:
         self.hist = np.zeros((self.R, T_max), np.int32)   # prefixes y_{1:t}
         self.kv = kv                                      # list of [R,H,S,D] arrays or None
         self.log_Zhat = np.zeros(B, np.float64)           # running log of the normalising-constant estimate
+        self.scheme = scheme                              # resampling scheme (App. E); the paper uses systematic
         self.eos_id = int(eos_id)                         # -1: EOS is not special
         self.done = np.zeros(self.R, np.int32)            # Alg. 1 termination flags
 
@@ -164,7 +178,7 @@ class OracleSMC:
     def resample(self, t):
         """a4; also accumulates log Zhat += L1 - log N for prompts that resample."""
         L1 = np.array([logsumexp(self.logW[b * self.N:(b + 1) * self.N]) for b in range(self.B)])
-        anc, flag, e, lw = resample(self.logW, self.B, self.N, self.kappa, self.seed, t)
+        anc, flag, e, lw = resample(self.logW, self.B, self.N, self.kappa, self.seed, t, self.scheme)
         self.log_Zhat += np.where(flag != 0, L1 - np.log(self.N), 0.0)
         self.logW = lw
         return anc, flag, e

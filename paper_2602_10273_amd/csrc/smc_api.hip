@@ -121,6 +121,7 @@ smc_status smc_init(const smc_config* cfg, void* d_workspace, size_t workspace_b
     auto_shape(c->R, cfg->V, cfg->logits_dtype, &c->wg_waves, &c->n_split);
     c->dense = 0;
     c->mask_words = (cfg->N + 63) / 64;
+    c->resampler = 0;
     c->kv_bound = 0;
     c->hist_bound = 0;
     c->profiling = 0;
@@ -291,6 +292,14 @@ smc_status smc_get_diag(smc_ctx* ctx, double* h_delta, double* h_logZ1, double* 
         }
         h_counters[3] = (uint64_t)R * (uint64_t)ctx->cfg.V;
     }
+    return SMC_OK;
+}
+
+smc_status smc_set_resampler(smc_ctx* ctx, int32_t scheme)
+{
+    if (!ctx) return SMC_E_NULL;
+    if (scheme < 0 || scheme > 3) return SMC_E_RANGE;
+    ctx->resampler = scheme;
     return SMC_OK;
 }
 

@@ -49,13 +49,35 @@ __global__ __launch_bounds__(kWave) void ess_kernel(const double* __restrict__ l
         for (int i = lane; i < N; i += kWave) lognormw_out[(int64_t)b * N + i] = lw[i] - L1;
 }
 
-// a3 + a4: trigger, offset u0 from the Philox stream (domain 1), ancestors A_i = min{ j : C_j >= (u0 + i)/N }
-// with C the running sum of the normalised weights in particle order, weights of resampled prompts reset.
+// first j in [0, n) with C_j >= p for a non-decreasing C; n-1 if rounding leaves none
+__device__ __forceinline__ int first_reaching(const double* C, int n, double p)
+{
+    int lo = 0, hi = n - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (C[mid] >= p) hi = mid; else lo = mid + 1;
+    }
+    return lo;
+}
+
+// uniform of word i of the prompt's resampling stream (Philox domain 1, row := prompt)
+__device__ __forceinline__ double resampling_uniform(uint32_t i, uint32_t b, uint32_t step, uint32_t key0, uint32_t key1)
+{
+    const U4 blk = philox4x32_10(i >> 2, b, step, 1u, key0, key1);
+    return ((double)pick_word(blk, i & 3u) + 0.5) * 0x1p-32;
+}
+
+// a3 + a4: trigger ESS < kappa*N, ancestors, weights of resampled prompts reset.  Running sums of the normalised
+// weights are taken in particle order by one lane.  scheme 0 is the paper's systematic resampling
+// (A_i = min{ j : C_j >= (u_0 + i)/N }); 1 stratified ((u_i + i)/N), 2 multinomial (u_i), 3 residual
+// (floor(N w_j) copies, the rest multinomial on the residual weights) are the alternatives App. E names.
 __global__ __launch_bounds__(kWave) void resample_kernel(double* __restrict__ logW, int N, double kappa, uint32_t key0,
-                                                         uint32_t key1, uint32_t step, int32_t* __restrict__ anc,
-                                                         int32_t* __restrict__ resampled, double* __restrict__ ess_out)
+                                                         uint32_t key1, uint32_t step, int scheme,
+                                                         int32_t* __restrict__ anc, int32_t* __restrict__ resampled,
+                                                         double* __restrict__ ess_out)
 {
     __shared__ double sh_a[SMC_MAX_PARTICLES], sh_b[SMC_MAX_PARTICLES];
+    __shared__ int sh_k;
     const int b = blockIdx.x, lane = threadIdx.x;
     double* lw = logW + (int64_t)b * N;
     double L1, L2;
@@ -70,24 +92,48 @@ __global__ __launch_bounds__(kWave) void resample_kernel(double* __restrict__ lo
     }
     for (int i = lane; i < N; i += kWave) sh_a[i] = exp(lw[i] - L1);
     __syncthreads();
-    if (lane == 0) {
-        double c = 0.0;
-        for (int j = 0; j < N; ++j) { c += sh_a[j]; sh_b[j] = c; }
+    int32_t* A = anc + (int64_t)b * N;
+    if (scheme != 3) {
+        if (lane == 0) {
+            double c = 0.0;
+            for (int j = 0; j < N; ++j) { c += sh_a[j]; sh_b[j] = c; }
+        }
+        __syncthreads();
+        const double u0 = resampling_uniform(0u, (uint32_t)b, step, key0, key1);
+        for (int i = lane; i < N; i += kWave) {
+            double p;
+            if (scheme == 0) p = (u0 + (double)i) / (double)N;
+            else {
+                const double u = resampling_uniform((uint32_t)i, (uint32_t)b, step, key0, key1);
+                p = scheme == 1 ? (u + (double)i) / (double)N : u;
+            }
+            A[i] = b * N + first_reaching(sh_b, N, p);
+        }
+    } else {
+        if (lane == 0) {                                  // deterministic copies, then the residual weights' running sum
+            int k = 0;
+            for (int j = 0; j < N; ++j) {
+                const double nw = (double)N * sh_a[j];
+                const int copies = (int)floor(nw);
+                sh_b[j] = nw - (double)copies;
+                for (int c = 0; c < copies && k < N; ++c) A[k++] = b * N + j;
+            }
+            sh_k = k;
+            const int rest = N - k;
+            if (rest > 0) {
+                double c = 0.0;
+                for (int j = 0; j < N; ++j) { c += sh_b[j] / (double)rest; sh_b[j] = c; }
+            }
+        }
+        __syncthreads();
+        const int k = sh_k;
+        for (int i = lane; i < N - k; i += kWave) {
+            const double u = resampling_uniform((uint32_t)i, (uint32_t)b, step, key0, key1);
+            A[k + i] = b * N + first_reaching(sh_b, N, u);
+        }
     }
     __syncthreads();
-    const U4 blk = philox4x32_10(0u, (uint32_t)b, step, 1u, key0, key1);
-    const double u0 = ((double)blk.x + 0.5) * 0x1p-32;
-    for (int i = lane; i < N; i += kWave) {
-        const double p = (u0 + (double)i) / (double)N;
-        // first j with C_j >= p (C is non-decreasing); N-1 if rounding leaves none
-        int lo = 0, hi = N - 1;
-        while (lo < hi) {
-            const int mid = (lo + hi) >> 1;
-            if (sh_b[mid] >= p) hi = mid; else lo = mid + 1;
-        }
-        anc[(int64_t)b * N + i] = b * N + lo;
-        lw[i] = 0.0;
-    }
+    for (int i = lane; i < N; i += kWave) lw[i] = 0.0;
 }
 
 // Output of Alg. 1: I ~ Categorical(W) by inversion of the running sum of the normalised weights (particle order).
@@ -147,7 +193,7 @@ hipError_t launch_ess(smc_ctx* c, const double* logW, double* ess_out, double* l
 hipError_t launch_resample(smc_ctx* c, double* logW, int t, int32_t* anc, int32_t* resampled, double* ess_out)
 {
     hipLaunchKernelGGL(resample_kernel, dim3(c->cfg.B), dim3(kWave), 0, c->stream, logW, c->cfg.N, c->cfg.kappa,
-                       (uint32_t)c->cfg.seed, (uint32_t)(c->cfg.seed >> 32), (uint32_t)t, anc, resampled, ess_out);
+                       (uint32_t)c->cfg.seed, (uint32_t)(c->cfg.seed >> 32), (uint32_t)t, c->resampler, anc, resampled, ess_out);
     return hipGetLastError();
 }
 

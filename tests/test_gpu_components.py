@@ -129,6 +129,25 @@ def test_ess_and_resample_match_oracle():
         s.close()
 
 
+@pytest.mark.parametrize("scheme", ["stratified", "multinomial", "residual"])
+def test_other_resampling_schemes_match_oracle(scheme):
+    from paper_2602_10273_amd import binding as smc
+    rng = np.random.default_rng(5)
+    for (B, N) in [(6, 8), (4, 64), (3, 100), (2, 1024)]:
+        s = Session(B, N, 64, 8, "f32", 1.0, seed=77, with_hist=False)      # kappa = 1: every prompt resamples
+        smc.smc_set_resampler(s.ctx, orc.SCHEMES[scheme])
+        for scale in (0.3, 2.0, 10.0):
+            logW = rng.standard_normal(B * N) * scale
+            for t in (1, 5):
+                d = torch.as_tensor(logW).cuda()
+                smc.smc_resample_from(s.ctx, d, t, s.anc, s.resampled, s.ess)
+                anc_ref, flag_ref, _, lw_ref = orc.resample(logW, B, N, 1.0, 77, t, scheme)
+                assert np.array_equal(s.resampled.cpu().numpy(), flag_ref)
+                assert np.array_equal(s.anc.cpu().numpy(), anc_ref)
+                assert np.array_equal(d.cpu().numpy(), lw_ref)
+        s.close()
+
+
 def test_resample_degenerate_weights():
     from paper_2602_10273_amd import binding as smc
     B, N = 3, 8
