@@ -148,8 +148,10 @@ def main():
     flag_h = flag_log.cpu().numpy()
     esz = 2 if w.dtype == "bf16" else 4
     vocab_bytes = float(w.R) * w.V * esz                              # per launch: every logit read once
-    uniq = np.array([[len(np.unique(anc_h[i, b])) for b in range(w.B)] for i in range(K)])
-    rows_moved = ((uniq + w.N) * flag_h).sum()                        # unique ancestors read + N rows written
+    # per resampled prompt: rows whose ancestor is another row are written once; their distinct ancestors are read once
+    local = anc_h - (np.arange(w.B)[None, :, None] * w.N)
+    moved = (local != np.arange(w.N)[None, None, :]) & (flag_h[:, :, None] != 0)
+    rows_moved = int(moved.sum()) + sum(len(np.unique(local[i, b][moved[i, b]])) for i in range(K) for b in range(w.B))
     gather_bytes_total = float(rows_moved) * w.kv_row_bytes * w.kv_tensors
     resample_frac = float(flag_h.mean())
 

@@ -74,7 +74,7 @@ size_t smc_workspace_bytes(const smc_config* cfg);
 
 /* Creates a context.  d_workspace: device memory, 256-byte aligned, >= smc_workspace_bytes(cfg), owned
  * by the caller and left alone by it until smc_destroy.  hip_stream: a hipStream_t (NULL = default stream).
- * Enqueues the initialisation of Alg. 1: log W~ = 0, cumulative log p = 0, all prompts on buffer A. */
+ * Enqueues the initialisation of Alg. 1: log W~ = 0, cumulative log p = 0, every row live in buffer A. */
 smc_status smc_init(const smc_config* cfg, void* d_workspace, size_t workspace_bytes, void* hip_stream,
                     smc_ctx** out_ctx);
 
@@ -83,8 +83,9 @@ smc_status smc_destroy(smc_ctx* ctx);
 
 /* Registers the double-buffered caches (App. C).  h_bufA / h_bufB: host arrays of kv_tensors device pointers
  * (16-byte aligned, each tensor [R, kv_H, kv_S, kv_D]); d_histA / d_histB: device int32 [R, T_max] token
- * histories (may both be NULL: no history is kept).  Prompt b's live data is in buffer A while parity[b] = 0
- * and in buffer B while parity[b] = 1; smc_kv_reindex reads the live buffer, writes the other and flips parity[b].
+ * histories (may both be NULL: no history is kept).  Row k's live data is in buffer A while parity[k] = 0 and in
+ * buffer B while parity[k] = 1; smc_kv_reindex reads live buffers, writes the inactive buffer of every row that
+ * receives another row's data, and flips the parity of exactly those rows (smc_get_state returns the parities).
  * Synchronous (copies the pointer tables into the workspace). */
 smc_status smc_kv_bind(smc_ctx* ctx, void* const* h_bufA, void* const* h_bufB, int32_t* d_histA, int32_t* d_histB);
 
@@ -115,12 +116,12 @@ smc_status smc_resample(smc_ctx* ctx, int32_t t, int32_t* d_anc_out, int32_t* d_
  * residual weights. */
 smc_status smc_set_resampler(smc_ctx* ctx, int32_t scheme);
 
-/* a5: for every prompt b with d_resampled[b] != 0 and every row k of it, copies row d_anc[k] of the live
- * buffer into row k of the other buffer -- the first valid_len (0..kv_S) positions of every head of every KV
+/* a5: for every prompt b with d_resampled[b] != 0 and every row k of it with d_anc[k] != k, copies the live row
+ * d_anc[k] into the inactive buffer of row k -- the first valid_len (0..kv_S) positions of every head of every KV
  * tensor, the first t columns of the history -- gathers cumulative log p and the termination flags the same way,
- * then flips parity[b].
- * d_anc entries of a resampled prompt must lie inside that prompt's row range.  Each distinct ancestor row is
- * read once and written to all of its descendants. */
+ * then flips parity[k].  Rows that are their own ancestor move no bytes.  d_anc entries of a resampled prompt must
+ * lie inside that prompt's row range (others are ignored and the row left as it is).  Each distinct ancestor row is
+ * read once and written to all of its moved descendants. */
 smc_status smc_kv_reindex(smc_ctx* ctx, const int32_t* d_anc, const int32_t* d_resampled, int32_t valid_len,
                           int32_t t);
 
@@ -140,7 +141,7 @@ smc_status smc_get_done(smc_ctx* ctx, int32_t* h_done);
 smc_status smc_set_done(smc_ctx* ctx, const int32_t* h_done);
 
 /* Synchronous inspection / teacher forcing (host arrays; any may be NULL to skip):
- * h_logW, h_cumlogp double [R]; h_parity int32 [B]. */
+ * h_logW, h_cumlogp double [R]; h_parity int32 [R]. */
 smc_status smc_get_state(smc_ctx* ctx, double* h_logW, double* h_cumlogp, int32_t* h_parity);
 smc_status smc_set_state(smc_ctx* ctx, const double* h_logW, const double* h_cumlogp);
 

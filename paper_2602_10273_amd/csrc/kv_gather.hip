@@ -1,14 +1,17 @@
 // Cache-safe reindex after resampling (Alg. 1 "reorder KV cache by A"; App. C: reindex along the
 // batch/particle dimension) for gfx950: an out-of-place, double-buffered row gather.
 //
-// For a resampled prompt b, row k of the inactive buffer receives row anc[k] of the live buffer, for every KV
-// tensor and the token history; then parity[b] flips.  Pure HBM traffic, 16-byte vector loads and stores.
-// Rows that share an ancestor form a group: the ancestor's bytes are read ONCE into registers and stored to
-// every descendant, so a reindex moves (unique ancestors + N) rows per prompt, the least the method allows.
+// Every row (particle slot) k has two buffers and a parity bit: its live data is in buffer A while parity[k] = 0,
+// in buffer B while parity[k] = 1.  For a resampled prompt, a row whose ancestor is another row (anc[k] != k)
+// receives the ancestor's LIVE row in its own INACTIVE buffer, for every KV tensor and the token history, and then
+// its parity flips.  Readers only touch live buffers and writers only inactive ones, so any ancestor vector is safe,
+// and a row that is its own ancestor moves no bytes at all.  Pure HBM traffic, 16-byte vector loads and stores.
+// Moved rows that share an ancestor form a group: the ancestor's bytes are read ONCE into registers and stored to
+// every member, so a reindex moves (distinct ancestors of moved rows + moved rows) rows, the least the method allows.
 //
-//   plan_kernel    : one wave per prompt, builds the groups (ancestor row, bit set of descendants).
+//   plan_kernel    : one wave per prompt, builds the groups (ancestor row, bit set of moved descendants).
 //   gather_kernel  : persistent grid-stride loop over (group, tensor, head chunk, slab of 8..64 KiB).
-//   commit_kernel  : cumulative log p and termination flags gathered the same way, parity flipped, plan cleared.
+//   commit_kernel  : cumulative log p and termination flags gathered the same way, parities flipped, plan cleared.
 #include "device_rng.hpp"
 #include "smc_internal.hpp"
 
@@ -33,10 +36,11 @@ __global__ __launch_bounds__(kWave) void plan_kernel(const int32_t* __restrict__
     for (int k = lane; k < N; k += kWave) {
         int a = anc[row0 + k] - row0;
         if (a < 0 || a >= N) { a = -1; ++bad; }                    // outside the prompt: row is left untouched
+        if (a == k) a = -1;                                        // its own ancestor: nothing to move
         sh_anc[k] = a;
     }
     __syncthreads();
-    // leaders: first row (in particle order) of each distinct ancestor
+    // leaders: first moved row (in particle order) of each distinct ancestor
     int n_lead = 0;
     for (int k0 = 0; k0 < N; k0 += kWave) {
         const int k = k0 + lane;
@@ -108,9 +112,9 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(
 
         const int src_row = grp_src[g];
         const int row0 = grp_base[g];
-        const int par = parity[row0 / N];
-        const char* src = (const char*)(par ? bufB[tensor] : bufA[tensor]);
-        char* dst = (char*)(par ? bufA[tensor] : bufB[tensor]);
+        char* const baseA = (char*)bufA[tensor];
+        char* const baseB = (char*)bufB[tensor];
+        const char* src = parity[src_row] ? baseB : baseA;          // the ancestor's live buffer
         const int64_t off0 = (int64_t)chunk * chunk_stride + (int64_t)slab * kSlabBytes;
         const int64_t left = copy_bytes - (int64_t)slab * kSlabBytes;       // bytes of this chunk from the slab start
 
@@ -129,7 +133,8 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(
             while (bits) {
                 const int j = __ffsll((long long)bits) - 1;
                 bits &= bits - 1;
-                char* d = dst + (int64_t)(row0 + mw * 64 + j) * row_stride + off0;
+                const int drow = row0 + mw * 64 + j;
+                char* d = (parity[drow] ? baseA : baseB) + (int64_t)drow * row_stride + off0;   // its inactive buffer
 #pragma unroll
                 for (int u = 0; u < kVecPerThread; ++u) {
                     const int64_t o = ((int64_t)u * kGatherThreads + tid) * 16;
@@ -158,9 +163,11 @@ __global__ __launch_bounds__(kWave) void commit_kernel(const int32_t* __restrict
     __syncthreads();
     for (int k = lane; k < N; k += kWave) {
         const int a = anc[row0 + k] - row0;
-        if (a >= 0 && a < N) { cumlogp[row0 + k] = sh[a]; done[row0 + k] = sh_done[a]; }
+        if (a >= 0 && a < N && a != k) {
+            cumlogp[row0 + k] = sh[a]; done[row0 + k] = sh_done[a];
+            parity[row0 + k] ^= 1;                                 // the row now lives in the buffer just written
+        }
     }
-    if (lane == 0) parity[b] ^= 1;
 }
 
 template <int VPT, bool NT_LD, bool NT_ST>

@@ -42,7 +42,7 @@ size_t layout(const smc_config* c, char* base, Workspace* w)
     char* p;
     p = take(R * 8); if (w) w->logW = (double*)p;
     p = take(R * 8); if (w) w->cumlogp = (double*)p;
-    p = take((size_t)c->B * 4); if (w) w->parity = (int32_t*)p;
+    p = take(R * 4); if (w) w->parity = (int32_t*)p;
     p = take(R * 4); if (w) w->done = (int32_t*)p;
     p = take(R * kMaxSplit * sizeof(Partial)); if (w) w->partials = (Partial*)p;
     p = take(R * 8); if (w) w->d_delta = (double*)p;
@@ -257,7 +257,7 @@ smc_status smc_get_state(smc_ctx* ctx, double* h_logW, double* h_cumlogp, int32_
     const size_t R = ctx->R;
     if (h_logW && hipMemcpy(h_logW, ctx->ws.logW, R * 8, hipMemcpyDeviceToHost) != hipSuccess) return SMC_E_HIP;
     if (h_cumlogp && hipMemcpy(h_cumlogp, ctx->ws.cumlogp, R * 8, hipMemcpyDeviceToHost) != hipSuccess) return SMC_E_HIP;
-    if (h_parity && hipMemcpy(h_parity, ctx->ws.parity, (size_t)ctx->cfg.B * 4, hipMemcpyDeviceToHost) != hipSuccess)
+    if (h_parity && hipMemcpy(h_parity, ctx->ws.parity, R * 4, hipMemcpyDeviceToHost) != hipSuccess)
         return SMC_E_HIP;
     return SMC_OK;
 }

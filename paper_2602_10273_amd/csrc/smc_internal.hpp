@@ -41,7 +41,7 @@ struct GatherPlan {
 struct Workspace {                // device pointers carved out of the caller's workspace
     double* logW;                 // [R]
     double* cumlogp;              // [R]
-    int32_t* parity;              // [B]
+    int32_t* parity;              // [R] which of its two buffers holds a row's live KV / history
     int32_t* done;                // [R] termination flags (Alg. 1)
     Partial* partials;            // [R * kMaxSplit]
     double* d_delta;              // [R] diagnostics of the last step

@@ -473,7 +473,7 @@ __global__ __launch_bounds__(kWave) void finalize_rows_kernel(
             logW[row] += (alpha_t - alpha_prev) * cumlogp[row];
             tokens_out[row] = eos_id;
             if (histAB) {
-                int32_t* h = histAB[parity[row / N]];
+                int32_t* h = histAB[parity[row]];
                 if (h) h[(int64_t)row * T_max + (step - 1)] = eos_id;
             }
             d_delta[row] = 0.0; d_logZ1[row] = 0.0; d_logZb[row] = 0.0; d_gap[row] = INFINITY; d_second[row] = -1;
@@ -536,7 +536,7 @@ __global__ __launch_bounds__(kWave) void finalize_rows_kernel(
         cumlogp[row] += logp;
         tokens_out[row] = tok;
         if (histAB) {
-            int32_t* h = histAB[parity[row / N]];
+            int32_t* h = histAB[parity[row]];
             if (h) h[(int64_t)row * T_max + (step - 1)] = tok;
         }
         d_delta[row] = delta; d_logZ1[row] = logZ1; d_logZb[row] = logZb;

@@ -164,13 +164,12 @@ hipError_t launch_final_draw(smc_ctx* c, int t, int32_t* choice)
     return hipGetLastError();
 }
 
-// Alg. 1 initialisation: W~ = 1, empty prefixes; all prompts live in buffer A; diagnostics cleared.
+// Alg. 1 initialisation: W~ = 1, empty prefixes; all rows live in buffer A; diagnostics cleared.
 __global__ void init_state_kernel(double* logW, double* cumlogp, int32_t* parity, int32_t* done, int R, int B, int32_t* rowstat,
                                   GatherPlan* plan)
 {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < R) { logW[i] = 0.0; cumlogp[i] = 0.0; done[i] = 0; rowstat[3 * i] = 0; rowstat[3 * i + 1] = 0; rowstat[3 * i + 2] = 0; }
-    if (i < B) parity[i] = 0;
+    if (i < R) { logW[i] = 0.0; cumlogp[i] = 0.0; done[i] = 0; parity[i] = 0; rowstat[3 * i] = 0; rowstat[3 * i + 1] = 0; rowstat[3 * i + 2] = 0; }
     if (i == 0) {
         plan->n_groups = 0; plan->bad_anc = 0;
     }

@@ -92,7 +92,7 @@ class Session:
 
     # ---- inspection ---------------------------------------------------------------------------------------
     def state(self):
-        logW = np.empty(self.R, np.float64); cum = np.empty(self.R, np.float64); par = np.empty(self.B, np.int32)
+        logW = np.empty(self.R, np.float64); cum = np.empty(self.R, np.float64); par = np.empty(self.R, np.int32)
         smc.smc_get_state(self.ctx, logW, cum, par)
         return logW, cum, par
 
@@ -108,10 +108,10 @@ class Session:
         return d
 
     def live_hist(self):
-        """[R, T_max] numpy: each prompt's rows taken from its live buffer."""
+        """[R, T_max] numpy: each row taken from its live buffer."""
         _, _, par = self.state()
         A, Bh = self.histA.cpu().numpy(), self.histB.cpu().numpy()
-        sel = np.repeat(par, self.N).astype(bool)
+        sel = par.astype(bool)
         return np.where(sel[:, None], Bh, A)
 
     def live_kv(self, tensor, rows=None):
@@ -120,7 +120,7 @@ class Session:
         rows = np.arange(self.R) if rows is None else np.asarray(rows)
         out = []
         for r in rows:
-            src = self.kvB[tensor] if par[r // self.N] else self.kvA[tensor]
+            src = self.kvB[tensor] if par[r] else self.kvA[tensor]
             out.append(src[int(r)].view(torch.int16).cpu().numpy().view(np.uint16))
         return np.stack(out)
 

@@ -189,22 +189,25 @@ def test_reindex_bytes_exact(B, N, H, S, D, valid):
                 anc[b * N:(b + 1) * N] = b * N + rng.permutation(N)                 # permutation
             else:
                 anc[b * N:(b + 1) * N] = b * N + np.sort(rng.integers(0, N, N))     # duplicates
-        # poison the inactive buffers: stale bytes must never be read as live data
+        # poison every row's inactive buffer: stale bytes must never be read as live data
         _, _, par = s.state()
-        for b in range(B):
-            for ten in range(len(kv)):
-                (s.kvA if par[b] else s.kvB)[ten][b * N:(b + 1) * N].fill_(-21846 if s.kvA[ten].dtype == torch.int16 else 0)
+        for ten in range(len(kv)):
+            pa = torch.as_tensor(par.astype(bool)).cuda()
+            s.kvA[ten][pa] = -21846                                         # 0xAAAA in the buffer that is not live
+            s.kvB[ten][~pa] = -21846
         t = 5 + it
         # what a step does before a reindex: column t-1 of the live history receives this step's tokens
         col = rng.integers(0, 32, size=R).astype(np.int32)
         o.hist[:, t - 1] = col
         cold = torch.as_tensor(col).cuda()
-        for b in range(B):
-            (s.histB if par[b] else s.histA)[b * N:(b + 1) * N, t - 1] = cold[b * N:(b + 1) * N]
+        pa = torch.as_tensor(par.astype(bool)).cuda()
+        s.histA[~pa, t - 1] = cold[~pa]
+        s.histB[pa, t - 1] = cold[pa]
         s.reindex(valid, t, torch.as_tensor(anc).cuda(), torch.as_tensor(flag).cuda())
         o.reindex(anc, flag, valid, t)
         _, cum_g, par2 = s.state()
-        assert np.array_equal(par2, par ^ flag)
+        moved = (anc != np.arange(R)) & (np.repeat(flag, N) != 0)
+        assert np.array_equal(par2, par ^ moved.astype(np.int32))      # exactly the rows that received data flip
         assert np.array_equal(cum_g, o.cumlogp)
         assert np.array_equal(s.live_hist()[:, :t], o.hist[:, :t])
         for ten in range(len(kv)):
@@ -223,5 +226,7 @@ def test_reindex_rejects_foreign_ancestors_without_touching_memory():
     s.reindex(4, 1, torch.as_tensor(anc).cuda(), torch.as_tensor(flag).cuda())
     got = s.live_kv(0)
     assert np.array_equal(got[0], kv[0][0]) and np.array_equal(got[1], kv[0][0])
-    assert np.all(got[2] == 0) and np.all(got[3] == 0)        # skipped rows stay as the (zeroed) inactive buffer
+    assert np.array_equal(got[2], kv[0][2]) and np.array_equal(got[3], kv[0][3])      # skipped rows keep their data
+    _, _, par = s.state()
+    assert list(par) == [0, 1, 0, 0, 0, 0, 0, 0]              # only row 1 received another row
     s.close()

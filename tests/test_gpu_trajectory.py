@@ -22,9 +22,9 @@ TOL = 1e-4
 def _resync_hist(s, o, t):
     _, _, par = s.state()
     h = torch.as_tensor(o.hist[:, :t]).cuda()
-    for b in range(s.B):
-        rows = slice(b * s.N, (b + 1) * s.N)
-        (s.histB if par[b] else s.histA)[rows, :t] = h[rows]
+    pa = torch.as_tensor(par.astype(bool)).cuda()
+    s.histA[~pa, :t] = h[~pa]
+    s.histB[pa, :t] = h[pa]
 
 
 def _ambiguous_resample(o, lnw, t):
@@ -95,9 +95,9 @@ def run_lockstep(w, seed, steps, tau=-1.0, table=None, grow_kv=True, kv_seed=3, 
                 new = synth.f32_to_bf16_bits(kv_rng.standard_normal((w.R, w.H, w.D), dtype=np.float32))
                 o.kv[ten][:, :, t - 1, :] = new
                 nd = torch.as_tensor(new.view(np.int16)).cuda()
-                for b in range(w.B):
-                    rows = slice(b * w.N, (b + 1) * w.N)
-                    (s.kvB if par[b] else s.kvA)[ten][rows, :, t - 1, :] = nd[rows]
+                pa = torch.as_tensor(par.astype(bool)).cuda()
+                s.kvA[ten][~pa, :, t - 1, :] = nd[~pa]
+                s.kvB[ten][pa, :, t - 1, :] = nd[pa]
         done_before_reindex = o.done.copy()
         if eos_id >= 0 and not dirty:
             assert np.array_equal(s.done(), o.done), t          # termination flags after the step
