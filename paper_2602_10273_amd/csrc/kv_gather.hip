@@ -9,9 +9,11 @@
 // Moved rows that share an ancestor form a group: the ancestor's bytes are read ONCE into registers and stored to
 // every member, so a reindex moves (distinct ancestors of moved rows + moved rows) rows, the least the method allows.
 //
-//   plan_kernel    : one wave per prompt, builds the groups (ancestor row, bit set of moved descendants).
-//   gather_kernel  : persistent grid-stride loop over (group, tensor, head chunk, slab of 8..64 KiB).
-//   commit_kernel  : cumulative log p and termination flags gathered the same way, parities flipped, plan cleared.
+//   plan_kernel    : one wave per prompt.  Builds the groups (ancestor row and which of its buffers is live, bit set
+//                    of moved descendants), gathers cumulative log p and termination flags the same way, and flips
+//                    the parity of the moved rows -- so after it, a moved row's parity names the buffer to WRITE.
+//   gather_kernel  : persistent grid-stride loop over (group, tensor, head chunk, slab of 8..64 KiB) for the KV
+//                    tensors, followed in the same launch by the token-history rows.
 #include "device_rng.hpp"
 #include "smc_internal.hpp"
 
@@ -22,14 +24,21 @@ constexpr int kGatherThreads = 256;
 typedef unsigned int vec16 __attribute__((ext_vector_type(4)));    // one 16-byte global load / store
 }  // namespace
 
+// phase: which of the plan's two group counters this call uses; the other one is cleared for the next call.
 __global__ __launch_bounds__(kWave) void plan_kernel(const int32_t* __restrict__ anc, const int32_t* __restrict__ resampled,
-                                                     int N, int mask_words, GatherPlan* __restrict__ plan,
+                                                     int N, int mask_words, int phase, GatherPlan* __restrict__ plan,
                                                      int32_t* __restrict__ grp_src, int32_t* __restrict__ grp_base,
-                                                     unsigned long long* __restrict__ grp_mask)
+                                                     int32_t* __restrict__ grp_srcpar,
+                                                     unsigned long long* __restrict__ grp_mask,
+                                                     double* __restrict__ cumlogp, int32_t* __restrict__ done,
+                                                     int32_t* __restrict__ parity)
 {
     __shared__ int32_t sh_anc[SMC_MAX_PARTICLES];
+    __shared__ double sh_cum[SMC_MAX_PARTICLES];
+    __shared__ int32_t sh_done[SMC_MAX_PARTICLES];
     __shared__ int32_t sh_base;
     const int b = blockIdx.x, lane = threadIdx.x;
+    if (b == 0 && lane == 0) plan->n_groups[phase ^ 1] = 0;
     if (!resampled[b]) return;
     const int row0 = b * N;
     int bad = 0;
@@ -38,6 +47,8 @@ __global__ __launch_bounds__(kWave) void plan_kernel(const int32_t* __restrict__
         if (a < 0 || a >= N) { a = -1; ++bad; }                    // outside the prompt: row is left untouched
         if (a == k) a = -1;                                        // its own ancestor: nothing to move
         sh_anc[k] = a;
+        sh_cum[k] = cumlogp[row0 + k];
+        sh_done[k] = done[row0 + k];
     }
     __syncthreads();
     // leaders: first moved row (in particle order) of each distinct ancestor
@@ -52,13 +63,11 @@ __global__ __launch_bounds__(kWave) void plan_kernel(const int32_t* __restrict__
         }
         n_lead += __popcll(__ballot(lead));
     }
-    if (lane == 0) {
-        sh_base = n_lead ? atomicAdd(&plan->n_groups, n_lead) : 0;
-    }
+    if (lane == 0) sh_base = n_lead ? atomicAdd(&plan->n_groups[phase], n_lead) : 0;
     for (int o = 32; o > 0; o >>= 1) bad += __shfl_xor(bad, o);
     if (lane == 0 && bad) atomicAdd(&plan->bad_anc, bad);
     __syncthreads();
-    int done = 0;
+    int placed = 0;
     for (int k0 = 0; k0 < N; k0 += kWave) {
         const int k = k0 + lane;
         bool lead = false;
@@ -70,9 +79,10 @@ __global__ __launch_bounds__(kWave) void plan_kernel(const int32_t* __restrict__
         }
         const unsigned long long mk = __ballot(lead);
         if (lead) {
-            const int g = sh_base + done + mask_rank(mk);
+            const int g = sh_base + placed + mask_rank(mk);
             grp_src[g] = row0 + a;
             grp_base[g] = row0;
+            grp_srcpar[g] = parity[row0 + a];                      // the ancestor's live buffer, before any flip
             for (int w = 0; w < mask_words; ++w) {
                 unsigned long long bits = 0;
                 const int hi = min(N - w * 64, 64);
@@ -80,46 +90,65 @@ __global__ __launch_bounds__(kWave) void plan_kernel(const int32_t* __restrict__
                 grp_mask[(int64_t)g * mask_words + w] = bits;
             }
         }
-        done += __popcll(mk);
+        placed += __popcll(mk);
+    }
+    __syncthreads();                                               // every group has recorded its source parity
+    for (int k = lane; k < N; k += kWave) {
+        const int a = sh_anc[k];
+        if (a >= 0) {
+            cumlogp[row0 + k] = sh_cum[a];
+            done[row0 + k] = sh_done[a];
+            parity[row0 + k] ^= 1;                                 // from now on: the buffer this row is written to
+        }
     }
 }
 
-// One launch copies `n_tensors` tensors of identical geometry.  Row r of a tensor starts at r*row_stride bytes;
-// of each of its `n_chunks` chunks (chunk_stride bytes apart) the first `copy_bytes` bytes are copied.
-// copy_bytes is a multiple of 16; the last vector of a chunk may be cut at `chunk_limit` bytes (history rows).
+struct GatherGeom {               // one family of tensors with identical geometry
+    void* const* bufA; void* const* bufB;
+    int n_tensors, n_chunks, slabs_per_chunk;
+    long long row_stride, chunk_stride, copy_bytes;
+};
+
+// Row r of a tensor starts at r*row_stride bytes; of each of its n_chunks chunks (chunk_stride bytes apart) the first
+// copy_bytes bytes (a multiple of 16) are copied.  `kv` and `hist` are the two families handled by one launch.
 // VPT: 16-byte vectors in flight per thread (a workgroup iteration moves a slab of 256*VPT*16 bytes);
 // NT_LD / NT_ST: non-temporal loads / stores.
 template <int VPT, bool NT_LD, bool NT_ST>
 __global__ __launch_bounds__(kGatherThreads) void gather_kernel(
-    void* const* __restrict__ bufA, void* const* __restrict__ bufB, const int32_t* __restrict__ parity, int N,
-    int n_tensors, int n_chunks, int64_t row_stride, int64_t chunk_stride, int64_t copy_bytes, int slabs_per_chunk,
-    int mask_words, const GatherPlan* __restrict__ plan, const int32_t* __restrict__ grp_src,
-    const int32_t* __restrict__ grp_base, const unsigned long long* __restrict__ grp_mask)
+    GatherGeom kv, GatherGeom hist, const int32_t* __restrict__ parity, int mask_words, int phase,
+    const GatherPlan* __restrict__ plan, const int32_t* __restrict__ grp_src, const int32_t* __restrict__ grp_base,
+    const int32_t* __restrict__ grp_srcpar, const unsigned long long* __restrict__ grp_mask)
 {
     constexpr int kVecPerThread = VPT;
     constexpr int kSlabBytes = kGatherThreads * VPT * 16;
-    const int n_groups = plan->n_groups;
-    const int64_t per_group = (int64_t)n_tensors * n_chunks * slabs_per_chunk;
-    const int64_t total = per_group * n_groups;
+    const int n_groups = plan->n_groups[phase];
+    const int64_t per_group_kv = (int64_t)kv.n_tensors * kv.n_chunks * kv.slabs_per_chunk;
+    const int64_t per_group_h = (int64_t)hist.n_tensors * hist.n_chunks * hist.slabs_per_chunk;
+    const int64_t total_kv = per_group_kv * n_groups;
+    const int64_t total = total_kv + per_group_h * n_groups;
     const int tid = threadIdx.x;
     for (int64_t w = blockIdx.x; w < total; w += gridDim.x) {
-        const int g = (int)(w / per_group);
-        int64_t rem = w - (int64_t)g * per_group;
-        const int tensor = (int)(rem / ((int64_t)n_chunks * slabs_per_chunk));
-        rem -= (int64_t)tensor * n_chunks * slabs_per_chunk;
-        const int chunk = (int)(rem / slabs_per_chunk);
-        const int slab = (int)(rem - (int64_t)chunk * slabs_per_chunk);
+        const bool is_kv = w < total_kv;
+        const GatherGeom& ge = is_kv ? kv : hist;
+        const int64_t per_group = is_kv ? per_group_kv : per_group_h;
+        int64_t rem = is_kv ? w : w - total_kv;
+        const int g = (int)(rem / per_group);
+        rem -= (int64_t)g * per_group;
+        const int tensor = (int)(rem / ((int64_t)ge.n_chunks * ge.slabs_per_chunk));
+        rem -= (int64_t)tensor * ge.n_chunks * ge.slabs_per_chunk;
+        const int chunk = (int)(rem / ge.slabs_per_chunk);
+        const int slab = (int)(rem - (int64_t)chunk * ge.slabs_per_chunk);
 
         const int src_row = grp_src[g];
         const int row0 = grp_base[g];
-        char* const baseA = (char*)bufA[tensor];
-        char* const baseB = (char*)bufB[tensor];
-        const char* src = parity[src_row] ? baseB : baseA;          // the ancestor's live buffer
-        const int64_t off0 = (int64_t)chunk * chunk_stride + (int64_t)slab * kSlabBytes;
-        const int64_t left = copy_bytes - (int64_t)slab * kSlabBytes;       // bytes of this chunk from the slab start
+        char* const baseA = (char*)ge.bufA[tensor];
+        char* const baseB = (char*)ge.bufB[tensor];
+        const char* src = grp_srcpar[g] ? baseB : baseA;            // the ancestor's live buffer
+        const int64_t off0 = (int64_t)chunk * ge.chunk_stride + (int64_t)slab * kSlabBytes;
+        const int64_t left = ge.copy_bytes - (int64_t)slab * kSlabBytes;    // bytes of this chunk from the slab start
 
         vec16 v[kVecPerThread];
-        const char* s = src + (int64_t)src_row * row_stride + off0;
+        const char* s = src + (int64_t)src_row * ge.row_stride + off0;
 #pragma unroll
         for (int u = 0; u < kVecPerThread; ++u) {
             const int64_t o = ((int64_t)u * kGatherThreads + tid) * 16;
@@ -134,7 +163,8 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(
                 const int j = __ffsll((long long)bits) - 1;
                 bits &= bits - 1;
                 const int drow = row0 + mw * 64 + j;
-                char* d = (parity[drow] ? baseA : baseB) + (int64_t)drow * row_stride + off0;   // its inactive buffer
+                // the plan has already flipped the parity of moved rows: it names the buffer to write
+                char* d = (parity[drow] ? baseB : baseA) + (int64_t)drow * ge.row_stride + off0;
 #pragma unroll
                 for (int u = 0; u < kVecPerThread; ++u) {
                     const int64_t o = ((int64_t)u * kGatherThreads + tid) * 16;
@@ -148,44 +178,20 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(
     }
 }
 
-// After the gathers: cumulative log p follows its particle, parity flips, the plan is cleared.
-__global__ __launch_bounds__(kWave) void commit_kernel(const int32_t* __restrict__ anc, const int32_t* __restrict__ resampled,
-                                                       int N, double* __restrict__ cumlogp, int32_t* __restrict__ done,
-                                                       int32_t* __restrict__ parity, GatherPlan* __restrict__ plan)
-{
-    __shared__ double sh[SMC_MAX_PARTICLES];
-    __shared__ int32_t sh_done[SMC_MAX_PARTICLES];
-    const int b = blockIdx.x, lane = threadIdx.x;
-    if (b == 0 && lane == 0) plan->n_groups = 0;
-    if (!resampled[b]) return;
-    const int row0 = b * N;
-    for (int k = lane; k < N; k += kWave) { sh[k] = cumlogp[row0 + k]; sh_done[k] = done[row0 + k]; }
-    __syncthreads();
-    for (int k = lane; k < N; k += kWave) {
-        const int a = anc[row0 + k] - row0;
-        if (a >= 0 && a < N && a != k) {
-            cumlogp[row0 + k] = sh[a]; done[row0 + k] = sh_done[a];
-            parity[row0 + k] ^= 1;                                 // the row now lives in the buffer just written
-        }
-    }
-}
-
 template <int VPT, bool NT_LD, bool NT_ST>
-static void launch_gather(smc_ctx* c, void* const* bufA, void* const* bufB, int n_tensors, int n_chunks, int64_t row_stride,
-                          int64_t chunk_stride, int64_t copy_bytes)
+static void launch_gather(smc_ctx* c, GatherGeom kv, GatherGeom hist)
 {
     constexpr int64_t slab = (int64_t)kGatherThreads * VPT * 16;
-    const int slabs = (int)((copy_bytes + slab - 1) / slab);
+    kv.slabs_per_chunk = (int)((kv.copy_bytes + slab - 1) / slab);
+    hist.slabs_per_chunk = (int)((hist.copy_bytes + slab - 1) / slab);
     auto& w = c->ws;
-    hipLaunchKernelGGL((gather_kernel<VPT, NT_LD, NT_ST>), dim3(c->gather_grid), dim3(kGatherThreads), 0, c->stream, bufA, bufB,
-                       w.parity, c->cfg.N, n_tensors, n_chunks, row_stride, chunk_stride, copy_bytes, slabs, c->mask_words,
-                       w.plan, w.grp_src, w.grp_base, w.grp_mask);
+    hipLaunchKernelGGL((gather_kernel<VPT, NT_LD, NT_ST>), dim3(c->gather_grid), dim3(kGatherThreads), 0, c->stream, kv, hist,
+                       w.parity, c->mask_words, c->plan_phase, w.plan, w.grp_src, w.grp_base, w.grp_srcpar, w.grp_mask);
 }
 
-static void launch_gather_variant(smc_ctx* c, int variant, void* const* bufA, void* const* bufB, int n_tensors, int n_chunks,
-                                  int64_t row_stride, int64_t chunk_stride, int64_t copy_bytes)
+static void launch_gather_variant(smc_ctx* c, int variant, const GatherGeom& kv, const GatherGeom& hist)
 {
-#define PSMC_G(V, L, S) launch_gather<V, L, S>(c, bufA, bufB, n_tensors, n_chunks, row_stride, chunk_stride, copy_bytes)
+#define PSMC_G(V, L, S) launch_gather<V, L, S>(c, kv, hist)
     switch (variant) {
         case 0: PSMC_G(8, true, true); break;
         case 1: PSMC_G(8, false, true); break;
@@ -198,7 +204,7 @@ static void launch_gather_variant(smc_ctx* c, int variant, void* const* bufA, vo
         case 8: PSMC_G(16, false, false); break;
         case 9: PSMC_G(2, true, true); break;
         case 10: PSMC_G(2, false, false); break;
-        default: PSMC_G(8, true, true); break;
+        default: PSMC_G(4, false, true); break;
     }
 #undef PSMC_G
 }
@@ -209,30 +215,33 @@ hipError_t launch_reindex(smc_ctx* c, const int32_t* anc, const int32_t* resampl
     auto& w = c->ws;
     const bool have_kv = c->kv_bound && cfg.kv_tensors > 0 && valid_len > 0;
     const bool have_hist = c->hist_bound && t > 0;
+    c->plan_phase ^= 1;
+    hipLaunchKernelGGL(plan_kernel, dim3(cfg.B), dim3(kWave), 0, c->stream, anc, resampled, cfg.N, c->mask_words,
+                       c->plan_phase, w.plan, w.grp_src, w.grp_base, w.grp_srcpar, w.grp_mask, w.cumlogp, w.done, w.parity);
     if (have_kv || have_hist) {
-        hipLaunchKernelGGL(plan_kernel, dim3(cfg.B), dim3(kWave), 0, c->stream, anc, resampled, cfg.N, c->mask_words,
-                           w.plan, w.grp_src, w.grp_base, w.grp_mask);
-    }
-    if (have_kv) {
-        const int64_t pos_bytes = (int64_t)cfg.kv_D * cfg.kv_elem_bytes;
-        const int64_t head_stride = (int64_t)cfg.kv_S * pos_bytes;
-        const int64_t row_stride = head_stride * cfg.kv_H;
-        int n_chunks = cfg.kv_H;
-        int64_t copy_bytes = (int64_t)valid_len * pos_bytes;
-        if (valid_len == cfg.kv_S) { n_chunks = 1; copy_bytes = row_stride; }       // whole row is contiguous
+        GatherGeom kv{}, hist{};
+        if (have_kv) {
+            const int64_t pos_bytes = (int64_t)cfg.kv_D * cfg.kv_elem_bytes;
+            const int64_t head_stride = (int64_t)cfg.kv_S * pos_bytes;
+            kv.bufA = (void* const*)w.kvA; kv.bufB = (void* const*)w.kvB;
+            kv.n_tensors = cfg.kv_tensors;
+            kv.row_stride = head_stride * cfg.kv_H;
+            kv.chunk_stride = head_stride;
+            kv.n_chunks = cfg.kv_H;
+            kv.copy_bytes = (int64_t)valid_len * pos_bytes;
+            if (valid_len == cfg.kv_S) { kv.n_chunks = 1; kv.copy_bytes = kv.row_stride; }   // whole row is contiguous
+        }
+        if (have_hist) {
+            hist.bufA = (void* const*)w.histAB; hist.bufB = (void* const*)(w.histAB + 1);
+            hist.n_tensors = 1; hist.n_chunks = 1;
+            hist.row_stride = (int64_t)cfg.T_max * 4;
+            hist.chunk_stride = hist.row_stride;
+            hist.copy_bytes = (((int64_t)t * 4) + 15) & ~15ll;                              // whole 16-byte vectors
+            if (hist.copy_bytes > hist.row_stride) hist.copy_bytes = hist.row_stride;
+        }
         ScopedKernelTimer timer(c, 1);
-        launch_gather_variant(c, c->gather_variant, (void* const*)w.kvA, (void* const*)w.kvB, cfg.kv_tensors, n_chunks,
-                              row_stride, head_stride, copy_bytes);
+        launch_gather_variant(c, c->gather_variant, kv, hist);
     }
-    if (have_hist) {
-        const int64_t row_stride = (int64_t)cfg.T_max * 4;
-        int64_t copy_bytes = (((int64_t)t * 4) + 15) & ~15ll;                       // whole 16-byte vectors
-        if (copy_bytes > row_stride) copy_bytes = row_stride;
-        launch_gather<4, false, false>(c, (void* const*)w.histAB, (void* const*)(w.histAB + 1), 1, 1, row_stride, row_stride,
-                                       copy_bytes);
-    }
-    hipLaunchKernelGGL(commit_kernel, dim3(cfg.B), dim3(kWave), 0, c->stream, anc, resampled, cfg.N, w.cumlogp, w.done, w.parity,
-                       w.plan);
     return hipGetLastError();
 }
 

@@ -54,6 +54,7 @@ size_t layout(const smc_config* c, char* base, Workspace* w)
     p = take(sizeof(GatherPlan)); if (w) w->plan = (GatherPlan*)p;
     p = take(R * 4); if (w) w->grp_src = (int32_t*)p;
     p = take(R * 4); if (w) w->grp_base = (int32_t*)p;
+    p = take(R * 4); if (w) w->grp_srcpar = (int32_t*)p;
     p = take(R * mask_words * 8); if (w) w->grp_mask = (unsigned long long*)p;
     p = take((size_t)(c->kv_tensors > 0 ? c->kv_tensors : 1) * sizeof(void*)); if (w) w->kvA = (void**)p;
     p = take((size_t)(c->kv_tensors > 0 ? c->kv_tensors : 1) * sizeof(void*)); if (w) w->kvB = (void**)p;
@@ -122,6 +123,7 @@ smc_status smc_init(const smc_config* cfg, void* d_workspace, size_t workspace_b
     c->dense = 0;
     c->mask_words = (cfg->N + 63) / 64;
     c->resampler = 0;
+    c->plan_phase = 0;
     c->kv_bound = 0;
     c->hist_bound = 0;
     c->profiling = 0;

@@ -33,9 +33,9 @@ static_assert(sizeof(Partial) == 48, "Partial layout");
 
 // Groups of rows that share one ancestor, built by the plan kernel for the gather kernels.
 struct GatherPlan {
-    int32_t n_groups;             // number of (ancestor, descendants) groups over all resampled prompts
+    int32_t n_groups[2];          // number of (ancestor, descendants) groups; successive calls alternate the counter
     int32_t bad_anc;              // ancestors outside their prompt's row range (ignored rows)
-    int32_t pad[2];
+    int32_t pad;
 };
 
 struct Workspace {                // device pointers carved out of the caller's workspace
@@ -53,6 +53,7 @@ struct Workspace {                // device pointers carved out of the caller's 
     GatherPlan* plan;
     int32_t* grp_src;             // [R] ancestor row of each group
     int32_t* grp_base;            // [R] first row of the group's prompt
+    int32_t* grp_srcpar;          // [R] which buffer held the ancestor's live row when the plan was made
     unsigned long long* grp_mask; // [R * mask_words] descendants of each group as a bit set over the prompt's rows
     void** kvA;                   // [kv_tensors]
     void** kvB;                   // [kv_tensors]
@@ -74,6 +75,7 @@ struct smc_ctx {
     int kv_bound;
     int hist_bound;
     int gather_grid;              // workgroups of the persistent gather kernel
+    int plan_phase;               // which group counter the current reindex uses
     int gather_variant;           // vectors per thread / non-temporal choice of the gather kernel
     int n_cus;
     // optional per-kernel timing: event pairs recorded around launches of kind 0 (vocab pass) and 1 (KV gather)
