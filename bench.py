@@ -45,20 +45,23 @@ def cpu_baseline(w, seed, gpu_resample_frac):
     from paper_2602_10273_amd import synth
 
     threads = orc.threads()
-    o = orc.OracleSMC(w.B, w.N, w.V, 8, w.kappa, seed, w.dtype)
-    n_steps = 2 if w.R * w.V > 1e8 else 3
-    x = [synth.logits_torch(w, 1000 + i, seed, device="cpu") for i in range(n_steps)]
+    o = orc.OracleSMC(w.B, w.N, w.V, 4096, w.kappa, seed, w.dtype)
+    n_buf = 2 if w.R * w.V > 1e8 else 3
+    x = [synth.logits_torch(w, 1000 + i, seed, device="cpu") for i in range(n_buf)]
     if w.dtype == "bf16":
         import torch
         x = [t.view(torch.int16).numpy().view(np.uint16) for t in x]
     else:
         x = [t.numpy() for t in x]
+    # full-width steps on all rows until about 10 s of CPU work have been timed (at least 3 steps)
     t0 = time.perf_counter()
-    n_res = 0
-    for i in range(n_steps):
-        o.step(x[i], i + 1, w.alpha_at(i + 1), w.alpha_at(i), -1.0)
+    n_res = n_steps = 0
+    while n_steps < 3 or (time.perf_counter() - t0 < 10.0 and n_steps < 4000):
+        i = n_steps
+        o.step(x[i % n_buf], i + 1, w.alpha_at(i + 1), w.alpha_at(i), -1.0)
         _, flag, _ = o.resample(i + 1)
         n_res += int(flag.sum())
+        n_steps += 1
     t_step = (time.perf_counter() - t0) / n_steps
     # KV gather: one prompt (N rows) of a few tensors, timed and scaled linearly to all tensors
     n_t = max(1, min(w.kv_tensors, int(1.5e9 // (w.N * w.kv_row_bytes))))
