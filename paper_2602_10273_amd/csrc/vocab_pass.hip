@@ -408,11 +408,7 @@ __global__ __launch_bounds__(NW * kWave) void vocab_pass_kernel(
             }
             vm = wave_max_f32(vm);
             if (vm > m) raise_max(vm);
-            if constexpr (!DENSE) {
-                publish();
-                __syncthreads();     // reached by every wave: the loop bounds are the same for the whole workgroup
-                adopt();
-            }
+            if constexpr (!DENSE) { publish(); adopt(); }      // no waiting: whatever the other waves have found so far
             PSMC_STAMP(1);
         }
 #pragma unroll
@@ -587,13 +583,14 @@ hipError_t launch_vocab_pass(smc_ctx* c, const void* logits, int64_t row_stride,
     // 4 waves when rows alone fill the chip
     const int nw = c->wg_waves;
     const int threads = nw * kWave;
-    // split a row into n_split contiguous runs of whole "tiles" (one vector per thread)
+    // split a row into n_split contiguous runs of vectors
     int n_split = c->n_split;
     const int tiles = (nvec + threads - 1) / threads;
     if (n_split > tiles) n_split = tiles;
-    const int tiles_per_split = (tiles + n_split - 1) / n_split;
-    n_split = (tiles + tiles_per_split - 1) / tiles_per_split;
-    const int vecs_per_split = tiles_per_split * threads;
+    // equal shares at vector granularity (whole wave-widths), so that no slice of a row is a tile longer than another
+    int vecs_per_split = (nvec + n_split - 1) / n_split;
+    vecs_per_split = (vecs_per_split + kWave - 1) / kWave * kWave;
+    n_split = (nvec + vecs_per_split - 1) / vecs_per_split;
 
     hipError_t e;
     const float betaf = (float)beta;
