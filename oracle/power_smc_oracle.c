@@ -252,11 +252,32 @@ void orc_resample_scheme(const double* w, int32_t N, int32_t scheme, uint64_t se
     }
 }
 
+/* Survivors stay in place: a permutation of the ancestor vector A (same multiset of ancestors) in which every
+ * distinct ancestor j keeps slot j.  After resampling all weights are equal and nothing in Alg. 1 depends on a
+ * particle's index, so the particle system is the same; only the slots that really change owner have to be copied.
+ * Rule: each distinct ancestor takes its own slot; the remaining copies, in the order they occur in A (the first
+ * occurrence of each ancestor is the one that stayed), fill the free slots in increasing order. */
+void orc_survivors_in_place(const int32_t* A, int32_t N, int32_t* out)
+{
+    int32_t seen[N];
+    for (int32_t k = 0; k < N; ++k) { out[k] = -1; seen[k] = 0; }
+    for (int32_t i = 0; i < N; ++i) out[A[i]] = A[i];
+    int32_t free_slot = 0;
+    for (int32_t i = 0; i < N; ++i) {
+        int32_t a = A[i];
+        if (!seen[a]) { seen[a] = 1; continue; }
+        while (out[free_slot] != -1) ++free_slot;
+        out[free_slot] = a;
+    }
+}
+
 /* Step a4 for B prompts: trigger ESS < kappa*N (strict), ancestors by the chosen scheme (0 = the paper's
  * systematic resampling) as global row indices, weights of resampled prompts reset to 1 (logW = 0).
- * Prompts that do not resample get the identity.  scratch_w: 2N doubles. */
+ * Prompts that do not resample get the identity.  scratch_w: 2N doubles.  in_place != 0 reorders each ancestor
+ * vector with orc_survivors_in_place. */
 void orc_resample(double* logW, int32_t B, int32_t N, double kappa, uint64_t seed, int32_t t,
-                  int32_t* anc, int32_t* resampled, double* ess_out, double* scratch_w, int32_t scheme)
+                  int32_t* anc, int32_t* resampled, double* ess_out, double* scratch_w, int32_t scheme,
+                  int32_t in_place)
 {
     for (int32_t b = 0; b < B; ++b) {
         double* lw = logW + (int64_t)b * N;
@@ -265,9 +286,10 @@ void orc_resample(double* logW, int32_t B, int32_t N, double kappa, uint64_t see
         double ess = exp(2.0 * L1 - L2);
         if (ess_out) ess_out[b] = ess;
         if (ess < kappa * (double)N) {
-            int32_t A[N];
+            int32_t A[N], P[N];
             for (int32_t i = 0; i < N; ++i) scratch_w[i] = exp(lw[i] - L1);
             orc_resample_scheme(scratch_w, N, scheme, seed, t, b, A, scratch_w + N);
+            if (in_place) { orc_survivors_in_place(A, N, P); for (int32_t i = 0; i < N; ++i) A[i] = P[i]; }
             for (int32_t i = 0; i < N; ++i) { anc[(int64_t)b * N + i] = b * N + A[i]; lw[i] = 0.0; }
             resampled[b] = 1;
         } else {

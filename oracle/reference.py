@@ -112,7 +112,15 @@ def resample_scheme(w, scheme, seed, t, b):
     return A
 
 
-def resample(logW, B, N, kappa, seed, t, scheme=0):
+def survivors_in_place(A):
+    """The permutation of an ancestor vector (local indices) in which every distinct ancestor keeps its own slot."""
+    A = np.ascontiguousarray(A, np.int32)
+    out = np.empty_like(A)
+    lib().orc_survivors_in_place(_p(A), C.c_int32(A.size), _p(out))
+    return out
+
+
+def resample(logW, B, N, kappa, seed, t, scheme=0, in_place=False):
     """Returns (anc[R] global rows, resampled[B], ess[B], logW after reset)."""
     lw = np.array(logW, dtype=np.float64).copy()
     anc = np.empty(B * N, np.int32)
@@ -120,7 +128,8 @@ def resample(logW, B, N, kappa, seed, t, scheme=0):
     e = np.empty(B, np.float64)
     scratch = np.empty(2 * N, np.float64)
     lib().orc_resample(_p(lw), C.c_int32(B), C.c_int32(N), C.c_double(kappa), C.c_uint64(int(seed)),
-                       C.c_int32(t), _p(anc), _p(flag), _p(e), _p(scratch), C.c_int32(SCHEMES.get(scheme, scheme)))
+                       C.c_int32(t), _p(anc), _p(flag), _p(e), _p(scratch), C.c_int32(SCHEMES.get(scheme, scheme)),
+                       C.c_int32(1 if in_place else 0))
     return anc, flag, e, lw
 
 
@@ -146,7 +155,8 @@ def gather_kv(src, anc, resampled, N, valid_len, dst=None):
 class OracleSMC:
     """Algorithm 1 for B independent prompts, state held in fp64 / numpy, one call per step of the path."""
 
-    def __init__(self, B, N, V, T_max, kappa, seed, dtype="f32", kv=None, eos_id=-1, scheme="systematic"):
+    def __init__(self, B, N, V, T_max, kappa, seed, dtype="f32", kv=None, eos_id=-1, scheme="systematic",
+                 in_place=False):
         self.B, self.N, self.V, self.T_max, self.R = B, N, V, T_max, B * N
         self.kappa, self.seed, self.dtype = float(kappa), int(seed), dtype
         self.logW = np.zeros(self.R, np.float64)          # Alg. 1: W~_0 = 1
@@ -155,6 +165,7 @@ class OracleSMC:
         self.kv = kv                                      # list of [R,H,S,D] arrays or None
         self.log_Zhat = np.zeros(B, np.float64)           # running log of the normalising-constant estimate
         self.scheme = scheme                              # resampling scheme (App. E); the paper uses systematic
+        self.in_place = bool(in_place)                    # survivors keep their slot (same particle system)
         self.eos_id = int(eos_id)                         # -1: EOS is not special
         self.done = np.zeros(self.R, np.int32)            # Alg. 1 termination flags
 
@@ -178,7 +189,7 @@ class OracleSMC:
     def resample(self, t):
         """a4; also accumulates log Zhat += L1 - log N for prompts that resample."""
         L1 = np.array([logsumexp(self.logW[b * self.N:(b + 1) * self.N]) for b in range(self.B)])
-        anc, flag, e, lw = resample(self.logW, self.B, self.N, self.kappa, self.seed, t, self.scheme)
+        anc, flag, e, lw = resample(self.logW, self.B, self.N, self.kappa, self.seed, t, self.scheme, self.in_place)
         self.log_Zhat += np.where(flag != 0, L1 - np.log(self.N), 0.0)
         self.logW = lw
         return anc, flag, e

@@ -88,3 +88,50 @@ def test_normalising_constant_unbiased_under_each_scheme(scheme):
     z = np.exp(o.log_Z_estimate() - log_Z)
     se = z.std(ddof=1) / np.sqrt(B)
     assert n_res > B // 20 and abs(z.mean() - 1.0) < 4 * se and se < 0.05
+
+
+def test_survivors_in_place_is_a_permutation_that_fixes_every_ancestor():
+    rng = np.random.default_rng(7)
+    for N in (1, 2, 5, 8, 33, 64):
+        for _ in range(60):
+            A = rng.integers(0, N, N).astype(np.int32)
+            if rng.random() < 0.5:
+                A = np.sort(A)
+            P = orc.survivors_in_place(A)
+            assert sorted(P) == sorted(A)                                   # same multiset of ancestors
+            for j in np.unique(A):
+                assert P[j] == j                                            # every survivor keeps its slot
+            assert (P != np.arange(N)).sum() == N - len(np.unique(A))       # the fewest possible slots change owner
+            # the copies that move keep the order in which they occur in A
+            extra, seen = [], set()
+            for a in A:
+                if a in seen:
+                    extra.append(a)
+                seen.add(a)
+            assert [P[k] for k in range(N) if P[k] != k] == extra
+    assert list(orc.survivors_in_place(np.arange(6, dtype=np.int32))) == list(range(6))
+    assert list(orc.survivors_in_place(np.array([3, 3, 3, 3], np.int32))) == [3, 3, 3, 3]
+    assert list(orc.survivors_in_place(np.array([0, 0, 2, 2, 2, 5], np.int32))) == [0, 0, 2, 2, 2, 5]
+    assert list(orc.survivors_in_place(np.array([1, 1, 1, 4, 4, 4], np.int32))) == [1, 1, 1, 4, 4, 4]
+    assert list(orc.survivors_in_place(np.array([2, 2, 3, 3, 3, 3], np.int32))) == [2, 3, 2, 3, 3, 3]
+
+
+def test_normalising_constant_unbiased_with_survivors_in_place():
+    _, _, log_Z = enumerate_power_target(TABLE, W1.steps, W1.alpha)
+    T, a = W1.steps, W1.alpha
+    B = 20000
+    w = synth.scaled(W1, B=B)
+    o = orc.OracleSMC(B, W1.N, w.V, T, 0.5, 43, "f32", in_place=True)
+    n_res = 0
+    for t in range(1, T + 1):
+        prev = np.zeros(w.R, np.int64) if t == 1 else o.hist[:, t - 2]
+        o.step(synth.logits_numpy(w, t, 0, prev_tokens=prev, table=TABLE), t, a, a)
+        anc, flag, _ = o.resample(t)
+        for b in np.nonzero(flag)[0][:50]:
+            loc = anc[b * W1.N:(b + 1) * W1.N] - b * W1.N
+            assert all(loc[j] == j for j in np.unique(loc))
+        o.reindex(anc, flag, 0, t)
+        n_res += int(flag.sum())
+    z = np.exp(o.log_Z_estimate() - log_Z)
+    se = z.std(ddof=1) / np.sqrt(B)
+    assert n_res > B // 20 and abs(z.mean() - 1.0) < 4 * se and se < 0.05
