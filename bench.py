@@ -34,6 +34,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kv", action="store_true", help="vocabulary pass + weights only (no cache bound)")
     ap.add_argument("--n-split", type=int, default=0)
+    ap.add_argument("--in-place", action="store_true",
+                    help="ancestor order 1: surviving ancestors keep their slot, only the other copies move")
     return ap.parse_args()
 
 
@@ -107,6 +109,8 @@ def main():
     s = Session(w.B, w.N, w.V, T_max, w.dtype, w.kappa, args.seed, kv_geom=kv_geom)
     if args.n_split:
         smc.smc_set_tuning(s.ctx, args.n_split, 0)
+    if args.in_place:
+        smc.smc_set_ancestor_order(s.ctx, 1)
     if not args.no_kv:
         g = torch.Generator(device=dev); g.manual_seed(args.seed + 12345)
         for t in s.kvA:
@@ -200,7 +204,7 @@ def main():
         "ms_per_step": elapsed / K * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "N": w.N, "V": w.V, "logits_dtype": w.dtype, "alpha": w.alpha,
-                   "kappa": w.kappa, "kv": None if args.no_kv else f"{w.layers}x2 tensors [{w.R},{w.H},{w.S},{w.D}] bf16 x2 buffers",
+                   "kappa": w.kappa, "ancestor_order": "survivors-in-place" if args.in_place else "as-drawn", "kv": None if args.no_kv else f"{w.layers}x2 tensors [{w.R},{w.H},{w.S},{w.D}] bf16 x2 buffers",
                    "valid_len": w.S, "resampled_prompt_fraction": resample_frac,
                    "logits_ring": n_ring},
         "roofline": dominant, "roofline_other": other,

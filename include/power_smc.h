@@ -116,6 +116,16 @@ smc_status smc_resample(smc_ctx* ctx, int32_t t, int32_t* d_anc_out, int32_t* d_
  * residual weights. */
 smc_status smc_set_resampler(smc_ctx* ctx, int32_t scheme);
 
+/* Order of the ancestor vector that smc_resample / smc_resample_from return: 0 = as drawn (default), 1 = survivors
+ * stay in place.  After resampling every weight is 1 and nothing in Alg. 1 depends on a particle's index, so any
+ * permutation of a prompt's ancestor vector describes the same particle system (the App. C reorder only has to
+ * realise the multiset).  Order 1 returns the permutation in which every distinct ancestor j keeps slot j; the
+ * remaining copies, in the order in which they were drawn (the first occurrence of each ancestor is the one that
+ * stayed), fill the free slots in increasing order.  Then exactly N - #distinct rows change owner and
+ * smc_kv_reindex copies only those.  Tokens drawn afterwards differ from order 0 (the random stream is keyed by row
+ * slot) but have the same law. */
+smc_status smc_set_ancestor_order(smc_ctx* ctx, int32_t order);
+
 /* a5: for every prompt b with d_resampled[b] != 0 and every row k of it with d_anc[k] != k, copies the live row
  * d_anc[k] into the inactive buffer of row k -- the first valid_len (0..kv_S) positions of every head of every KV
  * tensor, the first t columns of the history -- gathers cumulative log p and the termination flags the same way,

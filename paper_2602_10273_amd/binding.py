@@ -16,7 +16,7 @@ STATUS = {0: "SMC_OK", 1: "SMC_E_NULL", 2: "SMC_E_SHAPE", 3: "SMC_E_DTYPE", 4: "
 
 EXPORTS = ["smc_workspace_bytes", "smc_init", "smc_destroy", "smc_kv_bind", "smc_step", "smc_ess", "smc_resample",
            "smc_kv_reindex", "smc_final_draw", "smc_get_done", "smc_set_done", "smc_ess_from", "smc_resample_from", "smc_get_state", "smc_set_state", "smc_get_diag",
-           "smc_set_tuning", "smc_set_resampler", "smc_set_gather_tuning", "smc_profile_enable", "smc_profile_read", "smc_status_str"]
+           "smc_set_tuning", "smc_set_resampler", "smc_set_ancestor_order", "smc_set_gather_tuning", "smc_profile_enable", "smc_profile_read", "smc_status_str"]
 
 
 class smc_config(C.Structure):
@@ -62,6 +62,7 @@ def lib():
         L.smc_get_diag.argtypes = [vp, vp, vp, vp, vp, vp, vp]
         L.smc_set_tuning.argtypes = [vp, i32, i32, i32]
         L.smc_set_resampler.argtypes = [vp, i32]
+        L.smc_set_ancestor_order.argtypes = [vp, i32]
         L.smc_set_gather_tuning.argtypes = [vp, i32, i32]
         L.smc_profile_enable.argtypes = [vp, i32]
         L.smc_profile_read.argtypes = [vp, i32, C.POINTER(f64), C.POINTER(i64)]
@@ -176,6 +177,10 @@ def smc_set_tuning(ctx, n_split=0, dense=0, wg_waves=0):
 
 def smc_set_resampler(ctx, scheme=0):
     _check("smc_set_resampler", lib().smc_set_resampler(ctx, scheme))
+
+
+def smc_set_ancestor_order(ctx, order=0):
+    _check("smc_set_ancestor_order", lib().smc_set_ancestor_order(ctx, order))
 
 
 def smc_set_gather_tuning(ctx, wgs_per_cu=8, variant=0):

@@ -123,6 +123,7 @@ smc_status smc_init(const smc_config* cfg, void* d_workspace, size_t workspace_b
     c->dense = 0;
     c->mask_words = (cfg->N + 63) / 64;
     c->resampler = 0;
+    c->ancestor_order = 0;
     c->plan_phase = 0;
     c->kv_bound = 0;
     c->hist_bound = 0;
@@ -302,6 +303,14 @@ smc_status smc_set_resampler(smc_ctx* ctx, int32_t scheme)
     if (!ctx) return SMC_E_NULL;
     if (scheme < 0 || scheme > 3) return SMC_E_RANGE;
     ctx->resampler = scheme;
+    return SMC_OK;
+}
+
+smc_status smc_set_ancestor_order(smc_ctx* ctx, int32_t order)
+{
+    if (!ctx) return SMC_E_NULL;
+    if (order < 0 || order > 1) return SMC_E_RANGE;
+    ctx->ancestor_order = order;
     return SMC_OK;
 }
 

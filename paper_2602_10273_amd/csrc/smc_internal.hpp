@@ -72,6 +72,7 @@ struct smc_ctx {
     int wg_waves;                 // waves per workgroup of the vocabulary pass: 4 or 16
     int mask_words;               // 64-bit words per descendant bit set = ceil(N/64)
     int resampler;                // 0 systematic (the paper's), 1 stratified, 2 multinomial, 3 residual
+    int ancestor_order;           // 0 as drawn, 1 survivors stay in place
     int kv_bound;
     int hist_bound;
     int gather_grid;              // workgroups of the persistent gather kernel

@@ -72,7 +72,7 @@ __device__ __forceinline__ double resampling_uniform(uint32_t i, uint32_t b, uin
 // (A_i = min{ j : C_j >= (u_0 + i)/N }); 1 stratified ((u_i + i)/N), 2 multinomial (u_i), 3 residual
 // (floor(N w_j) copies, the rest multinomial on the residual weights) are the alternatives App. E names.
 __global__ __launch_bounds__(kWave) void resample_kernel(double* __restrict__ logW, int N, double kappa, uint32_t key0,
-                                                         uint32_t key1, uint32_t step, int scheme,
+                                                         uint32_t key1, uint32_t step, int scheme, int order,
                                                          int32_t* __restrict__ anc, int32_t* __restrict__ resampled,
                                                          double* __restrict__ ess_out)
 {
@@ -134,6 +134,28 @@ __global__ __launch_bounds__(kWave) void resample_kernel(double* __restrict__ lo
     }
     __syncthreads();
     for (int i = lane; i < N; i += kWave) lw[i] = 0.0;
+    if (order == 1) {
+        // Survivors stay in place: every distinct ancestor keeps its own slot, the other copies fill the free slots
+        // in increasing order, in the order in which they were drawn.  One lane, O(N); the weight arrays are free now.
+        int32_t* slot = reinterpret_cast<int32_t*>(sh_a);
+        int32_t* seen = reinterpret_cast<int32_t*>(sh_b);
+        const int base = b * N;
+        for (int i = lane; i < N; i += kWave) { slot[i] = -1; seen[i] = 0; }
+        __syncthreads();
+        for (int i = lane; i < N; i += kWave) { const int a = A[i] - base; slot[a] = a; }
+        __syncthreads();
+        if (lane == 0) {
+            int free_slot = 0;
+            for (int i = 0; i < N; ++i) {
+                const int a = A[i] - base;
+                if (!seen[a]) { seen[a] = 1; continue; }
+                while (slot[free_slot] != -1) ++free_slot;
+                slot[free_slot] = a;
+            }
+        }
+        __syncthreads();
+        for (int i = lane; i < N; i += kWave) A[i] = base + slot[i];
+    }
 }
 
 // Output of Alg. 1: I ~ Categorical(W) by inversion of the running sum of the normalised weights (particle order).
@@ -192,7 +214,8 @@ hipError_t launch_ess(smc_ctx* c, const double* logW, double* ess_out, double* l
 hipError_t launch_resample(smc_ctx* c, double* logW, int t, int32_t* anc, int32_t* resampled, double* ess_out)
 {
     hipLaunchKernelGGL(resample_kernel, dim3(c->cfg.B), dim3(kWave), 0, c->stream, logW, c->cfg.N, c->cfg.kappa,
-                       (uint32_t)c->cfg.seed, (uint32_t)(c->cfg.seed >> 32), (uint32_t)t, c->resampler, anc, resampled, ess_out);
+                       (uint32_t)c->cfg.seed, (uint32_t)(c->cfg.seed >> 32), (uint32_t)t, c->resampler, c->ancestor_order, anc,
+                       resampled, ess_out);
     return hipGetLastError();
 }
 

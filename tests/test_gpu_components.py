@@ -148,6 +148,31 @@ def test_other_resampling_schemes_match_oracle(scheme):
         s.close()
 
 
+@pytest.mark.parametrize("scheme", ["systematic", "stratified", "multinomial", "residual"])
+def test_survivors_in_place_order_matches_oracle(scheme):
+    from paper_2602_10273_amd import binding as smc
+    rng = np.random.default_rng(6)
+    for (B, N) in [(5, 1), (6, 8), (4, 64), (3, 100), (2, 1024)]:
+        kappa = 1.0                                                         # every prompt with N > 1 resamples
+        s = Session(B, N, 64, 8, "f32", kappa, seed=78, with_hist=False)
+        smc.smc_set_resampler(s.ctx, orc.SCHEMES[scheme])
+        smc.smc_set_ancestor_order(s.ctx, 1)
+        for scale in (0.3, 2.0, 10.0):
+            logW = rng.standard_normal(B * N) * scale
+            d = torch.as_tensor(logW).cuda()
+            smc.smc_resample_from(s.ctx, d, 3, s.anc, s.resampled, s.ess)
+            anc_ref, flag_ref, _, lw_ref = orc.resample(logW, B, N, kappa, 78, 3, scheme, in_place=True)
+            anc = s.anc.cpu().numpy()
+            assert np.array_equal(s.resampled.cpu().numpy(), flag_ref)
+            assert np.array_equal(anc, anc_ref)
+            for b in range(B):
+                loc = anc[b * N:(b + 1) * N] - b * N
+                assert all(loc[j] == j for j in np.unique(loc))
+        with pytest.raises(Exception):
+            smc.smc_set_ancestor_order(s.ctx, 2)
+        s.close()
+
+
 def test_resample_degenerate_weights():
     from paper_2602_10273_amd import binding as smc
     B, N = 3, 8

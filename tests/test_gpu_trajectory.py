@@ -39,14 +39,18 @@ def _ambiguous_resample(o, lnw, t):
     return out
 
 
-def run_lockstep(w, seed, steps, tau=-1.0, table=None, grow_kv=True, kv_seed=3, eos_id=-1):
+def run_lockstep(w, seed, steps, tau=-1.0, table=None, grow_kv=True, kv_seed=3, eos_id=-1, in_place=False):
     kv = synth.kv_numpy(w, kv_seed)
     T_max = (steps + 3) // 4 * 4
     s = Session(w.B, w.N, w.V, T_max, w.dtype, w.kappa, seed, kv=kv, eos_id=eos_id)
-    o = orc.OracleSMC(w.B, w.N, w.V, T_max, w.kappa, seed, w.dtype, kv=[k.copy() for k in kv], eos_id=eos_id)
+    if in_place:
+        from paper_2602_10273_amd import binding as smc
+        smc.smc_set_ancestor_order(s.ctx, 1)
+    o = orc.OracleSMC(w.B, w.N, w.V, T_max, w.kappa, seed, w.dtype, kv=[k.copy() for k in kv], eos_id=eos_id,
+                      in_place=in_place)
     kv_rng = np.random.default_rng([seed, 99])
     stats = dict(token_ties=0, ess_band=0, pos_band=0, resamples=0, steps=0, max_dw=0.0, max_dess=0.0, done=0,
-                 draw_band=0)
+                 draw_band=0, rows_moved=0)
     for t in range(1, steps + 1):
         if table is not None:
             prev = np.zeros(w.R, np.int64) if t == 1 else o.hist[:, t - 2]
@@ -87,6 +91,7 @@ def run_lockstep(w, seed, steps, tau=-1.0, table=None, grow_kv=True, kv_seed=3, 
                 assert near[b], (t, b, anc[sl], anc_ref[sl])
                 stats["pos_band"] += 1; dirty = True
         stats["resamples"] += int(flag_ref.sum())
+        stats["rows_moved"] += int((anc_ref != np.arange(w.R)).sum())
 
         valid = min(t, w.S) if grow_kv else w.S
         if grow_kv and t <= w.S:            # what the decoder does: position t-1 of every live row is appended
@@ -180,3 +185,19 @@ def test_off_optimal_proposal_lockstep():
     w = synth.scaled(synth.WORKLOADS["cfg2"], B=6, N=8, V=3000, layers=1, H=1, S=24, D=64, dtype="f32")
     st = run_lockstep(w, seed=4, steps=24, tau=0.4)
     assert st["resamples"] > 0
+
+
+def test_survivors_in_place_lockstep():
+    """Ancestor order 1: the same particle system with every surviving ancestor left in its slot; fewer rows move."""
+    w = synth.scaled(synth.WORKLOADS["cfg2"], B=16, N=8, V=8200, layers=2, H=2, S=48, D=64)
+    st0 = run_lockstep(w, seed=0, steps=48)
+    st1 = run_lockstep(w, seed=0, steps=48, in_place=True)
+    print(st0, st1)
+    assert st1["resamples"] > 0 and st1["rows_moved"] < st0["rows_moved"]
+    w = synth.scaled(synth.WORKLOADS["cfg5"], B=4, N=64, V=9000, layers=1, H=1, S=32, D=64)
+    st = run_lockstep(w, seed=1, steps=32, in_place=True)
+    assert st["resamples"] > 0
+    w1 = synth.WORKLOADS["cfg1"]
+    table = synth.bigram_table(w1.V, w1.sigma, seed=0)
+    st = run_lockstep(synth.scaled(w1, B=300), 5, w1.steps, table=table, eos_id=3, in_place=True)
+    assert st["resamples"] > 10
