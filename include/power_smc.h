@@ -83,7 +83,8 @@ smc_status smc_destroy(smc_ctx* ctx);
 
 /* Registers the double-buffered caches (App. C).  h_bufA / h_bufB: host arrays of kv_tensors device pointers
  * (16-byte aligned, each tensor [R, kv_H, kv_S, kv_D]); d_histA / d_histB: device int32 [R, T_max] token
- * histories (may both be NULL: no history is kept).  Row k's live data is in buffer A while parity[k] = 0 and in
+ * histories (may both be NULL: no history is kept).  h_bufA and h_bufB may both be NULL: no dense cache is
+ * registered (the cache is paged, see smc_paged_bind, or absent) and only the histories are.  Row k's live data is in buffer A while parity[k] = 0 and in
  * buffer B while parity[k] = 1; smc_kv_reindex reads live buffers, writes the inactive buffer of every row that
  * receives another row's data, and flips the parity of exactly those rows (smc_get_state returns the parities).
  * Synchronous (copies the pointer tables into the workspace). */
@@ -172,9 +173,52 @@ smc_status smc_set_tuning(smc_ctx* ctx, int32_t n_split, int32_t dense, int32_t 
  * the default is 4 workgroups per compute unit and variant 4).  Every setting moves the same bytes. */
 smc_status smc_set_gather_tuning(smc_ctx* ctx, int32_t wgs_per_cu, int32_t variant);
 
-/* Optional timing of the two dominant kernels.  While enabled, a pair of HIP events is recorded on the context's
- * stream around every launch of kind 0 (the vocabulary-pass kernel of smc_step) and kind 1 (the KV gather kernel of
- * smc_kv_reindex).  smc_profile_read synchronises the stream, returns the summed elapsed milliseconds and the number
+/* ---- Paged form of the reorder (Alg. 1 "reorder KV cache by A"; App. C) --------------------------------------
+ * An alternative to smc_kv_bind / smc_kv_reindex for callers whose attention kernels read the cache through a page
+ * table.  Positions are stored in pages of page_len positions; tensor i's pool is an array
+ * [B*Q, kv_H, page_len, kv_D] of kv_elem_bytes elements (smc_paged_pool_bytes each), Q = N*M pages per prompt,
+ * M = ceil(kv_S / page_len) pages per row; prompt b owns pages [b*Q, (b+1)*Q).  The table (int32 [R, M], device)
+ * names the page of row r for positions [j*page_len, (j+1)*page_len), -1 while unused.  The reorder copies page
+ * numbers; descendants of one ancestor share pages until one of them is appended to (copy-on-write).  The logical
+ * content of every row equals what the dense reorder gives.  Rules: a page is free iff no row references it; rows
+ * that need a page take their prompt's free pages in increasing page order, the rows in increasing row order; of
+ * the rows that share the page about to be appended to, the lowest keeps it. */
+
+/* Bytes of device workspace smc_paged_bind needs / bytes of one tensor's pool; 0 if the geometry is invalid
+ * (kv_tensors < 1, page_len outside 1..kv_S, kv_D*kv_elem_bytes not a multiple of 16). */
+size_t smc_paged_workspace_bytes(const smc_config* cfg, int32_t page_len);
+size_t smc_paged_pool_bytes(const smc_config* cfg, int32_t page_len);
+
+/* h_pools: host array of kv_tensors device pointers (16-byte aligned, caller-owned, contents never cleared);
+ * d_workspace: 256-byte aligned device memory of at least smc_paged_workspace_bytes, owned by the caller and used
+ * until smc_destroy.  The table starts in the state that len0 (0..kv_S) appends with no resampling would leave:
+ * table[b*N+k, j] = b*Q + j*N + k for j < ceil(len0/page_len).  Synchronises the stream. */
+smc_status smc_paged_bind(smc_ctx* ctx, void* const* h_pools, int32_t page_len, void* d_workspace,
+                          size_t workspace_bytes, int32_t len0);
+
+/* To be called before the decoder writes position pos (0-based; must equal the number of positions appended so far,
+ * else SMC_E_STATE) of every row: gives every row a page of its own for that position -- a fresh page at a page
+ * start, otherwise a fresh page plus a copy of the pos % page_len positions already filled for every sharer of a
+ * page but the lowest -- and writes d_slot_out int32 [R]: the page of each row; the decoder stores K/V of the new
+ * position at pool[page, h, pos % page_len, :]. */
+smc_status smc_paged_prepare_append(smc_ctx* ctx, int32_t pos, int32_t* d_slot_out);
+
+/* a5 in paged form: for prompts with d_resampled[b] != 0, table[k, :] = old table[d_anc[k], :] over the columns in
+ * use and reference counts recounted; token history (first t columns), cumulative log p and termination flags are
+ * gathered as in smc_kv_reindex.  Ancestors outside the prompt's rows leave the row as it is. */
+smc_status smc_paged_reindex(smc_ctx* ctx, const int32_t* d_anc, const int32_t* d_resampled, int32_t t);
+
+/* Device pointers to the table [R, M] and the reference counts [B*Q], M, Q and the number of appended positions
+ * (each nullable).  No synchronisation: reads of the device arrays must be ordered after the context's stream. */
+smc_status smc_paged_view(smc_ctx* ctx, const int32_t** d_table, const int32_t** d_refcnt, int32_t* pages_per_row,
+                          int32_t* pages_per_prompt, int32_t* len);
+
+/* Synchronises and returns how many rows ever found no free page (always 0 unless the table was overwritten). */
+smc_status smc_paged_check(smc_ctx* ctx, int32_t* h_alloc_failures);
+
+/* Optional timing of the dominant kernels.  While enabled, a pair of HIP events is recorded on the context's
+ * stream around every launch of kind 0 (the vocabulary-pass kernel of smc_step), kind 1 (the KV gather kernel of
+ * smc_kv_reindex) and kind 2 (the page copy of smc_paged_prepare_append).  smc_profile_read synchronises the stream, returns the summed elapsed milliseconds and the number
  * of launches of that kind since the last read, and clears them.  Events are host objects; no device memory is used. */
 smc_status smc_profile_enable(smc_ctx* ctx, int32_t enable);
 smc_status smc_profile_read(smc_ctx* ctx, int32_t kind, double* h_total_ms, int64_t* h_launches);

@@ -16,7 +16,9 @@ STATUS = {0: "SMC_OK", 1: "SMC_E_NULL", 2: "SMC_E_SHAPE", 3: "SMC_E_DTYPE", 4: "
 
 EXPORTS = ["smc_workspace_bytes", "smc_init", "smc_destroy", "smc_kv_bind", "smc_step", "smc_ess", "smc_resample",
            "smc_kv_reindex", "smc_final_draw", "smc_get_done", "smc_set_done", "smc_ess_from", "smc_resample_from", "smc_get_state", "smc_set_state", "smc_get_diag",
-           "smc_set_tuning", "smc_set_resampler", "smc_set_ancestor_order", "smc_set_gather_tuning", "smc_profile_enable", "smc_profile_read", "smc_status_str"]
+           "smc_set_tuning", "smc_set_resampler", "smc_set_ancestor_order", "smc_set_gather_tuning", "smc_profile_enable", "smc_profile_read", "smc_status_str",
+           "smc_paged_workspace_bytes", "smc_paged_pool_bytes", "smc_paged_bind", "smc_paged_prepare_append",
+           "smc_paged_reindex", "smc_paged_view", "smc_paged_check"]
 
 
 class smc_config(C.Structure):
@@ -66,6 +68,15 @@ def lib():
         L.smc_set_gather_tuning.argtypes = [vp, i32, i32]
         L.smc_profile_enable.argtypes = [vp, i32]
         L.smc_profile_read.argtypes = [vp, i32, C.POINTER(f64), C.POINTER(i64)]
+        L.smc_paged_workspace_bytes.restype = C.c_size_t
+        L.smc_paged_workspace_bytes.argtypes = [C.POINTER(smc_config), i32]
+        L.smc_paged_pool_bytes.restype = C.c_size_t
+        L.smc_paged_pool_bytes.argtypes = [C.POINTER(smc_config), i32]
+        L.smc_paged_bind.argtypes = [vp, C.POINTER(vp), i32, vp, C.c_size_t, i32]
+        L.smc_paged_prepare_append.argtypes = [vp, i32, vp]
+        L.smc_paged_reindex.argtypes = [vp, vp, vp, i32]
+        L.smc_paged_view.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), C.POINTER(i32), C.POINTER(i32), C.POINTER(i32)]
+        L.smc_paged_check.argtypes = [vp, C.POINTER(i32)]
         L.smc_status_str.restype = C.c_char_p
         L.smc_status_str.argtypes = [C.c_int]
         for name in EXPORTS:
@@ -200,3 +211,38 @@ def smc_profile_read(ctx, kind):
 
 def smc_status_str(status):
     return lib().smc_status_str(status).decode()
+
+
+def smc_paged_workspace_bytes(cfg, page_len):
+    return int(lib().smc_paged_workspace_bytes(C.byref(cfg), page_len))
+
+
+def smc_paged_pool_bytes(cfg, page_len):
+    return int(lib().smc_paged_pool_bytes(C.byref(cfg), page_len))
+
+
+def smc_paged_bind(ctx, pools, page_len, d_workspace, workspace_bytes, len0=0):
+    P = (C.c_void_p * max(len(pools), 1))(*[_ptr(t) for t in pools])
+    _check("smc_paged_bind", lib().smc_paged_bind(ctx, P, page_len, _ptr(d_workspace), workspace_bytes, len0))
+
+
+def smc_paged_prepare_append(ctx, pos, d_slot_out):
+    _check("smc_paged_prepare_append", lib().smc_paged_prepare_append(ctx, pos, _ptr(d_slot_out)))
+
+
+def smc_paged_reindex(ctx, d_anc, d_resampled, t):
+    _check("smc_paged_reindex", lib().smc_paged_reindex(ctx, _ptr(d_anc), _ptr(d_resampled), t))
+
+
+def smc_paged_view(ctx):
+    """(table device address, refcnt device address, pages per row, pages per prompt, positions appended)."""
+    tab, ref = C.c_void_p(), C.c_void_p()
+    M, Q, n = C.c_int32(), C.c_int32(), C.c_int32()
+    _check("smc_paged_view", lib().smc_paged_view(ctx, C.byref(tab), C.byref(ref), C.byref(M), C.byref(Q), C.byref(n)))
+    return tab.value, ref.value, M.value, Q.value, n.value
+
+
+def smc_paged_check(ctx):
+    n = C.c_int32()
+    _check("smc_paged_check", lib().smc_paged_check(ctx, C.byref(n)))
+    return n.value

@@ -1,0 +1,332 @@
+// Paged (block-table) form of the cache reorder after resampling (Alg. 1 "reorder KV cache by A"; App. C: reindex
+// along the batch/particle dimension) for gfx950.
+//
+// The dense reorder copies whole cache rows.  Here a row's cache is a list of pages of P positions, table[r, j] being
+// the page that holds positions [j*P, (j+1)*P) of row r, and the reorder copies page NUMBERS: descendants of one
+// ancestor share its pages.  Before position pos is written every row must own its page for that position alone:
+// at a page start every row takes a fresh page; otherwise, of the rows that share a page the lowest keeps it and each
+// of the others takes a fresh page and receives a copy of the pos % P positions already filled (copy-on-write).
+// A reorder therefore moves kilobytes of page numbers, and an append at most (N-1)*(P-1) positions per prompt,
+// instead of the whole cache.
+//
+// Prompt b owns the page numbers [b*Q, (b+1)*Q), Q = N*M, M = ceil(S/P): at most N*M distinct pages can be referenced
+// by a prompt, so its pool never runs out.  A page is free iff its reference count is 0; needy rows, in increasing
+// row order, take the free pages of their prompt in increasing page order.  These rules are deterministic, so the
+// tables can be compared bit for bit with a CPU model that follows them.
+//
+//   paged_init_kernel     : the state after len0 appends with no resampling (table[b*N+k, j] = b*Q + j*N + k)
+//   paged_reindex_kernel  : one workgroup per resampled prompt; table rows copied by ancestor, counts recounted
+//   paged_prepare_kernel  : one workgroup per prompt; finds the needy rows, the lowest free pages, writes the slot of
+//                           every row and the list of (source page, new page) pairs
+//   paged_copy_kernel     : grid-stride over (pair, tensor, head): 16-byte vector copy of the filled part of a page
+#include "smc_internal.hpp"
+
+namespace psmc {
+
+namespace {
+constexpr int kPagedThreads = 256;
+typedef unsigned int vec16 __attribute__((ext_vector_type(4)));
+
+// Exclusive prefix sum of one int per thread over the 256-thread workgroup; `total` is the sum over all threads.
+__device__ inline int block_exclusive_scan(int v, int32_t* sh_wave, int& total)
+{
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    int inc = v;
+    for (int o = 1; o < kWave; o <<= 1) {
+        const int x = __shfl_up(inc, o);
+        if (lane >= o) inc += x;
+    }
+    __syncthreads();                                   // previous use of sh_wave is over
+    if (lane == kWave - 1) sh_wave[wave] = inc;
+    __syncthreads();
+    int before = 0;
+    total = 0;
+    for (int w = 0; w < kPagedThreads / kWave; ++w) {
+        const int s = sh_wave[w];
+        if (w < wave) before += s;
+        total += s;
+    }
+    return before + inc - v;
+}
+}  // namespace
+
+__global__ void paged_init_kernel(int R, int N, int M, int Q, int P, int len0, int32_t* __restrict__ table,
+                                  int32_t* __restrict__ refcnt, int32_t* __restrict__ counters)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int ncol = (len0 + P - 1) / P;
+    if (i < (int64_t)R * M) {
+        const int r = (int)(i / M), j = (int)(i % M);
+        const int b = r / N, k = r % N;
+        table[i] = j < ncol ? b * Q + j * N + k : -1;
+    }
+    if (i < (int64_t)(R / N) * Q) refcnt[i] = (int)(i % Q) < ncol * N ? 1 : 0;
+    if (i < 4) counters[i] = 0;                        // pair counters of the two phases, allocation failures, spare
+}
+
+__global__ __launch_bounds__(kPagedThreads) void paged_reindex_kernel(
+    const int32_t* __restrict__ anc, const int32_t* __restrict__ resampled, int N, int M, int Q, int ncol,
+    int32_t* __restrict__ table, int32_t* __restrict__ table_tmp, int32_t* __restrict__ refcnt)
+{
+    __shared__ int32_t sh_anc[SMC_MAX_PARTICLES];
+    const int b = blockIdx.x, tid = threadIdx.x;
+    if (!resampled[b]) return;
+    const int row0 = b * N, page0 = b * Q;
+    for (int k = tid; k < N; k += kPagedThreads) {
+        int a = anc[row0 + k] - row0;
+        if (a < 0 || a >= N) a = k;                    // outside the prompt: the row keeps its own pages
+        sh_anc[k] = a;
+    }
+    const int n = N * ncol;
+    for (int e = tid; e < n; e += kPagedThreads) {
+        const int64_t at = (int64_t)(row0 + e / ncol) * M + e % ncol;
+        table_tmp[at] = table[at];
+    }
+    for (int i = tid; i < Q; i += kPagedThreads) refcnt[page0 + i] = 0;
+    __syncthreads();
+    for (int e = tid; e < n; e += kPagedThreads) {
+        const int k = e / ncol, j = e % ncol;
+        const int p = table_tmp[(int64_t)(row0 + sh_anc[k]) * M + j];
+        table[(int64_t)(row0 + k) * M + j] = p;
+        if (p >= page0 && p < page0 + Q) atomicAdd(&refcnt[p], 1);
+    }
+}
+
+// counters: [0], [1] number of (source, new page) pairs of the two phases; [2] rows that found no free page.
+__global__ __launch_bounds__(kPagedThreads) void paged_prepare_kernel(
+    int N, int M, int Q, int j, int o, int phase, int32_t* __restrict__ table, int32_t* __restrict__ refcnt,
+    int32_t* __restrict__ counters, int32_t* __restrict__ cow_src, int32_t* __restrict__ cow_dst,
+    int32_t* __restrict__ slot)
+{
+    __shared__ int32_t sh_page[SMC_MAX_PARTICLES];     // page of each row for this position (-1 at a page start)
+    __shared__ int32_t sh_rank[SMC_MAX_PARTICLES];     // rank of a needy row among the prompt's needy rows, else -1
+    __shared__ int32_t sh_free[SMC_MAX_PARTICLES];     // the prompt's lowest free pages, increasing
+    __shared__ int32_t sh_wave[kPagedThreads / kWave];
+    __shared__ int32_t sh_base;
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const int row0 = b * N, page0 = b * Q;
+    if (b == 0 && tid == 0) counters[phase ^ 1] = 0;   // the other phase's counter, for the next call
+    for (int k = tid; k < N; k += kPagedThreads) sh_page[k] = o == 0 ? -1 : table[(int64_t)(row0 + k) * M + j];
+    __syncthreads();
+    // needy rows: all of them at a page start; otherwise every sharer of a page but the lowest
+    int n_needy = 0;
+    for (int k0 = 0; k0 < N; k0 += kPagedThreads) {
+        const int k = k0 + tid;
+        int needy = 0;
+        if (k < N) {
+            if (o == 0) needy = 1;
+            else {
+                const int p = sh_page[k];
+                for (int q = 0; q < k; ++q) if (sh_page[q] == p) { needy = 1; break; }
+            }
+        }
+        int total;
+        const int before = block_exclusive_scan(needy, sh_wave, total);
+        if (k < N) sh_rank[k] = needy ? n_needy + before : -1;
+        n_needy += total;
+    }
+    // the n_needy lowest free pages of the prompt: each thread counts the free pages of a contiguous range
+    const int chunk = (Q + kPagedThreads - 1) / kPagedThreads;
+    const int lo = min(Q, tid * chunk), hi = min(Q, lo + chunk);
+    int n_free_mine = 0;
+    for (int i = lo; i < hi; ++i) n_free_mine += refcnt[page0 + i] == 0;
+    int n_free;
+    int z = block_exclusive_scan(n_free_mine, sh_wave, n_free);
+    for (int i = lo; i < hi && z < n_needy; ++i)
+        if (refcnt[page0 + i] == 0) sh_free[z++] = i;
+    const int n_served = min(n_needy, n_free);         // n_free >= n_needy unless the table was corrupted
+    if (tid == 0) {
+        sh_base = (o > 0 && n_served > 0) ? atomicAdd(&counters[phase], n_served) : 0;
+        if (n_served < n_needy) atomicAdd(&counters[2], n_needy - n_served);
+    }
+    __syncthreads();
+    for (int k = tid; k < N; k += kPagedThreads) {
+        const int rank = sh_rank[k];
+        int page = sh_page[k];
+        if (rank >= 0 && rank < n_served) {
+            const int fresh = page0 + sh_free[rank];
+            if (o > 0) { cow_src[sh_base + rank] = page; cow_dst[sh_base + rank] = fresh; }
+            table[(int64_t)(row0 + k) * M + j] = fresh;
+            refcnt[fresh] = 1;
+            page = fresh;
+        } else if (rank < 0 && page >= page0 && page < page0 + Q) {
+            refcnt[page] = 1;                          // the lowest sharer keeps the page for itself
+        }
+        slot[row0 + k] = page;
+    }
+}
+
+// Copies the first copy_bytes bytes (a multiple of 16) of each of the n_heads head chunks of a page, for every tensor
+// and every (source page, new page) pair.
+__global__ __launch_bounds__(kPagedThreads) void paged_copy_kernel(
+    void* const* __restrict__ pools, int n_tensors, int n_heads, long long page_stride, long long head_stride,
+    long long copy_bytes, int n_pages, int phase, const int32_t* __restrict__ counters,
+    const int32_t* __restrict__ cow_src, const int32_t* __restrict__ cow_dst)
+{
+    const int n_pairs = counters[phase];
+    const int64_t per_pair = (int64_t)n_tensors * n_heads;
+    const int64_t total = per_pair * n_pairs;
+    for (int64_t w = blockIdx.x; w < total; w += gridDim.x) {
+        const int pair = (int)(w / per_pair);
+        const int rem = (int)(w - (int64_t)pair * per_pair);
+        const int tensor = rem / n_heads, head = rem - tensor * n_heads;
+        const int from = cow_src[pair], to = cow_dst[pair];
+        if (from < 0 || from >= n_pages || to < 0 || to >= n_pages) continue;      // only after a corrupted table
+        char* base = (char*)pools[tensor] + (int64_t)head * head_stride;
+        const char* s = base + (int64_t)from * page_stride;
+        char* d = base + (int64_t)to * page_stride;
+        for (int64_t off = (int64_t)threadIdx.x * 16; off < copy_bytes; off += (int64_t)kPagedThreads * 16)
+            *(vec16*)(d + off) = *(const vec16*)(s + off);
+    }
+}
+
+}  // namespace psmc
+
+using namespace psmc;
+
+namespace {
+constexpr size_t kAlign = 256;
+inline size_t up(size_t x) { return (x + kAlign - 1) & ~(kAlign - 1); }
+
+struct PagedDims { int P, M, Q; size_t n_table, n_pages; };
+
+bool paged_dims(const smc_config* c, int page_len, PagedDims* d)
+{
+    if (!c || c->kv_tensors < 1 || c->kv_S < 1 || c->N < 1 || c->B < 1 || page_len < 1 || page_len > c->kv_S) return false;
+    if (((int64_t)c->kv_D * c->kv_elem_bytes) % 16 != 0) return false;
+    d->P = page_len;
+    d->M = (c->kv_S + page_len - 1) / page_len;
+    const int64_t Q = (int64_t)c->N * d->M;
+    const int64_t pages = Q * c->B;
+    if (pages > ((int64_t)1 << 30)) return false;
+    d->Q = (int)Q;
+    d->n_pages = (size_t)pages;
+    d->n_table = (size_t)c->B * c->N * d->M;
+    return true;
+}
+
+size_t paged_layout(const smc_config* c, const PagedDims& d, char* base, PagedKV* p)
+{
+    const size_t R = (size_t)c->B * c->N;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { char* q = base ? base + off : nullptr; off += up(bytes); return q; };
+    char* q;
+    q = take(d.n_table * 4); if (p) p->table = (int32_t*)q;
+    q = take(d.n_table * 4); if (p) p->table_tmp = (int32_t*)q;
+    q = take(d.n_pages * 4); if (p) p->refcnt = (int32_t*)q;
+    q = take(R * 4); if (p) p->cow_src = (int32_t*)q;
+    q = take(R * 4); if (p) p->cow_dst = (int32_t*)q;
+    q = take(4 * 4); if (p) p->counters = (int32_t*)q;
+    q = take((size_t)c->kv_tensors * sizeof(void*)); if (p) p->pools = (void**)q;
+    return off;
+}
+}  // namespace
+
+extern "C" {
+
+size_t smc_paged_workspace_bytes(const smc_config* cfg, int32_t page_len)
+{
+    PagedDims d;
+    if (!paged_dims(cfg, page_len, &d)) return 0;
+    return paged_layout(cfg, d, nullptr, nullptr);
+}
+
+size_t smc_paged_pool_bytes(const smc_config* cfg, int32_t page_len)
+{
+    PagedDims d;
+    if (!paged_dims(cfg, page_len, &d)) return 0;
+    return d.n_pages * (size_t)cfg->kv_H * (size_t)d.P * (size_t)cfg->kv_D * (size_t)cfg->kv_elem_bytes;
+}
+
+smc_status smc_paged_bind(smc_ctx* ctx, void* const* h_pools, int32_t page_len, void* d_workspace, size_t workspace_bytes,
+                          int32_t len0)
+{
+    if (!ctx || !h_pools || !d_workspace) return SMC_E_NULL;
+    PagedDims d;
+    if (!paged_dims(&ctx->cfg, page_len, &d)) return SMC_E_SHAPE;
+    if (len0 < 0 || len0 > ctx->cfg.kv_S) return SMC_E_RANGE;
+    if (((uintptr_t)d_workspace & (kAlign - 1)) != 0) return SMC_E_ALIGN;
+    if (workspace_bytes < paged_layout(&ctx->cfg, d, nullptr, nullptr)) return SMC_E_SHAPE;
+    for (int i = 0; i < ctx->cfg.kv_tensors; ++i) {
+        if (!h_pools[i]) return SMC_E_NULL;
+        if (((uintptr_t)h_pools[i] & 15u) != 0) return SMC_E_ALIGN;
+    }
+    if (hipStreamSynchronize(ctx->stream) != hipSuccess) return SMC_E_HIP;
+    PagedKV& p = ctx->paged;
+    paged_layout(&ctx->cfg, d, (char*)d_workspace, &p);
+    p.P = d.P; p.M = d.M; p.Q = d.Q; p.len = len0; p.phase = 0;
+    if (hipMemcpy(p.pools, h_pools, (size_t)ctx->cfg.kv_tensors * sizeof(void*), hipMemcpyHostToDevice) != hipSuccess)
+        return SMC_E_HIP;
+    const size_t n = d.n_table > d.n_pages ? d.n_table : d.n_pages;
+    hipLaunchKernelGGL(paged_init_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, ctx->stream, ctx->R, ctx->cfg.N,
+                       d.M, d.Q, d.P, len0, p.table, p.refcnt, p.counters);
+    if (hipGetLastError() != hipSuccess) return SMC_E_HIP;
+    p.bound = 1;
+    return SMC_OK;
+}
+
+smc_status smc_paged_prepare_append(smc_ctx* ctx, int32_t pos, int32_t* d_slot_out)
+{
+    if (!ctx || !d_slot_out) return SMC_E_NULL;
+    PagedKV& p = ctx->paged;
+    if (!p.bound) return SMC_E_STATE;
+    if (pos < 0 || pos >= ctx->cfg.kv_S) return SMC_E_RANGE;
+    if (pos != p.len) return SMC_E_STATE;              // positions are appended one by one, the same for every row
+    const auto& cfg = ctx->cfg;
+    const int j = pos / p.P, o = pos % p.P;
+    p.phase ^= 1;
+    hipLaunchKernelGGL(paged_prepare_kernel, dim3(cfg.B), dim3(kPagedThreads), 0, ctx->stream, cfg.N, p.M, p.Q, j, o, p.phase,
+                       p.table, p.refcnt, p.counters, p.cow_src, p.cow_dst, d_slot_out);
+    if (o > 0) {
+        const long long pos_bytes = (long long)cfg.kv_D * cfg.kv_elem_bytes;
+        const long long head_stride = pos_bytes * p.P;
+        ScopedKernelTimer timer(ctx, 2);
+        hipLaunchKernelGGL(paged_copy_kernel, dim3(ctx->n_cus * 8), dim3(kPagedThreads), 0, ctx->stream,
+                           (void* const*)p.pools, cfg.kv_tensors, cfg.kv_H, head_stride * cfg.kv_H, head_stride,
+                           pos_bytes * o, cfg.B * p.Q, p.phase, p.counters, p.cow_src, p.cow_dst);
+    }
+    if (hipGetLastError() != hipSuccess) return SMC_E_HIP;
+    p.len = pos + 1;
+    return SMC_OK;
+}
+
+smc_status smc_paged_reindex(smc_ctx* ctx, const int32_t* d_anc, const int32_t* d_resampled, int32_t t)
+{
+    if (!ctx || !d_anc || !d_resampled) return SMC_E_NULL;
+    PagedKV& p = ctx->paged;
+    if (!p.bound) return SMC_E_STATE;
+    if (t < 0 || t > ctx->cfg.T_max) return SMC_E_RANGE;
+    // token history, cumulative log p and termination flags follow their ancestors as in the dense reorder
+    if (launch_reindex(ctx, d_anc, d_resampled, 0, t) != hipSuccess) return SMC_E_HIP;
+    const int ncol = (p.len + p.P - 1) / p.P;
+    if (ncol > 0) {
+        hipLaunchKernelGGL(paged_reindex_kernel, dim3(ctx->cfg.B), dim3(kPagedThreads), 0, ctx->stream, d_anc, d_resampled,
+                           ctx->cfg.N, p.M, p.Q, ncol, p.table, p.table_tmp, p.refcnt);
+        if (hipGetLastError() != hipSuccess) return SMC_E_HIP;
+    }
+    return SMC_OK;
+}
+
+smc_status smc_paged_view(smc_ctx* ctx, const int32_t** d_table, const int32_t** d_refcnt, int32_t* pages_per_row,
+                          int32_t* pages_per_prompt, int32_t* len)
+{
+    if (!ctx) return SMC_E_NULL;
+    const PagedKV& p = ctx->paged;
+    if (!p.bound) return SMC_E_STATE;
+    if (d_table) *d_table = p.table;
+    if (d_refcnt) *d_refcnt = p.refcnt;
+    if (pages_per_row) *pages_per_row = p.M;
+    if (pages_per_prompt) *pages_per_prompt = p.Q;
+    if (len) *len = p.len;
+    return SMC_OK;
+}
+
+smc_status smc_paged_check(smc_ctx* ctx, int32_t* h_alloc_failures)
+{
+    if (!ctx || !h_alloc_failures) return SMC_E_NULL;
+    if (!ctx->paged.bound) return SMC_E_STATE;
+    if (hipStreamSynchronize(ctx->stream) != hipSuccess) return SMC_E_HIP;
+    return hipMemcpy(h_alloc_failures, ctx->paged.counters + 2, 4, hipMemcpyDeviceToHost) == hipSuccess ? SMC_OK : SMC_E_HIP;
+}
+
+}  // extern "C"

@@ -60,12 +60,28 @@ struct Workspace {                // device pointers carved out of the caller's 
     void** histAB;                // [2]
 };
 
+// Paged form of the KV cache: page numbers per (row, column), reference counts, copy-on-write work list.
+struct PagedKV {
+    int bound;
+    int P, M, Q;                  // positions per page, pages per row, pages per prompt (= N*M)
+    int len;                      // positions appended so far (the same for every row)
+    int phase;                    // which pair counter the current append uses
+    int32_t* table;               // [R*M] page of row r for positions [j*P, (j+1)*P), -1 while unused
+    int32_t* table_tmp;           // [R*M] the reorder's copy of the old table
+    int32_t* refcnt;              // [B*Q] rows that reference a page; 0 = free
+    int32_t* cow_src;             // [R] source page of each pending copy
+    int32_t* cow_dst;             // [R] new page of each pending copy
+    int32_t* counters;            // [4] pairs of phase 0 / 1, rows that found no free page, spare
+    void** pools;                 // [kv_tensors] page pools [B*Q, H, P, D]
+};
+
 }  // namespace psmc
 
 struct smc_ctx {
     smc_config cfg;
     hipStream_t stream;
     psmc::Workspace ws;
+    psmc::PagedKV paged;
     int R;
     int n_split;                  // current split of a row over workgroups
     int dense;                    // 1: score every vocabulary entry (no candidate filter)
@@ -79,10 +95,11 @@ struct smc_ctx {
     int plan_phase;               // which group counter the current reindex uses
     int gather_variant;           // vectors per thread / non-temporal choice of the gather kernel
     int n_cus;
-    // optional per-kernel timing: event pairs recorded around launches of kind 0 (vocab pass) and 1 (KV gather)
+    // optional per-kernel timing: event pairs recorded around launches of kind 0 (vocab pass), 1 (KV gather) and
+    // 2 (copy-on-write page copy)
     int profiling;
-    std::vector<hipEvent_t> ev_pool[2];   // [2*i] start, [2*i+1] stop
-    size_t ev_used[2];
+    std::vector<hipEvent_t> ev_pool[3];   // [2*i] start, [2*i+1] stop
+    size_t ev_used[3];
 };
 
 namespace psmc {

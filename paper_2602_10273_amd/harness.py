@@ -10,9 +10,10 @@ from . import binding as smc
 
 class Session:
     def __init__(self, B, N, V, T_max, dtype, kappa, seed, kv_geom=None, kv=None, with_hist=True, device="cuda",
-                 stream=None, eos_id=-1):
+                 stream=None, eos_id=-1, page_len=0, len0=0):
         """kv_geom = (kv_tensors, H, S, D) allocates zeroed double buffers; kv = list of [R,H,S,D] bf16/uint16
-        tensors (numpy or torch) to copy into buffer A instead."""
+        tensors (numpy or torch) to copy into buffer A instead.  page_len > 0 (with kv_geom): the cache is paged
+        instead -- one zeroed pool [B*Q, H, page_len, D] per tensor, the table as after len0 appends."""
         self.B, self.N, self.V, self.T_max, self.R = B, N, V, T_max, B * N
         self.dtype, self.device = dtype, device
         dev = torch.device(device)
@@ -24,7 +25,7 @@ class Session:
                 self.kvA.append(a)
                 self.kvB.append(torch.zeros_like(a))
             kv_geom = (len(kv),) + tuple(self.kvA[0].shape[1:])
-        elif kv_geom is not None:
+        elif kv_geom is not None and page_len == 0:
             n, H, S, D = kv_geom
             for _ in range(n):
                 self.kvA.append(torch.zeros((self.R, H, S, D), dtype=torch.bfloat16, device=dev))
@@ -53,6 +54,16 @@ class Session:
             self.histB = torch.zeros((self.R, T_max), dtype=torch.int32, device=dev)
         if n > 0 or with_hist:
             smc.smc_kv_bind(self.ctx, self.kvA, self.kvB, self.histA, self.histB)
+        self.page_len = page_len
+        if page_len > 0:
+            self.M = (S + page_len - 1) // page_len
+            self.Q = N * self.M
+            self.pools = [torch.zeros((B * self.Q, H, page_len, D), dtype=torch.bfloat16, device=dev) for _ in range(n)]
+            assert self.pools[0].numel() * 2 == smc.smc_paged_pool_bytes(self.cfg, page_len)
+            pbytes = smc.smc_paged_workspace_bytes(self.cfg, page_len)
+            self.paged_ws = torch.empty(pbytes + 256, dtype=torch.uint8, device=dev)
+            smc.smc_paged_bind(self.ctx, self.pools, page_len, (self.paged_ws.data_ptr() + 255) & ~255, pbytes, len0)
+            self.slot = torch.zeros(self.R, dtype=torch.int32, device=dev)
 
     def close(self):
         if self.ctx is not None:
@@ -78,6 +89,25 @@ class Session:
     def reindex(self, valid_len, t, anc=None, resampled=None):
         smc.smc_kv_reindex(self.ctx, self.anc if anc is None else anc,
                            self.resampled if resampled is None else resampled, valid_len, t)
+
+    def prepare_append(self, pos):
+        smc.smc_paged_prepare_append(self.ctx, pos, self.slot)
+
+    def paged_reindex(self, t, anc=None, resampled=None):
+        smc.smc_paged_reindex(self.ctx, self.anc if anc is None else anc,
+                              self.resampled if resampled is None else resampled, t)
+
+    def paged_state(self):
+        """(table [R, M], refcnt [B*Q]) as numpy, after synchronising."""
+        torch.cuda.synchronize()
+        tab, ref, M, Q, _ = smc.smc_paged_view(self.ctx)
+        base = (self.paged_ws.data_ptr() + 255) & ~255
+        flat = self.paged_ws[base - self.paged_ws.data_ptr():]
+        t0 = tab - base
+        r0 = ref - base
+        table = flat[t0:t0 + self.R * M * 4].view(torch.int32).reshape(self.R, M).cpu().numpy()
+        refcnt = flat[r0:r0 + self.B * Q * 4].view(torch.int32).cpu().numpy()
+        return table, refcnt
 
     def final_draw(self, t):
         smc.smc_final_draw(self.ctx, t, self.choice)

@@ -1,0 +1,147 @@
+"""Paged form of the cache reorder: HIP path vs the CPU model that follows the same allocation rules, and vs the
+dense row gather that defines the reorder (Alg. 1 "reorder KV cache by A"; App. C).  Tables, reference counts and
+slots bit-exact; logical cache content bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import reference as orc
+from oracle.paged import PagedKV
+from paper_2602_10273_amd import binding as smc
+from paper_2602_10273_amd import synth
+from paper_2602_10273_amd.harness import Session, to_device_logits
+
+pytestmark = pytest.mark.gpu
+
+
+def _logical(s, ten, table, length):
+    """[R, H, length, D] uint16 read through the table from the device pools."""
+    P = s.page_len
+    ncol = (length + P - 1) // P
+    pool = s.pools[ten].view(torch.int16)
+    idx = torch.as_tensor(table[:, :ncol].astype(np.int64)).cuda()
+    pages = pool[idx]                                          # [R, ncol, H, P, D]
+    R, _, H, _, D = pages.shape
+    out = pages.permute(0, 2, 1, 3, 4).reshape(R, H, ncol * P, D)[:, :, :length]
+    return out.cpu().numpy().view(np.uint16)
+
+
+def _write(s, pk, pos, new):
+    """The decoder's append on both sides: new[ten] is [R, H, D] uint16."""
+    o = pos % pk.P
+    pk.write(pos, new)
+    for ten, x in enumerate(new):
+        s.pools[ten].view(torch.int16)[s.slot.long(), :, o, :] = torch.as_tensor(x.view(np.int16)).cuda()
+
+
+def _compare_tables(s, pk):
+    table, refcnt = s.paged_state()
+    ncol = (pk.len + pk.P - 1) // pk.P
+    assert np.array_equal(table[:, :ncol], pk.table[:, :ncol])
+    assert np.all(table[:, ncol:] == -1)
+    assert np.array_equal(refcnt, pk.refcnt)
+    return table
+
+
+@pytest.mark.parametrize("B,N,H,S,D,P,len0", [
+    (3, 4, 2, 24, 8, 4, 0), (2, 5, 1, 23, 8, 3, 0), (1, 8, 2, 9, 8, 1, 0), (2, 3, 1, 7, 8, 7, 0),
+    (2, 64, 1, 40, 8, 16, 0), (1, 100, 1, 12, 8, 5, 0), (1, 1024, 1, 6, 8, 4, 0), (4, 1, 2, 10, 8, 4, 0),
+    (3, 6, 2, 40, 16, 8, 21),
+])
+def test_paged_matches_model_and_dense_gather(B, N, H, S, D, P, len0):
+    rng = np.random.default_rng(B * 1000 + N + P)
+    R, n_t = B * N, 2
+    s = Session(B, N, 64, 64, "f32", 0.5, 1, kv_geom=(n_t, H, S, D), page_len=P, len0=len0)
+    pk = PagedKV(B, N, H, S, D, P, n_t)
+    dense = [np.zeros((R, H, S, D), np.uint16) for _ in range(n_t)]
+    if len0:
+        pk.reset(len0)
+        for pos in range(len0):                                # history before the test starts: same on both sides
+            new = [rng.integers(0, 65536, (R, H, D), dtype=np.uint16) for _ in range(n_t)]
+            pk.write(pos, new)
+            for d, x in zip(dense, new):
+                d[:, :, pos, :] = x
+        for ten in range(n_t):
+            s.pools[ten].view(torch.int16).copy_(torch.as_tensor(pk.pool[ten].view(np.int16)))
+        _compare_tables(s, pk)
+    for pos in range(len0, S):
+        slot_ref, copies = pk.prepare_append(pos)
+        s.prepare_append(pos)
+        assert np.array_equal(s.slot.cpu().numpy(), slot_ref), pos
+        new = [rng.integers(0, 65536, (R, H, D), dtype=np.uint16) for _ in range(n_t)]
+        _write(s, pk, pos, new)
+        for d, x in zip(dense, new):
+            d[:, :, pos, :] = x
+        flag = (rng.random(B) < 0.6).astype(np.int32)
+        anc = np.concatenate([b * N + np.sort(rng.integers(0, N, N)) for b in range(B)]).astype(np.int32)
+        if pos % 3 == 1:                                       # unsorted ancestors as well
+            anc = np.concatenate([b * N + rng.integers(0, N, N) for b in range(B)]).astype(np.int32)
+        pk.reindex(anc, flag)
+        dense = [orc.gather_kv(d, anc, flag, N, pos + 1, d.copy()) for d in dense]
+        s.paged_reindex(0, torch.as_tensor(anc).cuda(), torch.as_tensor(flag).cuda())
+        table = _compare_tables(s, pk)
+        if pos % 4 == 3 or pos == S - 1:
+            for ten in range(n_t):
+                assert np.array_equal(_logical(s, ten, table, pos + 1), dense[ten][:, :, :pos + 1]), (pos, ten)
+    assert smc.smc_paged_check(s.ctx) == 0
+    s.close()
+
+
+def test_paged_argument_errors_and_foreign_ancestors():
+    cfg = smc.make_config(2, 4, 64, 8, "f32", 0.5, 0, 2, 1, 10, 8, 2)
+    assert smc.smc_paged_workspace_bytes(cfg, 0) == 0 and smc.smc_paged_workspace_bytes(cfg, 11) == 0
+    assert smc.smc_paged_pool_bytes(cfg, 4) == 2 * (4 * 3) * 1 * 4 * 8 * 2
+    s = Session(2, 4, 64, 8, "f32", 0.5, 0, kv_geom=(2, 1, 10, 8), page_len=4)
+    with pytest.raises(smc.SMCError):
+        s.prepare_append(1)                                    # positions are appended one by one from 0
+    s.prepare_append(0)
+    with pytest.raises(smc.SMCError):
+        s.prepare_append(0)
+    before, _ = s.paged_state()
+    anc = torch.tensor([5, 0, 1, 99, 4, 4, -3, 7], dtype=torch.int32).cuda()      # 5, 99, -3: outside their prompt
+    s.paged_reindex(0, anc, torch.ones(2, dtype=torch.int32).cuda())
+    table, refcnt = s.paged_state()
+    assert table[:, 0].tolist() == [before[0, 0], before[0, 0], before[1, 0], before[3, 0],
+                                    before[4, 0], before[4, 0], before[6, 0], before[7, 0]]
+    assert refcnt.sum() == 8 and smc.smc_paged_check(s.ctx) == 0
+    s2 = Session(2, 4, 64, 8, "f32", 0.5, 0, kv_geom=(2, 1, 10, 8))               # dense session: paged calls refuse
+    with pytest.raises(smc.SMCError):
+        smc.smc_paged_prepare_append(s2.ctx, 0, s2.tokens)
+    s.close(); s2.close()
+
+
+def test_paged_lockstep_with_the_sampler():
+    """The whole step with a paged cache: histories, weights and the logical cache follow the oracle's dense run."""
+    w = synth.scaled(synth.WORKLOADS["cfg2"], B=8, N=8, V=4104, layers=1, H=2, S=40, D=64)
+    steps, P = 40, 8
+    kv0 = [np.zeros((w.R, w.H, w.S, w.D), np.uint16) for _ in range(2)]
+    o = orc.OracleSMC(w.B, w.N, w.V, steps, w.kappa, 0, w.dtype, kv=kv0)
+    s = Session(w.B, w.N, w.V, steps, w.dtype, w.kappa, 0, kv_geom=(2, w.H, w.S, w.D), page_len=P)
+    rng = np.random.default_rng(5)
+    n_res = 0
+    for t in range(1, steps + 1):
+        pos = t - 1                                            # the decoder appends position t-1, then emits logits
+        s.prepare_append(pos)
+        new = [rng.integers(0, 65536, (w.R, w.H, w.D), dtype=np.uint16) for _ in range(2)]
+        for ten in range(2):
+            o.kv[ten][:, :, pos, :] = new[ten]
+            s.pools[ten].view(torch.int16)[s.slot.long(), :, pos % P, :] = torch.as_tensor(new[ten].view(np.int16)).cuda()
+        x = synth.logits_numpy(w, t, 0)
+        want = o.step(x, t, w.alpha, w.alpha)
+        s.step(to_device_logits(x, w.dtype), t, w.alpha, w.alpha)
+        assert np.array_equal(s.tokens.cpu().numpy(), want["tokens"]) or (want["gap"] < 1e-6).any()
+        anc_ref, flag_ref, _ = o.resample(t)
+        s.resample(t)
+        assert np.array_equal(s.resampled.cpu().numpy(), flag_ref) and np.array_equal(s.anc.cpu().numpy(), anc_ref), t
+        o.reindex(anc_ref, flag_ref, t, t)
+        s.paged_reindex(t)
+        n_res += int(flag_ref.sum())
+        logW, cum, _ = s.state()
+        assert np.abs(logW - o.logW).max() < 1e-4 and np.abs(cum - o.cumlogp).max() < 1e-4
+        if t % 8 == 0:
+            assert np.array_equal(s.live_hist()[:, :t], o.hist[:, :t])
+            table, _ = s.paged_state()
+            for ten in range(2):
+                assert np.array_equal(_logical(s, ten, table, t), o.kv[ten][:, :, :t]), (t, ten)
+    assert n_res > 10 and smc.smc_paged_check(s.ctx) == 0
+    s.close()
