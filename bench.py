@@ -34,6 +34,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kv", action="store_true", help="vocabulary pass + weights only (no cache bound)")
     ap.add_argument("--n-split", type=int, default=0)
+    ap.add_argument("--paged", type=int, default=0, metavar="P",
+                    help="paged cache with P positions per page: the reorder copies page numbers, appends copy on write")
     ap.add_argument("--in-place", action="store_true",
                     help="ancestor order 1: surviving ancestors keep their slot, only the other copies move")
     return ap.parse_args()
@@ -106,14 +108,16 @@ def main():
     T_max = (W + 2 * K + 8 + 3) // 4 * 4
 
     kv_geom = None if args.no_kv else (w.kv_tensors, w.H, w.S, w.D)
-    s = Session(w.B, w.N, w.V, T_max, w.dtype, w.kappa, args.seed, kv_geom=kv_geom)
+    P = 0 if args.no_kv else args.paged
+    len0 = max(0, w.S - (W + 2 * K) - 1)           # paged runs: the cache is this full when the run starts
+    s = Session(w.B, w.N, w.V, T_max, w.dtype, w.kappa, args.seed, kv_geom=kv_geom, page_len=P, len0=len0)
     if args.n_split:
         smc.smc_set_tuning(s.ctx, args.n_split, 0)
     if args.in_place:
         smc.smc_set_ancestor_order(s.ctx, 1)
     if not args.no_kv:
         g = torch.Generator(device=dev); g.manual_seed(args.seed + 12345)
-        for t in s.kvA:
+        for t in (s.pools if P else s.kvA):
             t.normal_(generator=g)
     n_ring = 4 if w.dtype == "f32" else 16       # distinct logits buffers: more bytes than the 256 MB last-level cache
     ring = [synth.logits_torch(w, i, args.seed) for i in range(n_ring)]
@@ -121,12 +125,20 @@ def main():
 
     step_no = [0]
 
+    def reorder(t):
+        if P:
+            s.paged_reindex(t)
+        else:
+            s.reindex(w.S, t)
+
     def one_step():
         step_no[0] += 1
         t = step_no[0]
+        if P:
+            s.prepare_append(len0 + t - 1)          # the decoder would now write position len0+t-1 and emit logits
         s.step(ring[t % n_ring], t, w.alpha_at(t), w.alpha_at(t - 1), -1.0)
         s.resample(t)
-        s.reindex(w.S, t)
+        reorder(t)
 
     for _ in range(W):
         one_step()
@@ -144,12 +156,15 @@ def main():
     for i in range(K):
         step_no[0] += 1
         t = step_no[0]
+        if P:
+            s.prepare_append(len0 + t - 1)
         s.step(ring[t % n_ring], t, w.alpha_at(t), w.alpha_at(t - 1), -1.0)
         s.resample(t)
         anc_log[i].copy_(s.anc); flag_log[i].copy_(s.resampled)
-        s.reindex(w.S, t)
+        reorder(t)
+    first_t = step_no[0] - K + 1
     ms_vocab, n_vocab = smc.smc_profile_read(s.ctx, 0)
-    ms_gather, n_gather = smc.smc_profile_read(s.ctx, 1)
+    ms_gather, n_gather = smc.smc_profile_read(s.ctx, 2 if P else 1)
     smc.smc_profile_enable(s.ctx, 0)
     anc_h = anc_log.cpu().numpy().reshape(K, w.B, w.N)
     flag_h = flag_log.cpu().numpy()
@@ -160,6 +175,15 @@ def main():
     moved = (local != np.arange(w.N)[None, None, :]) & (flag_h[:, :, None] != 0)
     rows_moved = int(moved.sum()) + sum(len(np.unique(local[i, b][moved[i, b]])) for i in range(K) for b in range(w.B))
     gather_bytes_total = float(rows_moved) * w.kv_row_bytes * w.kv_tensors
+    if P:
+        # an append at offset o = pos % P copies o positions (read + write) for every sharer of a page but one: the
+        # rows of the prompts that resampled at the previous step, minus their distinct ancestors
+        gather_bytes_total = 0.0
+        pos_bytes = w.kv_row_bytes // w.S
+        for i in range(1, K):
+            o = (len0 + first_t + i - 1) % P
+            needy = sum(w.N - len(np.unique(local[i - 1, b])) for b in range(w.B) if flag_h[i - 1, b])
+            gather_bytes_total += 2.0 * needy * o * pos_bytes * w.kv_tensors
     resample_frac = float(flag_h.mean())
 
     def roof(name, total_bytes, ms, launches):
@@ -180,7 +204,8 @@ def main():
         pass
 
     r_vocab = roof("vocab_pass_kernel", vocab_bytes * n_vocab, ms_vocab, n_vocab)
-    r_gather = roof("gather_kernel", gather_bytes_total, ms_gather, n_gather if not args.no_kv else 0)
+    r_gather = roof("paged_copy_kernel" if P else "gather_kernel", gather_bytes_total, ms_gather,
+                    n_gather if not args.no_kv else 0)
     for r in (r_vocab, r_gather):
         if r["kernel"] in ratios and r.get("algorithmic_bytes_per_launch"):
             r["traffic"] = ratios[r["kernel"]] * r["algorithmic_bytes_per_launch"]
@@ -204,7 +229,8 @@ def main():
         "ms_per_step": elapsed / K * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "N": w.N, "V": w.V, "logits_dtype": w.dtype, "alpha": w.alpha,
-                   "kappa": w.kappa, "ancestor_order": "survivors-in-place" if args.in_place else "as-drawn", "kv": None if args.no_kv else f"{w.layers}x2 tensors [{w.R},{w.H},{w.S},{w.D}] bf16 x2 buffers",
+                   "kappa": w.kappa, "ancestor_order": "survivors-in-place" if args.in_place else "as-drawn", "kv": None if args.no_kv else (f"{w.layers}x2 paged pools [{w.B}x{s.Q},{w.H},{P},{w.D}] bf16, {len0} positions filled at start"
+                                                 if P else f"{w.layers}x2 tensors [{w.R},{w.H},{w.S},{w.D}] bf16 x2 buffers"),
                    "valid_len": w.S, "resampled_prompt_fraction": resample_frac,
                    "logits_ring": n_ring},
         "roofline": dominant, "roofline_other": other,

@@ -80,7 +80,7 @@ def lib():
         L.smc_status_str.restype = C.c_char_p
         L.smc_status_str.argtypes = [C.c_int]
         for name in EXPORTS:
-            if name not in ("smc_workspace_bytes", "smc_status_str"):
+            if name not in ("smc_workspace_bytes", "smc_paged_workspace_bytes", "smc_paged_pool_bytes", "smc_status_str"):
                 getattr(L, name).restype = C.c_int
         _lib = L
     return _lib

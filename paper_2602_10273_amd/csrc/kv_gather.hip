@@ -36,6 +36,8 @@ __global__ __launch_bounds__(kWave) void plan_kernel(const int32_t* __restrict__
     __shared__ int32_t sh_anc[SMC_MAX_PARTICLES];
     __shared__ double sh_cum[SMC_MAX_PARTICLES];
     __shared__ int32_t sh_done[SMC_MAX_PARTICLES];
+    __shared__ int32_t sh_first[SMC_MAX_PARTICLES];                // lowest moved row that continues each ancestor
+    __shared__ int32_t sh_group[SMC_MAX_PARTICLES];                // group number of each ancestor that has one
     __shared__ int32_t sh_base;
     const int b = blockIdx.x, lane = threadIdx.x;
     if (b == 0 && lane == 0) plan->n_groups[phase ^ 1] = 0;
@@ -52,15 +54,15 @@ __global__ __launch_bounds__(kWave) void plan_kernel(const int32_t* __restrict__
     }
     __syncthreads();
     // leaders: first moved row (in particle order) of each distinct ancestor
+    for (int k = lane; k < N; k += kWave) sh_first[k] = N;
+    __syncthreads();
+    for (int k = lane; k < N; k += kWave)
+        if (sh_anc[k] >= 0) atomicMin(&sh_first[sh_anc[k]], k);
+    __syncthreads();
     int n_lead = 0;
     for (int k0 = 0; k0 < N; k0 += kWave) {
         const int k = k0 + lane;
-        bool lead = false;
-        if (k < N && sh_anc[k] >= 0) {
-            lead = true;
-            const int a = sh_anc[k];
-            for (int j = 0; j < k; ++j) if (sh_anc[j] == a) { lead = false; break; }
-        }
+        const bool lead = k < N && sh_anc[k] >= 0 && sh_first[sh_anc[k]] == k;
         n_lead += __popcll(__ballot(lead));
     }
     if (lane == 0) sh_base = n_lead ? atomicAdd(&plan->n_groups[phase], n_lead) : 0;
@@ -70,27 +72,23 @@ __global__ __launch_bounds__(kWave) void plan_kernel(const int32_t* __restrict__
     int placed = 0;
     for (int k0 = 0; k0 < N; k0 += kWave) {
         const int k = k0 + lane;
-        bool lead = false;
-        int a = -1;
-        if (k < N && sh_anc[k] >= 0) {
-            lead = true;
-            a = sh_anc[k];
-            for (int j = 0; j < k; ++j) if (sh_anc[j] == a) { lead = false; break; }
-        }
+        const bool lead = k < N && sh_anc[k] >= 0 && sh_first[sh_anc[k]] == k;
         const unsigned long long mk = __ballot(lead);
         if (lead) {
+            const int a = sh_anc[k];
             const int g = sh_base + placed + mask_rank(mk);
             grp_src[g] = row0 + a;
             grp_base[g] = row0;
             grp_srcpar[g] = parity[row0 + a];                      // the ancestor's live buffer, before any flip
-            for (int w = 0; w < mask_words; ++w) {
-                unsigned long long bits = 0;
-                const int hi = min(N - w * 64, 64);
-                for (int j = 0; j < hi; ++j) if (sh_anc[w * 64 + j] == a) bits |= 1ull << j;
-                grp_mask[(int64_t)g * mask_words + w] = bits;
-            }
+            for (int w = 0; w < mask_words; ++w) grp_mask[(int64_t)g * mask_words + w] = 0ull;
+            sh_group[a] = g;
         }
         placed += __popcll(mk);
+    }
+    __syncthreads();                                               // group numbers known, bit sets cleared
+    for (int k = lane; k < N; k += kWave) {
+        const int a = sh_anc[k];
+        if (a >= 0) atomicOr(&grp_mask[(int64_t)sh_group[a] * mask_words + (k >> 6)], 1ull << (k & 63));
     }
     __syncthreads();                                               // every group has recorded its source parity
     for (int k = lane; k < N; k += kWave) {

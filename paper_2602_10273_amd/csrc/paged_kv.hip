@@ -15,7 +15,8 @@
 // tables can be compared bit for bit with a CPU model that follows them.
 //
 //   paged_init_kernel     : the state after len0 appends with no resampling (table[b*N+k, j] = b*Q + j*N + k)
-//   paged_reindex_kernel  : one workgroup per resampled prompt; table rows copied by ancestor, counts recounted
+//   paged_snapshot_kernel : copies the table rows of resampled prompts aside
+//   paged_reindex_kernel  : table[k, :] = old table[anc[k], :]; old row a's pages gain copies(a) - 1 references
 //   paged_prepare_kernel  : one workgroup per prompt; finds the needy rows, the lowest free pages, writes the slot of
 //                           every row and the list of (source page, new page) pairs
 //   paged_copy_kernel     : grid-stride over (pair, tensor, head): 16-byte vector copy of the filled part of a page
@@ -25,6 +26,8 @@ namespace psmc {
 
 namespace {
 constexpr int kPagedThreads = 256;
+constexpr int kEntriesPerBlock = 2048;               // table entries one workgroup of the reorder handles
+constexpr int kScanPerThread = 32;                  // reference counts one thread examines per sweep of the free-page search
 typedef unsigned int vec16 __attribute__((ext_vector_type(4)));
 
 // Exclusive prefix sum of one int per thread over the 256-thread workgroup; `total` is the sum over all threads.
@@ -64,31 +67,52 @@ __global__ void paged_init_kernel(int R, int N, int M, int Q, int P, int len0, i
     if (i < 4) counters[i] = 0;                        // pair counters of the two phases, allocation failures, spare
 }
 
+// Reorder, part 1: the in-use columns of a resampled prompt's table rows are copied aside.
+// Grid: prompts x chunks of kEntriesPerBlock table entries.
+__global__ __launch_bounds__(kPagedThreads) void paged_snapshot_kernel(
+    const int32_t* __restrict__ resampled, int N, int M, int ncol, int chunks, const int32_t* __restrict__ table,
+    int32_t* __restrict__ table_tmp)
+{
+    const int b = blockIdx.x / chunks;
+    if (!resampled[b]) return;
+    const int n = N * ncol;
+    const int e0 = (blockIdx.x % chunks) * kEntriesPerBlock;
+    for (int e = e0 + threadIdx.x; e < min(n, e0 + kEntriesPerBlock); e += kPagedThreads) {
+        const int64_t at = (int64_t)(b * N + e / ncol) * M + e % ncol;
+        table_tmp[at] = table[at];
+    }
+}
+
+// Reorder, part 2: table[k, j] = old table[anc[k], j].  Old row a's page for column j gains copies(a) - 1 references,
+// copies(a) being the number of rows that continue a; a page whose count reaches 0 is free from then on.
 __global__ __launch_bounds__(kPagedThreads) void paged_reindex_kernel(
-    const int32_t* __restrict__ anc, const int32_t* __restrict__ resampled, int N, int M, int Q, int ncol,
-    int32_t* __restrict__ table, int32_t* __restrict__ table_tmp, int32_t* __restrict__ refcnt)
+    const int32_t* __restrict__ anc, const int32_t* __restrict__ resampled, int N, int M, int Q, int ncol, int chunks,
+    int32_t* __restrict__ table, const int32_t* __restrict__ table_tmp, int32_t* __restrict__ refcnt)
 {
     __shared__ int32_t sh_anc[SMC_MAX_PARTICLES];
-    const int b = blockIdx.x, tid = threadIdx.x;
+    __shared__ int32_t sh_copies[SMC_MAX_PARTICLES];
+    const int b = blockIdx.x / chunks, tid = threadIdx.x;
     if (!resampled[b]) return;
     const int row0 = b * N, page0 = b * Q;
+    for (int k = tid; k < N; k += kPagedThreads) sh_copies[k] = 0;
+    __syncthreads();
     for (int k = tid; k < N; k += kPagedThreads) {
         int a = anc[row0 + k] - row0;
         if (a < 0 || a >= N) a = k;                    // outside the prompt: the row keeps its own pages
         sh_anc[k] = a;
+        atomicAdd(&sh_copies[a], 1);
     }
-    const int n = N * ncol;
-    for (int e = tid; e < n; e += kPagedThreads) {
-        const int64_t at = (int64_t)(row0 + e / ncol) * M + e % ncol;
-        table_tmp[at] = table[at];
-    }
-    for (int i = tid; i < Q; i += kPagedThreads) refcnt[page0 + i] = 0;
     __syncthreads();
-    for (int e = tid; e < n; e += kPagedThreads) {
+    const int n = N * ncol;
+    const int e0 = (blockIdx.x % chunks) * kEntriesPerBlock;
+    for (int e = e0 + tid; e < min(n, e0 + kEntriesPerBlock); e += kPagedThreads) {
         const int k = e / ncol, j = e % ncol;
-        const int p = table_tmp[(int64_t)(row0 + sh_anc[k]) * M + j];
-        table[(int64_t)(row0 + k) * M + j] = p;
-        if (p >= page0 && p < page0 + Q) atomicAdd(&refcnt[p], 1);
+        table[(int64_t)(row0 + k) * M + j] = table_tmp[(int64_t)(row0 + sh_anc[k]) * M + j];
+        const int gained = sh_copies[k] - 1;
+        if (gained != 0) {
+            const int p = table_tmp[(int64_t)(row0 + k) * M + j];
+            if (p >= page0 && p < page0 + Q) atomicAdd(&refcnt[p], gained);
+        }
     }
 }
 
@@ -125,15 +149,35 @@ __global__ __launch_bounds__(kPagedThreads) void paged_prepare_kernel(
         if (k < N) sh_rank[k] = needy ? n_needy + before : -1;
         n_needy += total;
     }
-    // the n_needy lowest free pages of the prompt: each thread counts the free pages of a contiguous range
-    const int chunk = (Q + kPagedThreads - 1) / kPagedThreads;
-    const int lo = min(Q, tid * chunk), hi = min(Q, lo + chunk);
-    int n_free_mine = 0;
-    for (int i = lo; i < hi; ++i) n_free_mine += refcnt[page0 + i] == 0;
-    int n_free;
-    int z = block_exclusive_scan(n_free_mine, sh_wave, n_free);
-    for (int i = lo; i < hi && z < n_needy; ++i)
-        if (refcnt[page0 + i] == 0) sh_free[z++] = i;
+    // the n_needy lowest free pages of the prompt.  Sweeps of 256*32 pages: every thread loads the counts of 32
+    // consecutive pages (independent 16-byte loads), one prefix sum over the workgroup orders the free ones.
+    int n_free = 0;
+    for (int base = 0; base < Q && n_free < n_needy; base += kPagedThreads * kScanPerThread) {
+        const int lo = base + tid * kScanPerThread;
+        int cnt[kScanPerThread];
+        if (lo + kScanPerThread <= Q && ((page0 + lo) & 3) == 0) {
+            const int4* src = reinterpret_cast<const int4*>(refcnt + page0 + lo);
+#pragma unroll
+            for (int v = 0; v < kScanPerThread / 4; ++v) {
+                const int4 x = src[v];
+                cnt[4 * v] = x.x; cnt[4 * v + 1] = x.y; cnt[4 * v + 2] = x.z; cnt[4 * v + 3] = x.w;
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < kScanPerThread; ++i) cnt[i] = lo + i < Q ? refcnt[page0 + lo + i] : 1;
+        }
+        unsigned free_bits = 0;
+#pragma unroll
+        for (int i = 0; i < kScanPerThread; ++i) free_bits |= (cnt[i] == 0 ? 1u : 0u) << i;
+        int total;
+        int z = n_free + block_exclusive_scan(__popc(free_bits), sh_wave, total);
+        while (free_bits && z < n_needy) {
+            const int i = __ffs(free_bits) - 1;
+            free_bits &= free_bits - 1;
+            sh_free[z++] = lo + i;
+        }
+        n_free += total;
+    }
     const int n_served = min(n_needy, n_free);         // n_free >= n_needy unless the table was corrupted
     if (tid == 0) {
         sh_base = (o > 0 && n_served > 0) ? atomicAdd(&counters[phase], n_served) : 0;
@@ -300,8 +344,13 @@ smc_status smc_paged_reindex(smc_ctx* ctx, const int32_t* d_anc, const int32_t* 
     if (launch_reindex(ctx, d_anc, d_resampled, 0, t) != hipSuccess) return SMC_E_HIP;
     const int ncol = (p.len + p.P - 1) / p.P;
     if (ncol > 0) {
-        hipLaunchKernelGGL(paged_reindex_kernel, dim3(ctx->cfg.B), dim3(kPagedThreads), 0, ctx->stream, d_anc, d_resampled,
-                           ctx->cfg.N, p.M, p.Q, ncol, p.table, p.table_tmp, p.refcnt);
+        const int N = ctx->cfg.N;
+        const int chunks = (int)(((int64_t)N * ncol + kEntriesPerBlock - 1) / kEntriesPerBlock);
+        const dim3 grid((unsigned)((int64_t)chunks * ctx->cfg.B));
+        hipLaunchKernelGGL(paged_snapshot_kernel, grid, dim3(kPagedThreads), 0, ctx->stream, d_resampled, N, p.M, ncol, chunks,
+                           p.table, p.table_tmp);
+        hipLaunchKernelGGL(paged_reindex_kernel, grid, dim3(kPagedThreads), 0, ctx->stream, d_anc, d_resampled, N, p.M, p.Q,
+                           ncol, chunks, p.table, p.table_tmp, p.refcnt);
         if (hipGetLastError() != hipSuccess) return SMC_E_HIP;
     }
     return SMC_OK;
