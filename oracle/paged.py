@@ -44,7 +44,7 @@ class PagedKV:
     # -- allocation -------------------------------------------------------------------------------------------
     def _free_pages(self, b):
         lo = b * self.Q
-        return [lo + i for i in range(self.Q) if self.refcnt[lo + i] == 0]
+        return (lo + np.nonzero(self.refcnt[lo:lo + self.Q] == 0)[0]).tolist()
 
     def prepare_append(self, pos):
         """Makes table[r, pos // P] exclusively owned by every row r.  Returns (slot[R], [(src_page, dst_page)])."""

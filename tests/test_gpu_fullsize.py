@@ -124,3 +124,58 @@ def test_full_size_reindex_sampled_rows(name, layers):
     assert torch.equal(s.kvB[ten].view(torch.int16)[sel], want[sel])
     del want
     s.close()
+
+
+@pytest.mark.parametrize("name,P", [("cfg2", 16), ("cfg5", 16), ("cfg4", 64), ("cfg3", 128)])
+def test_full_size_paged_reorder(name, P):
+    """Paged cache at the full row geometry (one layer): tables, counts and slots against the CPU model at every step,
+    the logical content of the whole cache against a dense copy kept with index_select."""
+    from oracle.paged import PagedKV
+    w = synth.scaled(synth.WORKLOADS[name], layers=1)
+    steps = 24
+    len0 = w.S - steps - 3
+    rng = np.random.default_rng(8)
+    s = Session(w.B, w.N, w.V, 8, w.dtype, w.kappa, 0, kv_geom=(2, w.H, w.S, w.D), with_hist=False, page_len=P, len0=len0)
+    pk = PagedKV(w.B, w.N, w.H, w.S, w.D, P, 0)                 # tables only: the content is checked against `dense`
+    pk.reset(len0)
+    g = torch.Generator(device="cuda"); g.manual_seed(12)
+    for pool in s.pools:
+        pool.view(torch.int16).random_(-32768, 32767, generator=g)
+
+    def logical(ten, table, length):
+        ncol = (length + P - 1) // P
+        idx = torch.as_tensor(table[:, :ncol].astype(np.int64)).cuda()
+        pages = s.pools[ten].view(torch.int16)[idx]             # [R, ncol, H, P, D]
+        return pages.permute(0, 2, 1, 3, 4).reshape(w.R, w.H, ncol * P, w.D)[:, :, :length]
+
+    table, refcnt = s.paged_state()
+    assert np.array_equal(table, pk.table) and np.array_equal(refcnt, pk.refcnt)
+    dense = [logical(ten, table, len0).clone() for ten in range(2)]
+    dense = [torch.cat([d, torch.zeros((w.R, w.H, w.S - len0, w.D), dtype=torch.int16, device="cuda")], dim=2) for d in dense]
+    copied = 0
+    for i in range(steps):
+        pos = len0 + i
+        slot_ref, copies = pk.prepare_append(pos)
+        copied += len(copies)
+        s.prepare_append(pos)
+        assert np.array_equal(s.slot.cpu().numpy(), slot_ref), pos
+        for ten in range(2):
+            new = torch.randint(-32768, 32767, (w.R, w.H, w.D), dtype=torch.int16, device="cuda", generator=g)
+            s.pools[ten].view(torch.int16)[s.slot.long(), :, pos % P, :] = new
+            dense[ten][:, :, pos, :] = new
+        flag = (rng.random(w.B) < 0.7).astype(np.int32)
+        anc = np.arange(w.R, dtype=np.int32)
+        for b in range(w.B):
+            if flag[b]:
+                anc[b * w.N:(b + 1) * w.N] = b * w.N + np.sort(rng.choice(w.N, size=w.N, p=rng.dirichlet(np.full(w.N, 0.5))))
+        pk.reindex(anc, flag)
+        s.paged_reindex(0, torch.as_tensor(anc).cuda(), torch.as_tensor(flag).cuda())
+        idx = torch.as_tensor(anc.astype(np.int64)).cuda()
+        dense = [d.index_select(0, idx) for d in dense]
+        table, refcnt = s.paged_state()
+        ncol = (pos + 1 + P - 1) // P
+        assert np.array_equal(table[:, :ncol], pk.table[:, :ncol]) and np.array_equal(refcnt, pk.refcnt), pos
+    assert copied > 0 and smc.smc_paged_check(s.ctx) == 0
+    for ten in range(2):
+        assert torch.equal(logical(ten, table, len0 + steps), dense[ten][:, :, :len0 + steps]), ten
+    s.close()
