@@ -24,14 +24,11 @@ constexpr int kGatherThreads = 256;
 typedef unsigned int vec16 __attribute__((ext_vector_type(4)));    // one 16-byte global load / store
 }  // namespace
 
-// phase: which of the plan's two group counters this call uses; the other one is cleared for the next call.
-__global__ __launch_bounds__(kWave) void plan_kernel(const int32_t* __restrict__ anc, const int32_t* __restrict__ resampled,
-                                                     int N, int mask_words, int phase, GatherPlan* __restrict__ plan,
-                                                     int32_t* __restrict__ grp_src, int32_t* __restrict__ grp_base,
-                                                     int32_t* __restrict__ grp_srcpar,
-                                                     unsigned long long* __restrict__ grp_mask,
-                                                     double* __restrict__ cumlogp, int32_t* __restrict__ done,
-                                                     int32_t* __restrict__ parity)
+// The plan of one resampled prompt (one wave).  phase: which of the plan's two group counters this call uses.
+__device__ void plan_prompt(const int32_t* __restrict__ anc, int N, int mask_words, int phase, GatherPlan* __restrict__ plan,
+                            int32_t* __restrict__ grp_src, int32_t* __restrict__ grp_base, int32_t* __restrict__ grp_srcpar,
+                            unsigned long long* __restrict__ grp_mask, double* __restrict__ cumlogp,
+                            int32_t* __restrict__ done, int32_t* __restrict__ parity)
 {
     __shared__ int32_t sh_anc[SMC_MAX_PARTICLES];
     __shared__ double sh_cum[SMC_MAX_PARTICLES];
@@ -40,8 +37,6 @@ __global__ __launch_bounds__(kWave) void plan_kernel(const int32_t* __restrict__
     __shared__ int32_t sh_group[SMC_MAX_PARTICLES];                // group number of each ancestor that has one
     __shared__ int32_t sh_base;
     const int b = blockIdx.x, lane = threadIdx.x;
-    if (b == 0 && lane == 0) plan->n_groups[phase ^ 1] = 0;
-    if (!resampled[b]) return;
     const int row0 = b * N;
     int bad = 0;
     for (int k = lane; k < N; k += kWave) {
@@ -101,6 +96,31 @@ __global__ __launch_bounds__(kWave) void plan_kernel(const int32_t* __restrict__
     }
 }
 
+// One wave per prompt.  The two group counters alternate between successive plans, and the switch happens on the
+// device: every workgroup reads plan->phase first and takes a ticket last, and the workgroup with the last ticket
+// clears the other counter for the next plan and flips the phase.  No host-side state is involved, so a captured
+// launch sequence can be replayed.
+__global__ __launch_bounds__(kWave) void plan_kernel(const int32_t* __restrict__ anc, const int32_t* __restrict__ resampled,
+                                                     int N, int mask_words, GatherPlan* __restrict__ plan,
+                                                     int32_t* __restrict__ grp_src, int32_t* __restrict__ grp_base,
+                                                     int32_t* __restrict__ grp_srcpar,
+                                                     unsigned long long* __restrict__ grp_mask,
+                                                     double* __restrict__ cumlogp, int32_t* __restrict__ done,
+                                                     int32_t* __restrict__ parity)
+{
+    const int phase = plan->phase;
+    if (resampled[blockIdx.x])
+        plan_prompt(anc, N, mask_words, phase, plan, grp_src, grp_base, grp_srcpar, grp_mask, cumlogp, done, parity);
+    if (threadIdx.x == 0) {
+        __threadfence();                                           // the read of plan->phase precedes the ticket
+        if (atomicAdd(&plan->ticket, 1) == (int)gridDim.x - 1) {
+            plan->n_groups[phase ^ 1] = 0;
+            plan->ticket = 0;
+            plan->phase = phase ^ 1;
+        }
+    }
+}
+
 struct GatherGeom {               // one family of tensors with identical geometry
     void* const* bufA; void* const* bufB;
     int n_tensors, n_chunks, slabs_per_chunk;
@@ -113,13 +133,13 @@ struct GatherGeom {               // one family of tensors with identical geomet
 // NT_LD / NT_ST: non-temporal loads / stores.
 template <int VPT, bool NT_LD, bool NT_ST>
 __global__ __launch_bounds__(kGatherThreads) void gather_kernel(
-    GatherGeom kv, GatherGeom hist, const int32_t* __restrict__ parity, int mask_words, int phase,
+    GatherGeom kv, GatherGeom hist, const int32_t* __restrict__ parity, int mask_words,
     const GatherPlan* __restrict__ plan, const int32_t* __restrict__ grp_src, const int32_t* __restrict__ grp_base,
     const int32_t* __restrict__ grp_srcpar, const unsigned long long* __restrict__ grp_mask)
 {
     constexpr int kVecPerThread = VPT;
     constexpr int kSlabBytes = kGatherThreads * VPT * 16;
-    const int n_groups = plan->n_groups[phase];
+    const int n_groups = plan->n_groups[plan->phase ^ 1];          // the plan flipped the phase after using it
     const int64_t per_group_kv = (int64_t)kv.n_tensors * kv.n_chunks * kv.slabs_per_chunk;
     const int64_t per_group_h = (int64_t)hist.n_tensors * hist.n_chunks * hist.slabs_per_chunk;
     const int64_t total_kv = per_group_kv * n_groups;
@@ -184,7 +204,7 @@ static void launch_gather(smc_ctx* c, GatherGeom kv, GatherGeom hist)
     hist.slabs_per_chunk = (int)((hist.copy_bytes + slab - 1) / slab);
     auto& w = c->ws;
     hipLaunchKernelGGL((gather_kernel<VPT, NT_LD, NT_ST>), dim3(c->gather_grid), dim3(kGatherThreads), 0, c->stream, kv, hist,
-                       w.parity, c->mask_words, c->plan_phase, w.plan, w.grp_src, w.grp_base, w.grp_srcpar, w.grp_mask);
+                       w.parity, c->mask_words, w.plan, w.grp_src, w.grp_base, w.grp_srcpar, w.grp_mask);
 }
 
 static void launch_gather_variant(smc_ctx* c, int variant, const GatherGeom& kv, const GatherGeom& hist)
@@ -213,9 +233,8 @@ hipError_t launch_reindex(smc_ctx* c, const int32_t* anc, const int32_t* resampl
     auto& w = c->ws;
     const bool have_kv = c->kv_bound && cfg.kv_tensors > 0 && valid_len > 0;
     const bool have_hist = c->hist_bound && t > 0;
-    c->plan_phase ^= 1;
     hipLaunchKernelGGL(plan_kernel, dim3(cfg.B), dim3(kWave), 0, c->stream, anc, resampled, cfg.N, c->mask_words,
-                       c->plan_phase, w.plan, w.grp_src, w.grp_base, w.grp_srcpar, w.grp_mask, w.cumlogp, w.done, w.parity);
+                       w.plan, w.grp_src, w.grp_base, w.grp_srcpar, w.grp_mask, w.cumlogp, w.done, w.parity);
     if (have_kv || have_hist) {
         GatherGeom kv{}, hist{};
         if (have_kv) {

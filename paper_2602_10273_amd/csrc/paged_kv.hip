@@ -64,7 +64,7 @@ __global__ void paged_init_kernel(int R, int N, int M, int Q, int P, int len0, i
         table[i] = j < ncol ? b * Q + j * N + k : -1;
     }
     if (i < (int64_t)(R / N) * Q) refcnt[i] = (int)(i % Q) < ncol * N ? 1 : 0;
-    if (i < 4) counters[i] = 0;                        // pair counters of the two phases, allocation failures, spare
+    if (i < 8) counters[i] = 0;                        // pair counters of the two phases, failures, phase, ticket
 }
 
 // Reorder, part 1: the in-use columns of a resampled prompt's table rows are copied aside.
@@ -116,9 +116,12 @@ __global__ __launch_bounds__(kPagedThreads) void paged_reindex_kernel(
     }
 }
 
-// counters: [0], [1] number of (source, new page) pairs of the two phases; [2] rows that found no free page.
+// counters: [0], [1] number of (source, new page) pairs, alternating between successive calls; [2] rows that found no
+// free page; [3] the pair counter the next call uses; [4] workgroups of the running call that have finished.  Every
+// workgroup reads counters[3] first and takes a ticket last; the one with the last ticket clears the other pair
+// counter and flips counters[3] (no host-side state, so a captured launch sequence can be replayed).
 __global__ __launch_bounds__(kPagedThreads) void paged_prepare_kernel(
-    int N, int M, int Q, int j, int o, int phase, int32_t* __restrict__ table, int32_t* __restrict__ refcnt,
+    int N, int M, int Q, int j, int o, int32_t* __restrict__ table, int32_t* __restrict__ refcnt,
     int32_t* __restrict__ counters, int32_t* __restrict__ cow_src, int32_t* __restrict__ cow_dst,
     int32_t* __restrict__ slot)
 {
@@ -129,7 +132,7 @@ __global__ __launch_bounds__(kPagedThreads) void paged_prepare_kernel(
     __shared__ int32_t sh_base;
     const int b = blockIdx.x, tid = threadIdx.x;
     const int row0 = b * N, page0 = b * Q;
-    if (b == 0 && tid == 0) counters[phase ^ 1] = 0;   // the other phase's counter, for the next call
+    const int phase = counters[3];
     for (int k = tid; k < N; k += kPagedThreads) sh_page[k] = o == 0 ? -1 : table[(int64_t)(row0 + k) * M + j];
     __syncthreads();
     // needy rows: all of them at a page start; otherwise every sharer of a page but the lowest
@@ -198,16 +201,24 @@ __global__ __launch_bounds__(kPagedThreads) void paged_prepare_kernel(
         }
         slot[row0 + k] = page;
     }
+    if (tid == 0) {
+        __threadfence();                               // the read of counters[3] precedes the ticket
+        if (atomicAdd(&counters[4], 1) == (int)gridDim.x - 1) {
+            counters[phase ^ 1] = 0;
+            counters[4] = 0;
+            counters[3] = phase ^ 1;
+        }
+    }
 }
 
 // Copies the first copy_bytes bytes (a multiple of 16) of each of the n_heads head chunks of a page, for every tensor
 // and every (source page, new page) pair.
 __global__ __launch_bounds__(kPagedThreads) void paged_copy_kernel(
     void* const* __restrict__ pools, int n_tensors, int n_heads, long long page_stride, long long head_stride,
-    long long copy_bytes, int n_pages, int phase, const int32_t* __restrict__ counters,
+    long long copy_bytes, int n_pages, const int32_t* __restrict__ counters,
     const int32_t* __restrict__ cow_src, const int32_t* __restrict__ cow_dst)
 {
-    const int n_pairs = counters[phase];
+    const int n_pairs = counters[counters[3] ^ 1];     // the prepare kernel flipped the phase after using it
     const int64_t per_pair = (int64_t)n_tensors * n_heads;
     const int64_t total = per_pair * n_pairs;
     for (int64_t w = blockIdx.x; w < total; w += gridDim.x) {
@@ -260,7 +271,7 @@ size_t paged_layout(const smc_config* c, const PagedDims& d, char* base, PagedKV
     q = take(d.n_pages * 4); if (p) p->refcnt = (int32_t*)q;
     q = take(R * 4); if (p) p->cow_src = (int32_t*)q;
     q = take(R * 4); if (p) p->cow_dst = (int32_t*)q;
-    q = take(4 * 4); if (p) p->counters = (int32_t*)q;
+    q = take(8 * 4); if (p) p->counters = (int32_t*)q;
     q = take((size_t)c->kv_tensors * sizeof(void*)); if (p) p->pools = (void**)q;
     return off;
 }
@@ -298,7 +309,7 @@ smc_status smc_paged_bind(smc_ctx* ctx, void* const* h_pools, int32_t page_len, 
     if (hipStreamSynchronize(ctx->stream) != hipSuccess) return SMC_E_HIP;
     PagedKV& p = ctx->paged;
     paged_layout(&ctx->cfg, d, (char*)d_workspace, &p);
-    p.P = d.P; p.M = d.M; p.Q = d.Q; p.len = len0; p.phase = 0;
+    p.P = d.P; p.M = d.M; p.Q = d.Q; p.len = len0;
     if (hipMemcpy(p.pools, h_pools, (size_t)ctx->cfg.kv_tensors * sizeof(void*), hipMemcpyHostToDevice) != hipSuccess)
         return SMC_E_HIP;
     const size_t n = d.n_table > d.n_pages ? d.n_table : d.n_pages;
@@ -318,8 +329,7 @@ smc_status smc_paged_prepare_append(smc_ctx* ctx, int32_t pos, int32_t* d_slot_o
     if (pos != p.len) return SMC_E_STATE;              // positions are appended one by one, the same for every row
     const auto& cfg = ctx->cfg;
     const int j = pos / p.P, o = pos % p.P;
-    p.phase ^= 1;
-    hipLaunchKernelGGL(paged_prepare_kernel, dim3(cfg.B), dim3(kPagedThreads), 0, ctx->stream, cfg.N, p.M, p.Q, j, o, p.phase,
+    hipLaunchKernelGGL(paged_prepare_kernel, dim3(cfg.B), dim3(kPagedThreads), 0, ctx->stream, cfg.N, p.M, p.Q, j, o,
                        p.table, p.refcnt, p.counters, p.cow_src, p.cow_dst, d_slot_out);
     if (o > 0) {
         const long long pos_bytes = (long long)cfg.kv_D * cfg.kv_elem_bytes;
@@ -327,7 +337,7 @@ smc_status smc_paged_prepare_append(smc_ctx* ctx, int32_t pos, int32_t* d_slot_o
         ScopedKernelTimer timer(ctx, 2);
         hipLaunchKernelGGL(paged_copy_kernel, dim3(ctx->n_cus * 8), dim3(kPagedThreads), 0, ctx->stream,
                            (void* const*)p.pools, cfg.kv_tensors, cfg.kv_H, head_stride * cfg.kv_H, head_stride,
-                           pos_bytes * o, cfg.B * p.Q, p.phase, p.counters, p.cow_src, p.cow_dst);
+                           pos_bytes * o, cfg.B * p.Q, p.counters, p.cow_src, p.cow_dst);
     }
     if (hipGetLastError() != hipSuccess) return SMC_E_HIP;
     p.len = pos + 1;

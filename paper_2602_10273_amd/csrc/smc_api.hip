@@ -124,7 +124,6 @@ smc_status smc_init(const smc_config* cfg, void* d_workspace, size_t workspace_b
     c->mask_words = (cfg->N + 63) / 64;
     c->resampler = 0;
     c->ancestor_order = 0;
-    c->plan_phase = 0;
     c->kv_bound = 0;
     c->hist_bound = 0;
     c->profiling = 0;

@@ -35,7 +35,9 @@ static_assert(sizeof(Partial) == 48, "Partial layout");
 struct GatherPlan {
     int32_t n_groups[2];          // number of (ancestor, descendants) groups; successive calls alternate the counter
     int32_t bad_anc;              // ancestors outside their prompt's row range (ignored rows)
-    int32_t pad;
+    int32_t phase;                // counter the NEXT plan uses; flipped on the device by the last workgroup of a plan
+    int32_t ticket;               // workgroups of the running plan that have finished
+    int32_t pad[3];
 };
 
 struct Workspace {                // device pointers carved out of the caller's workspace
@@ -65,13 +67,12 @@ struct PagedKV {
     int bound;
     int P, M, Q;                  // positions per page, pages per row, pages per prompt (= N*M)
     int len;                      // positions appended so far (the same for every row)
-    int phase;                    // which pair counter the current append uses
     int32_t* table;               // [R*M] page of row r for positions [j*P, (j+1)*P), -1 while unused
     int32_t* table_tmp;           // [R*M] the reorder's copy of the old table
     int32_t* refcnt;              // [B*Q] rows that reference a page; 0 = free
     int32_t* cow_src;             // [R] source page of each pending copy
     int32_t* cow_dst;             // [R] new page of each pending copy
-    int32_t* counters;            // [4] pairs of phase 0 / 1, rows that found no free page, spare
+    int32_t* counters;            // [8] pairs of phase 0 / 1, rows that found no free page, phase, ticket, spare
     void** pools;                 // [kv_tensors] page pools [B*Q, H, P, D]
 };
 
@@ -92,7 +93,6 @@ struct smc_ctx {
     int kv_bound;
     int hist_bound;
     int gather_grid;              // workgroups of the persistent gather kernel
-    int plan_phase;               // which group counter the current reindex uses
     int gather_variant;           // vectors per thread / non-temporal choice of the gather kernel
     int n_cus;
     // optional per-kernel timing: event pairs recorded around launches of kind 0 (vocab pass), 1 (KV gather) and

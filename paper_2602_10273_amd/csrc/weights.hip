@@ -193,7 +193,7 @@ __global__ void init_state_kernel(double* logW, double* cumlogp, int32_t* parity
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < R) { logW[i] = 0.0; cumlogp[i] = 0.0; done[i] = 0; parity[i] = 0; rowstat[3 * i] = 0; rowstat[3 * i + 1] = 0; rowstat[3 * i + 2] = 0; }
     if (i == 0) {
-        plan->n_groups[0] = 0; plan->n_groups[1] = 0; plan->bad_anc = 0;
+        plan->n_groups[0] = 0; plan->n_groups[1] = 0; plan->bad_anc = 0; plan->phase = 0; plan->ticket = 0;
     }
 }
 
