@@ -37,6 +37,8 @@ namespace {
 
 constexpr float kLog2e = 1.4426950408889634f;
 
+typedef unsigned int vec16 __attribute__((ext_vector_type(4)));    // one 16-byte global load
+
 template <int DT> struct Elems;
 template <> struct Elems<SMC_BF16> { static constexpr int kPerVec = 8; using Scalar = uint16_t; };
 template <> struct Elems<SMC_F32>  { static constexpr int kPerVec = 4; using Scalar = float; };
@@ -205,7 +207,7 @@ __global__ __launch_bounds__(NW * kWave) void vocab_pass_kernel(
     uint32_t step, int n_split, int vecs_per_split, Partial* __restrict__ partials, const int32_t* __restrict__ done)
 {
     constexpr int EPV = Elems<DT>::kPerVec;
-    constexpr int UNROLL = 4;
+    constexpr int UNROLL = 4;                          // 16-byte vectors per thread and batch (two batches in flight)
     constexpr int THREADS = NW * kWave;
     constexpr int kRing = 1024;                        // candidate ring entries per wave (power of two)
     static_assert(kRing >= 2 * EPV * kWave, "a full vector of candidates must fit beside a partly filled ring");
@@ -375,7 +377,11 @@ __global__ __launch_bounds__(NW * kWave) void vocab_pass_kernel(
     auto load_batch = [&](uint4 (&dst)[UNROLL], int b0) {
         if (b0 + kBatch <= full_end) {                                     // uniform
 #pragma unroll
-            for (int u = 0; u < UNROLL; ++u) dst[u] = *(const uint4*)(rowp + (int64_t)(b0 + u * THREADS + tid) * 16);
+            for (int u = 0; u < UNROLL; ++u) {
+                // every logit is read exactly once: non-temporal loads keep the stream out of the caches
+                const vec16 r = __builtin_nontemporal_load((const vec16*)(rowp + (int64_t)(b0 + u * THREADS + tid) * 16));
+                dst[u] = make_uint4(r.x, r.y, r.z, r.w);
+            }
         } else {
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) {
