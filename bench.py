@@ -34,6 +34,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kv", action="store_true", help="vocabulary pass + weights only (no cache bound)")
     ap.add_argument("--n-split", type=int, default=0)
+    ap.add_argument("--mode", default="step", choices=["step", "reindex"],
+                    help="step: the whole hot path (default); reindex: the KV reorder alone, every prompt resampled "
+                         "with synthetic ancestors (sorted draws from Dirichlet(0.5) weights)")
     ap.add_argument("--paged", type=int, default=0, metavar="P",
                     help="paged cache with P positions per page: the reorder copies page numbers, appends copy on write")
     ap.add_argument("--in-place", action="store_true",
@@ -88,6 +91,65 @@ def cpu_baseline(w, seed, gpu_resample_frac):
     }
 
 
+def measured_ceilings(smc, torch, dev):
+    """Plain streaming kernels of the library on a 4 GiB buffer: the device's own ceilings for four read:write mixes."""
+    nbytes = 4 << 30
+    buf = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream().cuda_stream
+    out = {name: smc.smc_hbm_probe(kind, buf, nbytes, stream)
+           for kind, name in enumerate(("read", "write", "copy_1r1w", "fanout_1r3w"))}
+    del buf
+    return out
+
+
+def reindex_only(args, w, K, W, smc, synth, Session, np, torch):
+    """The KV reorder alone at the workload's full cache: K launches with distinct synthetic ancestor vectors."""
+    s = Session(w.B, w.N, w.V, 8, w.dtype, w.kappa, args.seed, kv_geom=(w.kv_tensors, w.H, w.S, w.D))
+    g = torch.Generator(device="cuda"); g.manual_seed(args.seed + 12345)
+    for t in s.kvA:
+        t.normal_(generator=g)
+    ancs = [synth.ancestors_numpy(w, args.seed + i) for i in range(W + K)]
+    d_anc = [torch.as_tensor(a).cuda() for a in ancs]
+    flag = torch.ones(w.B, dtype=torch.int32, device="cuda")
+    for i in range(W):
+        s.reindex(w.S, 4, d_anc[i], flag)
+    torch.cuda.synchronize()
+    smc.smc_profile_enable(s.ctx, 1)
+    t0 = time.perf_counter()
+    for i in range(W, W + K):
+        s.reindex(w.S, 4, d_anc[i], flag)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_gather, n_gather = smc.smc_profile_read(s.ctx, 1)
+    smc.smc_profile_enable(s.ctx, 0)
+    ident = np.arange(w.R)
+    rows_written = rows_read = 0
+    for a in ancs[W:]:
+        moved = a != ident
+        rows_written += int(moved.sum())
+        rows_read += sum(len(np.unique(a[b * w.N:(b + 1) * w.N][moved[b * w.N:(b + 1) * w.N]])) for b in range(w.B))
+    total_bytes = float(rows_written + rows_read) * w.kv_row_bytes * w.kv_tensors
+    gbps = total_bytes / (ms_gather * 1e-3) / 1e9
+    s.close()
+    del s
+    torch.cuda.empty_cache()
+    out = {
+        "metric": "particle-steps/s (KV reindex only), 1 MI355X",
+        "value": w.R * K / elapsed, "unit": "particle-steps/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": elapsed / K * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u8", "data": "synthetic",
+        "config": {"workload": w.name, "mode": "reindex", "B": w.B, "N": w.N,
+                   "kv": f"{w.layers}x2 tensors [{w.R},{w.H},{w.S},{w.D}] bf16 x2 buffers", "valid_len": w.S,
+                   "ancestors": "sorted draws from Dirichlet(0.5) weights, every prompt resampled",
+                   "rows_read_per_row_written": rows_read / max(rows_written, 1)},
+        "roofline": {"kernel": "gather_kernel", "bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": gbps / HBM_PEAK_GBPS, "traffic": None, "launches": int(n_gather),
+                     "avg_launch_ms": ms_gather / max(n_gather, 1), "algorithmic_bytes_per_launch": total_bytes / max(n_gather, 1)},
+    }
+    out["measured_ceilings_GBps"] = measured_ceilings(smc, torch, "cuda")
+    print(json.dumps(out))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -103,6 +165,9 @@ def main():
     w = synth.WORKLOADS[args.workload]
     K = args.steps or {"cfg2": 48, "cfg3": 16, "cfg4": 12, "cfg5": 16}[args.workload]
     W = args.warmup
+    if args.mode == "reindex":
+        torch.cuda.set_device(0)
+        return reindex_only(args, w, K, min(W, 2), smc, synth, Session, np, torch)
     dev = "cuda"
     torch.cuda.set_device(0)
     T_max = (W + 2 * K + 8 + 3) // 4 * 4
@@ -212,17 +277,6 @@ def main():
             r["traffic_source"] = "profiles/hbm_traffic_ratio.json x algorithmic bytes of this run"
     dominant, other = (r_gather, r_vocab) if ms_gather >= ms_vocab else (r_vocab, r_gather)
 
-    # plain device copy as a second, measured denominator
-    a = torch.empty(1 << 30, dtype=torch.uint8, device=dev); b = torch.empty_like(a)
-    b.copy_(a); torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(4):
-        b.copy_(a)
-    e1.record(); torch.cuda.synchronize()
-    copy_gbps = 4 * 2 * a.numel() / (e0.elapsed_time(e1) * 1e-3) / 1e9
-    del a, b
-
     out = {
         "metric": "particle-steps/s (SMC step + KV reindex), 1 MI355X",
         "value": w.R * K / elapsed, "unit": "particle-steps/s", "n_gpus": 1, "steps": K, "warmup": W,
@@ -234,11 +288,13 @@ def main():
                    "valid_len": w.S, "resampled_prompt_fraction": resample_frac,
                    "logits_ring": n_ring},
         "roofline": dominant, "roofline_other": other,
-        "device_copy_GBps": copy_gbps,
     }
     s.close()
     del s
     torch.cuda.empty_cache()
+    # the device's own ceilings (plain streaming kernels) as a second, measured denominator
+    out["measured_ceilings_GBps"] = measured_ceilings(smc, torch, dev)
+    out["device_copy_GBps"] = out["measured_ceilings_GBps"]["copy_1r1w"]
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, args.seed, resample_frac if not args.no_kv else 0.0)
     print(json.dumps(out))

@@ -223,6 +223,13 @@ smc_status smc_paged_check(smc_ctx* ctx, int32_t* h_alloc_failures);
 smc_status smc_profile_enable(smc_ctx* ctx, int32_t enable);
 smc_status smc_profile_read(smc_ctx* ctx, int32_t kind, double* h_total_ms, int64_t* h_launches);
 
+/* Measurement helper, not part of the method: the bandwidth a plain streaming kernel reaches on this device over
+ * d_buf (16-byte aligned device memory, bytes >= 1 MiB and a multiple of 64; contents are overwritten), with the
+ * read : write mix of kind 0 = read only, 1 = write only, 2 = copy 1:1 (first half to second half), 3 = one read
+ * fanned out to three writes.  Runs one warm-up and three timed launches on the given stream, synchronises, and
+ * returns bytes moved per second in GB/s.  A second, measured denominator beside the published HBM peak. */
+smc_status smc_hbm_probe(int32_t kind, void* d_buf, size_t bytes, void* hip_stream, double* h_gbps);
+
 const char* smc_status_str(smc_status s);
 
 #ifdef __cplusplus

@@ -154,3 +154,15 @@ def kv_torch(w: Workload, seed: int, device="cuda"):
         t.normal_(generator=g)
         out.append(t)
     return out
+
+
+def ancestors_numpy(w: "Workload", seed: int, concentration: float = 0.5):
+    """Synthetic ancestor vector [R] (global rows) for a stand-alone reorder: per prompt, N sorted draws from weights
+    ~ Dirichlet(concentration) -- sorted with duplicates, as resampling of a moderately degenerate weight vector
+    gives.  Every prompt counts as resampled."""
+    rng = np.random.default_rng([seed, 777])
+    anc = np.empty(w.R, np.int32)
+    for b in range(w.B):
+        p = rng.dirichlet(np.full(w.N, concentration))
+        anc[b * w.N:(b + 1) * w.N] = b * w.N + np.sort(rng.choice(w.N, size=w.N, p=p))
+    return anc
