@@ -10,11 +10,11 @@
 
 #include "power_smc.h"
 
-namespace {
+namespace psmc {
 typedef unsigned int vec16 __attribute__((ext_vector_type(4)));
 constexpr int kThreads = 256, kInFlight = 4;
 
-__global__ __launch_bounds__(kThreads) void probe_read(const vec16* __restrict__ p, size_t n_vec, unsigned* sink)
+__global__ __launch_bounds__(kThreads) void hbm_probe_read(const vec16* __restrict__ p, size_t n_vec, unsigned* sink)
 {
     unsigned acc = 0;
     const size_t stride = (size_t)gridDim.x * kThreads * kInFlight;
@@ -33,7 +33,7 @@ __global__ __launch_bounds__(kThreads) void probe_read(const vec16* __restrict__
 
 // Reads n_vec vectors from src once and writes them to `copies` destinations dst, dst + n_vec, ...; copies = 0 with
 // src == nullptr is the write-only case (one destination, a constant pattern).
-__global__ __launch_bounds__(kThreads) void probe_fanout(const vec16* __restrict__ src, vec16* __restrict__ dst, size_t n_vec,
+__global__ __launch_bounds__(kThreads) void hbm_probe_fanout(const vec16* __restrict__ src, vec16* __restrict__ dst, size_t n_vec,
                                                          int copies)
 {
     const size_t stride = (size_t)gridDim.x * kThreads * kInFlight;
@@ -52,7 +52,9 @@ __global__ __launch_bounds__(kThreads) void probe_fanout(const vec16* __restrict
             }
     }
 }
-}  // namespace
+}  // namespace psmc
+
+using namespace psmc;
 
 extern "C" smc_status smc_hbm_probe(int32_t kind, void* d_buf, size_t bytes, void* hip_stream, double* h_gbps)
 {
@@ -70,10 +72,10 @@ extern "C" smc_status smc_hbm_probe(int32_t kind, void* d_buf, size_t bytes, voi
     size_t moved = 0;
     auto launch = [&]() {
         switch (kind) {
-            case 0: hipLaunchKernelGGL(probe_read, grid, block, 0, st, p, n_all, (unsigned*)d_buf); moved = bytes; break;
-            case 1: hipLaunchKernelGGL(probe_fanout, grid, block, 0, st, (const vec16*)nullptr, p, n_all, 0); moved = bytes; break;
-            case 2: hipLaunchKernelGGL(probe_fanout, grid, block, 0, st, p, p + n_all / 2, n_all / 2, 1); moved = (n_all / 2) * 32; break;
-            default: hipLaunchKernelGGL(probe_fanout, grid, block, 0, st, p, p + n_all / 4, n_all / 4, 3); moved = (n_all / 4) * 64; break;
+            case 0: hipLaunchKernelGGL(hbm_probe_read, grid, block, 0, st, p, n_all, (unsigned*)d_buf); moved = bytes; break;
+            case 1: hipLaunchKernelGGL(hbm_probe_fanout, grid, block, 0, st, (const vec16*)nullptr, p, n_all, 0); moved = bytes; break;
+            case 2: hipLaunchKernelGGL(hbm_probe_fanout, grid, block, 0, st, p, p + n_all / 2, n_all / 2, 1); moved = (n_all / 2) * 32; break;
+            default: hipLaunchKernelGGL(hbm_probe_fanout, grid, block, 0, st, p, p + n_all / 4, n_all / 4, 3); moved = (n_all / 4) * 64; break;
         }
     };
     hipEvent_t a, b;
