@@ -216,9 +216,23 @@ smc_status smc_paged_view(smc_ctx* ctx, const int32_t** d_table, const int32_t**
 /* Synchronises and returns how many rows ever found no free page (always 0 unless the table was overwritten). */
 smc_status smc_paged_check(smc_ctx* ctx, int32_t* h_alloc_failures);
 
+/* ---- Decode attention over the caches the reorder maintains -------------------------------------------------
+ * Not part of the paper's method: the reader a decoder needs so that neither cache layout has to be repacked.
+ * For every row r, KV head h and query head g of its group (G = n_q_heads / kv_H <= 16):
+ *   out[r, h*G+g, :] = sum_j softmax_j(scale * <q[r, h*G+g, :], K[r, h, j, :]>) V[r, h, j, :],  j < len,
+ * with K = KV tensor k_tensor and V = KV tensor v_tensor of the context (bf16, kv_D = 64 or 128), read from the
+ * paged pools through the page table if smc_paged_bind was called (then len <= positions appended), else from the
+ * live buffer of each row of the tensors given to smc_kv_bind.  d_q: bf16 [R, n_q_heads, kv_D]; d_out: float
+ * [R, n_q_heads, kv_D]; both 16-byte aligned.  d_workspace: at least smc_attn_workspace_bytes (0 = invalid
+ * geometry), 16-byte aligned, scratch for this call only.  Enqueues on the context's stream. */
+size_t smc_attn_workspace_bytes(const smc_config* cfg, int32_t n_q_heads);
+smc_status smc_attn_decode(smc_ctx* ctx, int32_t k_tensor, int32_t v_tensor, const void* d_q, int32_t n_q_heads,
+                           int32_t len, float scale, void* d_workspace, size_t workspace_bytes, float* d_out);
+
 /* Optional timing of the dominant kernels.  While enabled, a pair of HIP events is recorded on the context's
  * stream around every launch of kind 0 (the vocabulary-pass kernel of smc_step), kind 1 (the KV gather kernel of
- * smc_kv_reindex) and kind 2 (the page copy of smc_paged_prepare_append).  smc_profile_read synchronises the stream, returns the summed elapsed milliseconds and the number
+ * smc_kv_reindex), kind 2 (the page copy of smc_paged_prepare_append) and kind 3 (the attention kernel of
+ * smc_attn_decode).  smc_profile_read synchronises the stream, returns the summed elapsed milliseconds and the number
  * of launches of that kind since the last read, and clears them.  Events are host objects; no device memory is used. */
 smc_status smc_profile_enable(smc_ctx* ctx, int32_t enable);
 smc_status smc_profile_read(smc_ctx* ctx, int32_t kind, double* h_total_ms, int64_t* h_launches);

@@ -18,7 +18,8 @@ EXPORTS = ["smc_workspace_bytes", "smc_init", "smc_destroy", "smc_kv_bind", "smc
            "smc_kv_reindex", "smc_final_draw", "smc_get_done", "smc_set_done", "smc_ess_from", "smc_resample_from", "smc_get_state", "smc_set_state", "smc_get_diag",
            "smc_set_tuning", "smc_set_resampler", "smc_set_ancestor_order", "smc_set_gather_tuning", "smc_profile_enable", "smc_profile_read", "smc_status_str",
            "smc_paged_workspace_bytes", "smc_paged_pool_bytes", "smc_paged_bind", "smc_paged_prepare_append",
-           "smc_paged_reindex", "smc_paged_view", "smc_paged_check", "smc_hbm_probe"]
+           "smc_paged_reindex", "smc_paged_view", "smc_paged_check", "smc_hbm_probe",
+           "smc_attn_workspace_bytes", "smc_attn_decode"]
 
 
 class smc_config(C.Structure):
@@ -77,11 +78,15 @@ def lib():
         L.smc_paged_reindex.argtypes = [vp, vp, vp, i32]
         L.smc_paged_view.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), C.POINTER(i32), C.POINTER(i32), C.POINTER(i32)]
         L.smc_paged_check.argtypes = [vp, C.POINTER(i32)]
+        L.smc_attn_workspace_bytes.restype = C.c_size_t
+        L.smc_attn_workspace_bytes.argtypes = [C.POINTER(smc_config), i32]
+        L.smc_attn_decode.argtypes = [vp, i32, i32, vp, i32, i32, C.c_float, vp, C.c_size_t, vp]
         L.smc_hbm_probe.argtypes = [i32, vp, C.c_size_t, vp, C.POINTER(f64)]
         L.smc_status_str.restype = C.c_char_p
         L.smc_status_str.argtypes = [C.c_int]
         for name in EXPORTS:
-            if name not in ("smc_workspace_bytes", "smc_paged_workspace_bytes", "smc_paged_pool_bytes", "smc_status_str"):
+            if name not in ("smc_workspace_bytes", "smc_paged_workspace_bytes", "smc_paged_pool_bytes", "smc_attn_workspace_bytes",
+                            "smc_status_str"):
                 getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -253,3 +258,12 @@ def smc_hbm_probe(kind, d_buf, nbytes, hip_stream=None):
     g = C.c_double()
     _check("smc_hbm_probe", lib().smc_hbm_probe(kind, _ptr(d_buf), nbytes, hip_stream, C.byref(g)))
     return g.value
+
+
+def smc_attn_workspace_bytes(cfg, n_q_heads):
+    return int(lib().smc_attn_workspace_bytes(C.byref(cfg), n_q_heads))
+
+
+def smc_attn_decode(ctx, k_tensor, v_tensor, d_q, n_q_heads, length, scale, d_workspace, workspace_bytes, d_out):
+    _check("smc_attn_decode", lib().smc_attn_decode(ctx, k_tensor, v_tensor, _ptr(d_q), n_q_heads, length, scale,
+                                                    _ptr(d_workspace), workspace_bytes, _ptr(d_out)))

@@ -1,0 +1,351 @@
+// Single-token decode attention that reads the particle caches where the reorder step (Alg. 1 "reorder KV cache by
+// A"; App. C) leaves them: the double-buffered rows (row r lives in buffer parity[r]) or the paged pools (through the
+// page table).  Not part of the paper's method: it is the consumer a decoder needs so that neither layout has to be
+// repacked before attention.  Textbook scaled dot-product attention with grouped query heads:
+//     s_j = scale <q[r, h G + g], K[r, h, j]>,  p = softmax_j s,  out[r, h G + g] = sum_j p_j V[r, h, j],  j < len.
+//
+// gfx950 design.  The kernel is a stream over K and V (each read once, 16-byte loads); the two contractions run on the
+// matrix cores so that the vector ALUs only see the softmax.  One workgroup of 4 waves per (row, KV head, split of the
+// positions); a wave walks tiles of 16 positions:
+//   scores   S^T[pos, head] = K_tile[pos, dim] Q^T[dim, head]: 16x16x16 bf16 MFMA, A = the K tile exactly as loaded
+//            (lane = (pos, 8-dim slice)), B = the group's query heads (padded to 16) preloaded in registers;
+//   softmax  online, base 2, one running maximum per head; the result lane (head, 4 positions) is already the A
+//            operand layout of the second contraction;
+//   output   O[head, dim] += P[head, pos] V_tile[pos, dim]: the V tile goes through LDS (rows padded to 272 bytes, so
+//            the 2-byte transposed reads are conflict-free) to become the B operand; P is fed as bf16 high + low parts
+//            (two MFMAs), which keeps the result within ~1e-5 of fp64.
+// Waves are merged through LDS; with more than one split a second small kernel merges the splits.
+#include <math.h>
+
+#include "smc_internal.hpp"
+
+namespace psmc {
+
+namespace {
+typedef short bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int vec16 __attribute__((ext_vector_type(4)));
+
+constexpr int kAttnWaves = 4;
+constexpr int kTile = 16;                 // positions per MFMA tile
+constexpr int kHeadsPad = 16;             // query heads of a group, padded to the MFMA width
+constexpr float kLog2e = 1.4426950408889634f;
+
+struct AttnSrc {
+    void* const* bufA;          // dense: buffer A tensors; paged: the pools
+    void* const* bufB;          // dense: buffer B tensors
+    const int32_t* parity;      // dense: which buffer holds row r
+    const int32_t* table;       // paged: [R, M] page numbers
+    int paged, P, M;            // positions per page, pages per row
+    int H, S;                   // KV heads, positions per row (dense)
+    int k_tensor, v_tensor;
+};
+
+// Byte address of position pos (< S) of (row, KV head) in tensor `tensor`; D elements of 2 bytes per position.
+template <int D>
+__device__ __forceinline__ const char* position_ptr(const AttnSrc& a, int tensor, int row, int head, int pos)
+{
+    if (a.paged) {
+        const int page = a.table[(int64_t)row * a.M + pos / a.P];
+        return (const char*)a.bufA[tensor] + ((((int64_t)page * a.H + head) * a.P + pos % a.P) * D) * 2;
+    }
+    const char* base = (const char*)(a.parity[row] ? a.bufB[tensor] : a.bufA[tensor]);
+    return base + ((((int64_t)row * a.H + head) * a.S + pos) * D) * 2;
+}
+
+__device__ __forceinline__ bf16x4 lo4(const vec16 v) { bf16x4 r; __builtin_memcpy(&r, &v, 8); return r; }
+__device__ __forceinline__ bf16x4 hi4(const vec16 v) { bf16x4 r; __builtin_memcpy(&r, (const char*)&v + 8, 8); return r; }
+
+// p = hi + lo with hi, lo representable in bf16 (hi by truncation, lo rounded to nearest even); returns the bit patterns
+__device__ __forceinline__ void split_bf16(float p, unsigned& hi, unsigned& lo)
+{
+    const unsigned b = __float_as_uint(p);
+    hi = b >> 16;
+    const unsigned r = __float_as_uint(p - __uint_as_float(b & 0xFFFF0000u));
+    lo = (r + 0x7FFFu + ((r >> 16) & 1u)) >> 16;
+}
+}  // namespace
+
+// Partial result of one split for one query head: reference exponent, sum of weights, unnormalised output.
+// Layout of the workspace: [row, query head, split, 2 + D] floats.
+template <int D>
+__global__ __launch_bounds__(kAttnWaves* kWave) void attn_decode_kernel(
+    AttnSrc src, const uint16_t* __restrict__ q, int Hq, int G, int len, float scale_log2, int n_splits, int tiles_per_split,
+    float* __restrict__ partial, float* __restrict__ out)
+{
+    constexpr int NKL = D / 32;                 // 16-byte K loads per lane and tile
+    constexpr int NDB = D / 16;                 // 16-dim blocks of the output
+    constexpr int NVL = D / 32;                 // 16-byte V loads per lane and tile (16 positions x D x 2 bytes / 64 lanes / 16)
+    constexpr int kRowBytes = D * 2 + 16;       // padded LDS row of a V tile
+    constexpr int kPiecesPerRow = D / 8;        // 16-byte pieces per position
+    __shared__ __attribute__((aligned(16))) char sh_v[kAttnWaves][kTile * kRowBytes];
+    __shared__ __attribute__((aligned(16))) float sh_alpha[kAttnWaves][kHeadsPad];
+    __shared__ float sh_m[kAttnWaves][kHeadsPad], sh_l[kAttnWaves][kHeadsPad];
+    __shared__ float sh_o[kHeadsPad][D];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int c = lane & 15, j = lane >> 4;
+    const int split = blockIdx.x % n_splits;
+    const int head = (blockIdx.x / n_splits) % src.H;
+    const int row = blockIdx.x / (n_splits * src.H);
+
+    // the group's query heads as B operands: lane (head c, j) holds dims 32u + 8j .. + 7 of head c
+    bf16x4 qb[2 * NKL];
+    {
+        const bool have = c < G;
+        const uint16_t* qp = q + ((int64_t)row * Hq + (int64_t)head * G + (have ? c : 0)) * D;
+#pragma unroll
+        for (int u = 0; u < NKL; ++u) {
+            vec16 v = *(const vec16*)(qp + 32 * u + 8 * j);
+            if (!have) v = vec16{0u, 0u, 0u, 0u};
+            qb[2 * u] = lo4(v);
+            qb[2 * u + 1] = hi4(v);
+        }
+    }
+    for (int i = tid; i < kHeadsPad * D; i += kAttnWaves * kWave) (&sh_o[0][0])[i] = 0.f;
+
+    const int n_tiles = (len + kTile - 1) / kTile;
+    const int tile_begin = split * tiles_per_split;
+    const int tile_end = min(n_tiles, tile_begin + tiles_per_split);
+
+    float m_run = -INFINITY;                    // running maximum (base-2 scores) of head c, equal in the 4 lanes of a head
+    float l_run = 0.f;                          // sum of weights over this lane's own positions
+    f32x4 acc[NDB];
+#pragma unroll
+    for (int t = 0; t < NDB; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    vec16 kc[NKL], vc[NVL], kn[NKL], vn[NVL];
+    auto load_tile = [&](int tile, vec16 (&kd)[NKL], vec16 (&vd)[NVL]) {
+        const int p0 = tile * kTile;
+        {   // K: lane (pos c, j) reads dims 32u + 8j .. + 7; positions past the end repeat the last one (masked later)
+            const int pos = min(p0 + c, len - 1);
+            const char* kp = position_ptr<D>(src, src.k_tensor, row, head, pos);
+#pragma unroll
+            for (int u = 0; u < NKL; ++u) kd[u] = __builtin_nontemporal_load((const vec16*)(kp + (32 * u + 8 * j) * 2));
+        }
+#pragma unroll
+        for (int u = 0; u < NVL; ++u) {         // V: 16-byte piece (u*64 + lane) of the tile, rows are positions
+            const int piece = u * kWave + lane;
+            const int pos = min(p0 + piece / kPiecesPerRow, len - 1);
+            const char* vp = position_ptr<D>(src, src.v_tensor, row, head, pos);
+            vd[u] = __builtin_nontemporal_load((const vec16*)(vp + (piece % kPiecesPerRow) * 16));
+        }
+    };
+
+    int tile = tile_begin + wave;
+    if (tile < tile_end) load_tile(tile, kc, vc);
+    for (; tile < tile_end; tile += kAttnWaves) {
+        const int next = tile + kAttnWaves;
+        if (next < tile_end) load_tile(next, kn, vn);
+
+        // scores of the tile: lane (head c, j) gets positions 4j .. 4j+3
+        f32x4 s = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int u = 0; u < NKL; ++u) {
+            s = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(lo4(kc[u]), qb[2 * u], s, 0, 0, 0);
+            s = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(hi4(kc[u]), qb[2 * u + 1], s, 0, 0, 0);
+        }
+        float sv[4];
+        float tmax = -INFINITY;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            sv[i] = (tile * kTile + 4 * j + i < len) ? s[i] * scale_log2 : -INFINITY;
+            tmax = fmaxf(tmax, sv[i]);
+        }
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+        const float m_new = fmaxf(m_run, tmax);                 // finite: the tile has at least one valid position
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);   // 0 on the first tile (m_run = -inf)
+        float p[4], psum = 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { p[i] = __builtin_amdgcn_exp2f(sv[i] - m_new); psum += p[i]; }
+        l_run = l_run * alpha + psum;
+        m_run = m_new;
+
+        // rescale the output rows whose maximum moved; the factors travel through LDS (row = head 4j+i of this lane)
+        if (__ballot(alpha != 1.f)) {
+            if (j == 0) sh_alpha[wave][c] = alpha;
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            const f32x4 a4 = *(const f32x4*)&sh_alpha[wave][4 * j];
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int t = 0; t < NDB; ++t) acc[t] *= a4;
+        }
+
+        // weights as A operands (head c, positions 4j..4j+3), bf16 high and low parts
+        bf16x4 p_hi, p_lo;
+        {
+            unsigned h[4], l[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) split_bf16(p[i], h[i], l[i]);
+            const unsigned ph[2] = {h[0] | (h[1] << 16), h[2] | (h[3] << 16)};
+            const unsigned pl[2] = {l[0] | (l[1] << 16), l[2] | (l[3] << 16)};
+            __builtin_memcpy(&p_hi, ph, 8);
+            __builtin_memcpy(&p_lo, pl, 8);
+        }
+
+        // the V tile through LDS: written as rows, read as (4 consecutive positions of one dim)
+        char* vt = sh_v[wave];
+#pragma unroll
+        for (int u = 0; u < NVL; ++u) {
+            const int piece = u * kWave + lane;
+            *(vec16*)(vt + (piece / kPiecesPerRow) * kRowBytes + (piece % kPiecesPerRow) * 16) = vc[u];
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int t = 0; t < NDB; ++t) {
+            const char* col = vt + (4 * j) * kRowBytes + (16 * t + c) * 2;
+            const unsigned v0 = *(const uint16_t*)(col), v1 = *(const uint16_t*)(col + kRowBytes);
+            const unsigned v2 = *(const uint16_t*)(col + 2 * kRowBytes), v3 = *(const uint16_t*)(col + 3 * kRowBytes);
+            const unsigned w[2] = {v0 | (v1 << 16), v2 | (v3 << 16)};
+            bf16x4 vb;
+            __builtin_memcpy(&vb, w, 8);
+            acc[t] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(p_hi, vb, acc[t], 0, 0, 0);
+            acc[t] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(p_lo, vb, acc[t], 0, 0, 0);
+        }
+        __builtin_amdgcn_wave_barrier();        // all lanes have read the tile before the next one overwrites it
+
+#pragma unroll
+        for (int u = 0; u < NKL; ++u) kc[u] = kn[u];
+#pragma unroll
+        for (int u = 0; u < NVL; ++u) vc[u] = vn[u];
+    }
+
+    // merge the waves: common reference per head, then sums and outputs
+    l_run += __shfl_xor(l_run, 16);
+    l_run += __shfl_xor(l_run, 32);
+    if (j == 0) { sh_m[wave][c] = m_run; sh_l[wave][c] = l_run; }
+    __syncthreads();                            // also: sh_o is zeroed
+    float M = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < kAttnWaves; ++w) M = fmaxf(M, sh_m[w][c]);
+    if (j == 0) sh_alpha[wave][c] = m_run == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m_run - M);   // a wave without tiles adds nothing
+    __syncthreads();
+    {
+        const f32x4 f4 = *(const f32x4*)&sh_alpha[wave][4 * j];
+#pragma unroll
+        for (int t = 0; t < NDB; ++t)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) atomicAdd(&sh_o[4 * j + i][16 * t + c], acc[t][i] * f4[i]);
+    }
+    __syncthreads();
+    // head g < G: total weight L, then either the normalised output or this split's partial record
+    for (int e = tid; e < G * D; e += kAttnWaves * kWave) {
+        const int g = e / D, d = e % D;
+        float Mg = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < kAttnWaves; ++w) Mg = fmaxf(Mg, sh_m[w][g]);
+        float L = 0.f;
+#pragma unroll
+        for (int w = 0; w < kAttnWaves; ++w) L += sh_l[w][g] * sh_alpha[w][g];
+        const int64_t hq = (int64_t)row * Hq + (int64_t)head * G + g;
+        if (n_splits == 1) {
+            out[hq * D + d] = sh_o[g][d] / L;
+        } else {
+            float* rec = partial + (hq * n_splits + split) * (D + 2);
+            if (d == 0) { rec[0] = Mg; rec[1] = L; }
+            rec[2 + d] = sh_o[g][d];
+        }
+    }
+}
+
+// Merges the splits of one (row, query head): out = sum_s o_s 2^(M_s - M) / sum_s L_s 2^(M_s - M).
+template <int D>
+__global__ __launch_bounds__(D) void attn_combine_kernel(const float* __restrict__ partial, int n_splits, float* __restrict__ out)
+{
+    const int64_t hq = blockIdx.x;
+    const int d = threadIdx.x;
+    const float* rec = partial + hq * n_splits * (D + 2);
+    float M = -INFINITY;
+    for (int s = 0; s < n_splits; ++s) M = fmaxf(M, rec[s * (D + 2)]);
+    float L = 0.f, o = 0.f;
+    for (int s = 0; s < n_splits; ++s) {
+        const float f = __builtin_amdgcn_exp2f(rec[s * (D + 2)] - M);
+        L += rec[s * (D + 2) + 1] * f;
+        o += rec[s * (D + 2) + 2 + d] * f;
+    }
+    out[hq * D + d] = o / L;
+}
+
+}  // namespace psmc
+
+using namespace psmc;
+
+namespace {
+constexpr int kMaxAttnSplits = 16;
+}
+
+extern "C" {
+
+size_t smc_attn_workspace_bytes(const smc_config* cfg, int32_t n_q_heads)
+{
+    if (!cfg || cfg->kv_tensors < 2 || n_q_heads < 1 || cfg->kv_H < 1 || n_q_heads % cfg->kv_H != 0) return 0;
+    if (cfg->kv_D != 64 && cfg->kv_D != 128) return 0;
+    return (size_t)cfg->B * cfg->N * n_q_heads * kMaxAttnSplits * (cfg->kv_D + 2) * sizeof(float);
+}
+
+smc_status smc_attn_decode(smc_ctx* ctx, int32_t k_tensor, int32_t v_tensor, const void* d_q, int32_t n_q_heads, int32_t len,
+                           float scale, void* d_workspace, size_t workspace_bytes, float* d_out)
+{
+    if (!ctx || !d_q || !d_out || !d_workspace) return SMC_E_NULL;
+    const auto& cfg = ctx->cfg;
+    if (cfg.kv_tensors < 1 || k_tensor < 0 || v_tensor < 0 || k_tensor >= cfg.kv_tensors || v_tensor >= cfg.kv_tensors)
+        return SMC_E_RANGE;
+    if (cfg.kv_elem_bytes != 2) return SMC_E_DTYPE;
+    if (cfg.kv_D != 64 && cfg.kv_D != 128) return SMC_E_SHAPE;
+    if (n_q_heads < 1 || n_q_heads % cfg.kv_H != 0 || n_q_heads / cfg.kv_H > kHeadsPad) return SMC_E_SHAPE;
+    if (len < 1 || len > cfg.kv_S) return SMC_E_RANGE;
+    if (!(scale > 0.f) || !(scale < 3.0e38f)) return SMC_E_RANGE;
+    if (((uintptr_t)d_q & 15u) != 0 || ((uintptr_t)d_out & 15u) != 0 || ((uintptr_t)d_workspace & 15u) != 0) return SMC_E_ALIGN;
+    if (workspace_bytes < smc_attn_workspace_bytes(&cfg, n_q_heads)) return SMC_E_SHAPE;
+    const bool paged = ctx->paged.bound != 0;
+    if (!paged && !ctx->kv_bound) return SMC_E_STATE;
+    if (paged && len > ctx->paged.len) return SMC_E_RANGE;       // positions that were never appended have no page
+
+    AttnSrc src{};
+    src.paged = paged ? 1 : 0;
+    src.bufA = paged ? (void* const*)ctx->paged.pools : (void* const*)ctx->ws.kvA;
+    src.bufB = paged ? nullptr : (void* const*)ctx->ws.kvB;
+    src.parity = ctx->ws.parity;
+    src.table = paged ? ctx->paged.table : nullptr;
+    src.P = paged ? ctx->paged.P : 1;
+    src.M = paged ? ctx->paged.M : 0;
+    src.H = cfg.kv_H; src.S = cfg.kv_S;
+    src.k_tensor = k_tensor; src.v_tensor = v_tensor;
+
+    const int G = n_q_heads / cfg.kv_H;
+    const int n_tiles = (len + kTile - 1) / kTile;
+    const int64_t units = (int64_t)ctx->R * cfg.kv_H;
+    // enough workgroups for about four per compute unit, at least four tiles per wave of a split
+    int n_splits = (int)((4 * (int64_t)ctx->n_cus + units - 1) / units);
+    n_splits = n_splits < 1 ? 1 : n_splits;
+    if (n_splits > kMaxAttnSplits) n_splits = kMaxAttnSplits;
+    const int max_by_work = n_tiles / (4 * kAttnWaves);
+    if (n_splits > max_by_work) n_splits = max_by_work < 1 ? 1 : max_by_work;
+    const int tiles_per_split = (n_tiles + n_splits - 1) / n_splits;
+    n_splits = (n_tiles + tiles_per_split - 1) / tiles_per_split;            // no empty split
+
+    const dim3 grid((unsigned)(units * n_splits)), block(kAttnWaves * kWave);
+    const float scale_log2 = scale * kLog2e;
+    {
+        ScopedKernelTimer timer(ctx, 3);
+        if (cfg.kv_D == 128)
+            hipLaunchKernelGGL((attn_decode_kernel<128>), grid, block, 0, ctx->stream, src, (const uint16_t*)d_q, n_q_heads, G, len,
+                               scale_log2, n_splits, tiles_per_split, (float*)d_workspace, d_out);
+        else
+            hipLaunchKernelGGL((attn_decode_kernel<64>), grid, block, 0, ctx->stream, src, (const uint16_t*)d_q, n_q_heads, G, len,
+                               scale_log2, n_splits, tiles_per_split, (float*)d_workspace, d_out);
+    }
+    if (n_splits > 1) {
+        const dim3 cgrid((unsigned)((int64_t)ctx->R * n_q_heads));
+        if (cfg.kv_D == 128)
+            hipLaunchKernelGGL((attn_combine_kernel<128>), cgrid, dim3(128), 0, ctx->stream, (const float*)d_workspace, n_splits, d_out);
+        else
+            hipLaunchKernelGGL((attn_combine_kernel<64>), cgrid, dim3(64), 0, ctx->stream, (const float*)d_workspace, n_splits, d_out);
+    }
+    return hipGetLastError() == hipSuccess ? SMC_OK : SMC_E_HIP;
+}
+
+}  // extern "C"

@@ -127,7 +127,7 @@ smc_status smc_init(const smc_config* cfg, void* d_workspace, size_t workspace_b
     c->kv_bound = 0;
     c->hist_bound = 0;
     c->profiling = 0;
-    c->ev_used[0] = c->ev_used[1] = c->ev_used[2] = 0;
+    c->ev_used[0] = c->ev_used[1] = c->ev_used[2] = c->ev_used[3] = 0;
     c->paged = PagedKV{};
     int dev = 0, cus = 256;
     if (hipGetDevice(&dev) == hipSuccess) {
@@ -329,14 +329,14 @@ smc_status smc_profile_enable(smc_ctx* ctx, int32_t enable)
     if (!ctx) return SMC_E_NULL;
     if (hipStreamSynchronize(ctx->stream) != hipSuccess) return SMC_E_HIP;
     ctx->profiling = enable != 0;
-    ctx->ev_used[0] = ctx->ev_used[1] = ctx->ev_used[2] = 0;
+    ctx->ev_used[0] = ctx->ev_used[1] = ctx->ev_used[2] = ctx->ev_used[3] = 0;
     return SMC_OK;
 }
 
 smc_status smc_profile_read(smc_ctx* ctx, int32_t kind, double* h_total_ms, int64_t* h_launches)
 {
     if (!ctx || !h_total_ms || !h_launches) return SMC_E_NULL;
-    if (kind < 0 || kind > 2) return SMC_E_RANGE;
+    if (kind < 0 || kind > 3) return SMC_E_RANGE;
     if (hipStreamSynchronize(ctx->stream) != hipSuccess) return SMC_E_HIP;
     double total = 0.0;
     const size_t n = ctx->ev_used[kind] / 2;

@@ -96,10 +96,10 @@ struct smc_ctx {
     int gather_variant;           // vectors per thread / non-temporal choice of the gather kernel
     int n_cus;
     // optional per-kernel timing: event pairs recorded around launches of kind 0 (vocab pass), 1 (KV gather) and
-    // 2 (copy-on-write page copy)
+    // 2 (copy-on-write page copy), 3 (decode attention)
     int profiling;
-    std::vector<hipEvent_t> ev_pool[3];   // [2*i] start, [2*i+1] stop
-    size_t ev_used[3];
+    std::vector<hipEvent_t> ev_pool[4];   // [2*i] start, [2*i+1] stop
+    size_t ev_used[4];
 };
 
 namespace psmc {

@@ -109,6 +109,18 @@ class Session:
         refcnt = flat[r0:r0 + self.B * Q * 4].view(torch.int32).cpu().numpy()
         return table, refcnt
 
+    def attention(self, k_tensor, v_tensor, q, length, scale):
+        """Decode attention over the context's cache; q: bf16 [R, Hq, D] device tensor; returns float32 [R, Hq, D]."""
+        Hq = q.shape[1]
+        nbytes = smc.smc_attn_workspace_bytes(self.cfg, Hq)
+        if nbytes == 0:
+            raise ValueError("invalid attention geometry")
+        if getattr(self, "_attn_ws", None) is None or self._attn_ws.numel() < nbytes:
+            self._attn_ws = torch.empty(nbytes, dtype=torch.uint8, device=q.device)
+        out = torch.empty(q.shape, dtype=torch.float32, device=q.device)
+        smc.smc_attn_decode(self.ctx, k_tensor, v_tensor, q, Hq, length, scale, self._attn_ws, nbytes, out)
+        return out
+
     def final_draw(self, t):
         smc.smc_final_draw(self.ctx, t, self.choice)
 
