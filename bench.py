@@ -34,9 +34,11 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kv", action="store_true", help="vocabulary pass + weights only (no cache bound)")
     ap.add_argument("--n-split", type=int, default=0)
-    ap.add_argument("--mode", default="step", choices=["step", "reindex"],
+    ap.add_argument("--mode", default="step", choices=["step", "reindex", "attention"],
                     help="step: the whole hot path (default); reindex: the KV reorder alone, every prompt resampled "
-                         "with synthetic ancestors (sorted draws from Dirichlet(0.5) weights)")
+                         "with synthetic ancestors (sorted draws from Dirichlet(0.5) weights); attention: decode "
+                         "attention of every layer over the full cache (dense, or paged with --paged P)")
+    ap.add_argument("--q-heads", type=int, default=0, help="query heads for --mode attention (default 7 per KV head)")
     ap.add_argument("--paged", type=int, default=0, metavar="P",
                     help="paged cache with P positions per page: the reorder copies page numbers, appends copy on write")
     ap.add_argument("--in-place", action="store_true",
@@ -150,6 +152,57 @@ def reindex_only(args, w, K, W, smc, synth, Session, np, torch):
     print(json.dumps(out))
 
 
+def attention_only(args, w, K, W, smc, synth, Session, np, torch):
+    """Decode attention of all layers over the workload's full cache: one step = one call per layer."""
+    P = args.paged
+    s = Session(w.B, w.N, w.V, 8, w.dtype, w.kappa, args.seed, kv_geom=(w.kv_tensors, w.H, w.S, w.D), with_hist=False,
+                page_len=P, len0=w.S)
+    g = torch.Generator(device="cuda"); g.manual_seed(args.seed + 12345)
+    for t in (s.pools if P else s.kvA):
+        t.normal_(generator=g)
+    if not P:                                           # rows in both buffers, as after a few reorders
+        flag = torch.ones(w.B, dtype=torch.int32, device="cuda")
+        for i in range(2):
+            s.reindex(w.S, 0, torch.as_tensor(synth.ancestors_numpy(w, args.seed + i)).cuda(), flag)
+    Hq = args.q_heads or 7 * w.H
+    q = torch.randn((w.R, Hq, w.D), device="cuda", generator=g).to(torch.bfloat16)
+    scale = float(w.D) ** -0.5
+
+    def one_step():
+        for layer in range(w.layers):
+            s.attention(2 * layer, 2 * layer + 1, q, w.S, scale)
+
+    for _ in range(W):
+        one_step()
+    torch.cuda.synchronize()
+    smc.smc_profile_enable(s.ctx, 1)
+    t0 = time.perf_counter()
+    for _ in range(K):
+        one_step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms, n = smc.smc_profile_read(s.ctx, 3)
+    smc.smc_profile_enable(s.ctx, 0)
+    bytes_per_call = 2.0 * w.R * w.H * w.S * w.D * 2            # K and V of one layer, every position read once
+    gbps = bytes_per_call * n / (ms * 1e-3) / 1e9
+    s.close()
+    del s
+    torch.cuda.empty_cache()
+    out = {
+        "metric": "particle-steps/s (decode attention of all layers only), 1 MI355X",
+        "value": w.R * K / elapsed, "unit": "particle-steps/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": elapsed / K * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": w.name, "mode": "attention", "rows": w.R, "kv_heads": w.H, "q_heads": Hq, "head_dim": w.D,
+                   "positions": w.S, "layers": w.layers, "cache": f"paged, {P} positions per page" if P else "dense, double-buffered rows"},
+        "roofline": {"kernel": "attn_decode_kernel", "bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": gbps / HBM_PEAK_GBPS, "traffic": None, "launches": int(n), "avg_launch_ms": ms / max(n, 1),
+                     "algorithmic_bytes_per_launch": bytes_per_call},
+    }
+    out["measured_ceilings_GBps"] = measured_ceilings(smc, torch, "cuda")
+    print(json.dumps(out))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -168,6 +221,9 @@ def main():
     if args.mode == "reindex":
         torch.cuda.set_device(0)
         return reindex_only(args, w, K, min(W, 2), smc, synth, Session, np, torch)
+    if args.mode == "attention":
+        torch.cuda.set_device(0)
+        return attention_only(args, w, K, min(W, 2), smc, synth, Session, np, torch)
     dev = "cuda"
     torch.cuda.set_device(0)
     T_max = (W + 2 * K + 8 + 3) // 4 * 4

@@ -5,7 +5,7 @@
 //     s_j = scale <q[r, h G + g], K[r, h, j]>,  p = softmax_j s,  out[r, h G + g] = sum_j p_j V[r, h, j],  j < len.
 //
 // gfx950 design.  The kernel is a stream over K and V (each read once, 16-byte loads); the two contractions run on the
-// matrix cores so that the vector ALUs only see the softmax.  One workgroup of 4 waves per (row, KV head, split of the
+// matrix cores so that the vector ALUs only see the softmax.  One workgroup of 2 waves per (row, KV head, split of the
 // positions); a wave walks tiles of 16 positions:
 //   scores   S^T[pos, head] = K_tile[pos, dim] Q^T[dim, head]: 16x16x16 bf16 MFMA, A = the K tile exactly as loaded
 //            (lane = (pos, 8-dim slice)), B = the group's query heads (padded to 16) preloaded in registers;
@@ -26,7 +26,7 @@ typedef short bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int vec16 __attribute__((ext_vector_type(4)));
 
-constexpr int kAttnWaves = 4;
+constexpr int kAttnWaves = 2;             // waves per workgroup: small workgroups overlap each other's start-up and merge
 constexpr int kTile = 16;                 // positions per MFMA tile
 constexpr int kHeadsPad = 16;             // query heads of a group, padded to the MFMA width
 constexpr float kLog2e = 1.4426950408889634f;
@@ -41,18 +41,6 @@ struct AttnSrc {
     int k_tensor, v_tensor;
 };
 
-// Byte address of position pos (< S) of (row, KV head) in tensor `tensor`; D elements of 2 bytes per position.
-template <int D>
-__device__ __forceinline__ const char* position_ptr(const AttnSrc& a, int tensor, int row, int head, int pos)
-{
-    if (a.paged) {
-        const int page = a.table[(int64_t)row * a.M + pos / a.P];
-        return (const char*)a.bufA[tensor] + ((((int64_t)page * a.H + head) * a.P + pos % a.P) * D) * 2;
-    }
-    const char* base = (const char*)(a.parity[row] ? a.bufB[tensor] : a.bufA[tensor]);
-    return base + ((((int64_t)row * a.H + head) * a.S + pos) * D) * 2;
-}
-
 __device__ __forceinline__ bf16x4 lo4(const vec16 v) { bf16x4 r; __builtin_memcpy(&r, &v, 8); return r; }
 __device__ __forceinline__ bf16x4 hi4(const vec16 v) { bf16x4 r; __builtin_memcpy(&r, (const char*)&v + 8, 8); return r; }
 
@@ -66,9 +54,17 @@ __device__ __forceinline__ void split_bf16(float p, unsigned& hi, unsigned& lo)
 }
 }  // namespace
 
+// How positions are addressed: kDense = one contiguous run per (row, KV head) in the row's live buffer;
+// kPagedAligned = paged with a page length that is a multiple of the tile (a tile lies in one page: one page number
+// per tile, no per-lane division); kPagedAny = paged, any page length (page number and offset per lane).
+enum { kDense = 0, kPagedAligned = 1, kPagedAny = 2 };
+
+typedef const vec16 __attribute__((address_space(1)))* global_vec16_ptr;     // so that loads are global, not flat
+__device__ __forceinline__ vec16 stream_load(const char* p) { return __builtin_nontemporal_load((global_vec16_ptr)p); }
+
 // Partial result of one split for one query head: reference exponent, sum of weights, unnormalised output.
 // Layout of the workspace: [row, query head, split, 2 + D] floats.
-template <int D>
+template <int D, int MODE>
 __global__ __launch_bounds__(kAttnWaves* kWave) void attn_decode_kernel(
     AttnSrc src, const uint16_t* __restrict__ q, int Hq, int G, int len, float scale_log2, int n_splits, int tiles_per_split,
     float* __restrict__ partial, float* __restrict__ out)
@@ -78,6 +74,7 @@ __global__ __launch_bounds__(kAttnWaves* kWave) void attn_decode_kernel(
     constexpr int NVL = D / 32;                 // 16-byte V loads per lane and tile (16 positions x D x 2 bytes / 64 lanes / 16)
     constexpr int kRowBytes = D * 2 + 16;       // padded LDS row of a V tile
     constexpr int kPiecesPerRow = D / 8;        // 16-byte pieces per position
+    constexpr int kPosBytes = D * 2;
     __shared__ __attribute__((aligned(16))) char sh_v[kAttnWaves][kTile * kRowBytes];
     __shared__ __attribute__((aligned(16))) float sh_alpha[kAttnWaves][kHeadsPad];
     __shared__ float sh_m[kAttnWaves][kHeadsPad], sh_l[kAttnWaves][kHeadsPad];
@@ -114,30 +111,78 @@ __global__ __launch_bounds__(kAttnWaves* kWave) void attn_decode_kernel(
 #pragma unroll
     for (int t = 0; t < NDB; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    vec16 kc[NKL], vc[NVL], kn[NKL], vn[NVL];
-    auto load_tile = [&](int tile, vec16 (&kd)[NKL], vec16 (&vd)[NVL]) {
+    // Where the positions of this (row, KV head) live (see the MODE enumeration).  Page numbers are read one tile
+    // ahead of the loads that need them, so the dependent load does not stall the stream.
+    const int P = src.P;
+    const int32_t* table_row = MODE == kDense ? nullptr : src.table + (int64_t)row * src.M;
+    const int64_t page_stride = (int64_t)src.H * P * kPosBytes;
+    const char* kbase; const char* vbase;
+    if (MODE == kDense) {
+        const bool in_b = src.parity[row] != 0;
+        const int64_t off = ((int64_t)row * src.H + head) * src.S * kPosBytes;
+        kbase = (const char*)(in_b ? src.bufB[src.k_tensor] : src.bufA[src.k_tensor]) + off;
+        vbase = (const char*)(in_b ? src.bufB[src.v_tensor] : src.bufA[src.v_tensor]) + off;
+    } else {
+        kbase = (const char*)src.bufA[src.k_tensor] + (int64_t)head * P * kPosBytes;
+        vbase = (const char*)src.bufA[src.v_tensor] + (int64_t)head * P * kPosBytes;
+    }
+    // lane-constant parts of the addresses inside a tile
+    const int k_lane_off = c * kPosBytes + 16 * j;                              // position c of the tile, 16-byte piece j of a 64-byte run
+    int v_lane_pos[NVL], v_lane_off[NVL];
+#pragma unroll
+    for (int u = 0; u < NVL; ++u) {
+        const int piece = u * kWave + lane;
+        v_lane_pos[u] = piece / kPiecesPerRow;
+        v_lane_off[u] = (piece % kPiecesPerRow) * 16;
+    }
+    struct TilePages { int k; int v[NVL]; };
+    auto lookup = [&](int tile, TilePages& tp) {
         const int p0 = tile * kTile;
-        {   // K: lane (pos c, j) reads dims 32u + 8j .. + 7; positions past the end repeat the last one (masked later)
-            const int pos = min(p0 + c, len - 1);
-            const char* kp = position_ptr<D>(src, src.k_tensor, row, head, pos);
+        if (MODE == kPagedAligned) {
+            tp.k = table_row[p0 / P];                                           // one page for the whole tile
+        } else if (MODE == kPagedAny) {
+            tp.k = table_row[min(p0 + c, len - 1) / P];
 #pragma unroll
-            for (int u = 0; u < NKL; ++u) kd[u] = __builtin_nontemporal_load((const vec16*)(kp + (32 * u + 8 * j) * 2));
-        }
-#pragma unroll
-        for (int u = 0; u < NVL; ++u) {         // V: 16-byte piece (u*64 + lane) of the tile, rows are positions
-            const int piece = u * kWave + lane;
-            const int pos = min(p0 + piece / kPiecesPerRow, len - 1);
-            const char* vp = position_ptr<D>(src, src.v_tensor, row, head, pos);
-            vd[u] = __builtin_nontemporal_load((const vec16*)(vp + (piece % kPiecesPerRow) * 16));
+            for (int u = 0; u < NVL; ++u) tp.v[u] = table_row[min(p0 + v_lane_pos[u], len - 1) / P];
         }
     };
+    // Positions past the end repeat the last valid one (their weights are masked to zero).
+    auto load_tile = [&](int tile, const TilePages& tp, vec16 (&kd)[NKL], vec16 (&vd)[NVL]) {
+        const int p0 = tile * kTile;
+        const bool whole = p0 + kTile <= len;                                   // uniform: no clamping needed
+        const char* kp; const char* vp[NVL];
+        if (MODE == kDense) {
+            const char* kt = kbase + (int64_t)p0 * kPosBytes;
+            const char* vt = vbase + (int64_t)p0 * kPosBytes;
+            kp = kt + (whole ? k_lane_off : min(c, len - 1 - p0) * kPosBytes + 16 * j);
+#pragma unroll
+            for (int u = 0; u < NVL; ++u)
+                vp[u] = vt + (whole ? v_lane_pos[u] : min(v_lane_pos[u], len - 1 - p0)) * kPosBytes + v_lane_off[u];
+        } else if (MODE == kPagedAligned) {
+            const int64_t in_page = (int64_t)(p0 % P) * kPosBytes;
+            const char* kt = kbase + tp.k * page_stride + in_page;
+            const char* vt = vbase + tp.k * page_stride + in_page;
+            kp = kt + (whole ? k_lane_off : min(c, len - 1 - p0) * kPosBytes + 16 * j);
+#pragma unroll
+            for (int u = 0; u < NVL; ++u)
+                vp[u] = vt + (whole ? v_lane_pos[u] : min(v_lane_pos[u], len - 1 - p0)) * kPosBytes + v_lane_off[u];
+        } else {
+            const int kpos = min(p0 + c, len - 1);
+            kp = kbase + tp.k * page_stride + (int64_t)(kpos % P) * kPosBytes + 16 * j;
+#pragma unroll
+            for (int u = 0; u < NVL; ++u) {
+                const int vpos = min(p0 + v_lane_pos[u], len - 1);
+                vp[u] = vbase + tp.v[u] * page_stride + (int64_t)(vpos % P) * kPosBytes + v_lane_off[u];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < NKL; ++u) kd[u] = stream_load(kp + 64 * u);        // dims 32u + 8j .. + 7 of the lane's position
+#pragma unroll
+        for (int u = 0; u < NVL; ++u) vd[u] = stream_load(vp[u]);
+    };
 
-    int tile = tile_begin + wave;
-    if (tile < tile_end) load_tile(tile, kc, vc);
-    for (; tile < tile_end; tile += kAttnWaves) {
-        const int next = tile + kAttnWaves;
-        if (next < tile_end) load_tile(next, kn, vn);
-
+    // One tile: scores, online softmax, output.  kc / vc hold the tile's K and V as loaded.
+    auto process = [&](int tile, const vec16 (&kc)[NKL], const vec16 (&vc)[NVL]) {
         // scores of the tile: lane (head c, j) gets positions 4j .. 4j+3
         f32x4 s = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -188,10 +233,7 @@ __global__ __launch_bounds__(kAttnWaves* kWave) void attn_decode_kernel(
         // the V tile through LDS: written as rows, read as (4 consecutive positions of one dim)
         char* vt = sh_v[wave];
 #pragma unroll
-        for (int u = 0; u < NVL; ++u) {
-            const int piece = u * kWave + lane;
-            *(vec16*)(vt + (piece / kPiecesPerRow) * kRowBytes + (piece % kPiecesPerRow) * 16) = vc[u];
-        }
+        for (int u = 0; u < NVL; ++u) *(vec16*)(vt + v_lane_pos[u] * kRowBytes + v_lane_off[u]) = vc[u];
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
 #pragma unroll
@@ -206,11 +248,35 @@ __global__ __launch_bounds__(kAttnWaves* kWave) void attn_decode_kernel(
             acc[t] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(p_lo, vb, acc[t], 0, 0, 0);
         }
         __builtin_amdgcn_wave_barrier();        // all lanes have read the tile before the next one overwrites it
+    };
 
-#pragma unroll
-        for (int u = 0; u < NKL; ++u) kc[u] = kn[u];
-#pragma unroll
-        for (int u = 0; u < NVL; ++u) vc[u] = vn[u];
+    // Software pipeline over this wave's tiles (tile, tile + 4, ...): while one tile is processed the next one's
+    // loads are in flight and the page numbers of the one after are being read.  Unrolled by two so that the two
+    // register buffers swap roles without copies.
+    vec16 ka[NKL], va[NVL], kb[NKL], vb2[NVL];
+    TilePages pg{};
+    int tile = tile_begin + wave;
+    if (tile < tile_end) {
+        lookup(tile, pg);
+        load_tile(tile, pg, ka, va);
+        if (tile + kAttnWaves < tile_end) lookup(tile + kAttnWaves, pg);
+    }
+    while (tile < tile_end) {
+        int next = tile + kAttnWaves;
+        if (next < tile_end) {
+            load_tile(next, pg, kb, vb2);
+            if (next + kAttnWaves < tile_end) lookup(next + kAttnWaves, pg);
+        }
+        process(tile, ka, va);
+        tile = next;
+        if (tile >= tile_end) break;
+        next = tile + kAttnWaves;
+        if (next < tile_end) {
+            load_tile(next, pg, ka, va);
+            if (next + kAttnWaves < tile_end) lookup(next + kAttnWaves, pg);
+        }
+        process(tile, kb, vb2);
+        tile = next;
     }
 
     // merge the waves: common reference per head, then sums and outputs
@@ -318,8 +384,11 @@ smc_status smc_attn_decode(smc_ctx* ctx, int32_t k_tensor, int32_t v_tensor, con
     const int G = n_q_heads / cfg.kv_H;
     const int n_tiles = (len + kTile - 1) / kTile;
     const int64_t units = (int64_t)ctx->R * cfg.kv_H;
-    // enough workgroups for about four per compute unit, at least four tiles per wave of a split
-    int n_splits = (int)((4 * (int64_t)ctx->n_cus + units - 1) / units);
+    // Every split pays a fixed start-up and merge cost and more than one needs the merge launch, so a row's positions
+    // are split only when there are fewer than two workgroups per compute unit (measured: 512 workgroups of cfg2's
+    // shape run as fast unsplit as split in two), and never below four tiles per wave.
+    const int64_t slots = 2 * (int64_t)ctx->n_cus;
+    int n_splits = (int)((slots + units - 1) / units);
     n_splits = n_splits < 1 ? 1 : n_splits;
     if (n_splits > kMaxAttnSplits) n_splits = kMaxAttnSplits;
     const int max_by_work = n_tiles / (4 * kAttnWaves);
@@ -329,14 +398,17 @@ smc_status smc_attn_decode(smc_ctx* ctx, int32_t k_tensor, int32_t v_tensor, con
 
     const dim3 grid((unsigned)(units * n_splits)), block(kAttnWaves * kWave);
     const float scale_log2 = scale * kLog2e;
+    const int mode = !paged ? kDense : (ctx->paged.P % kTile == 0 ? kPagedAligned : kPagedAny);
     {
         ScopedKernelTimer timer(ctx, 3);
-        if (cfg.kv_D == 128)
-            hipLaunchKernelGGL((attn_decode_kernel<128>), grid, block, 0, ctx->stream, src, (const uint16_t*)d_q, n_q_heads, G, len,
-                               scale_log2, n_splits, tiles_per_split, (float*)d_workspace, d_out);
-        else
-            hipLaunchKernelGGL((attn_decode_kernel<64>), grid, block, 0, ctx->stream, src, (const uint16_t*)d_q, n_q_heads, G, len,
-                               scale_log2, n_splits, tiles_per_split, (float*)d_workspace, d_out);
+#define PSMC_ATTN(DD, MM) hipLaunchKernelGGL((attn_decode_kernel<DD, MM>), grid, block, 0, ctx->stream, src, (const uint16_t*)d_q, \
+                                             n_q_heads, G, len, scale_log2, n_splits, tiles_per_split, (float*)d_workspace, d_out)
+        if (cfg.kv_D == 128) {
+            if (mode == kDense) PSMC_ATTN(128, kDense); else if (mode == kPagedAligned) PSMC_ATTN(128, kPagedAligned); else PSMC_ATTN(128, kPagedAny);
+        } else {
+            if (mode == kDense) PSMC_ATTN(64, kDense); else if (mode == kPagedAligned) PSMC_ATTN(64, kPagedAligned); else PSMC_ATTN(64, kPagedAny);
+        }
+#undef PSMC_ATTN
     }
     if (n_splits > 1) {
         const dim3 cgrid((unsigned)((int64_t)ctx->R * n_q_heads));
