@@ -90,6 +90,10 @@ smc_status smc_destroy(smc_ctx* ctx);
  * Synchronous (copies the pointer tables into the workspace). */
 smc_status smc_kv_bind(smc_ctx* ctx, void* const* h_bufA, void* const* h_bufB, int32_t* d_histA, int32_t* d_histB);
 
+/* Device pointer to the parity words (int32 [R]; 0: the row lives in buffer A, 1: in buffer B): what a decoder needs
+ * to append to, or read, the live buffer of each row.  No synchronisation: order reads after the context's stream. */
+smc_status smc_kv_parity(smc_ctx* ctx, const int32_t** d_parity);
+
 /* a0 + a1 + a2 for step t (1-based, <= T_max).
  *   d_logits: [R, row_stride_elems] of cfg.logits_dtype, first V entries of each row used; base address and
  *             row stride in bytes must be multiples of 16.

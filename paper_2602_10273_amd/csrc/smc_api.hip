@@ -182,6 +182,13 @@ smc_status smc_kv_bind(smc_ctx* ctx, void* const* h_bufA, void* const* h_bufB, i
     return SMC_OK;
 }
 
+smc_status smc_kv_parity(smc_ctx* ctx, const int32_t** d_parity)
+{
+    if (!ctx || !d_parity) return SMC_E_NULL;
+    *d_parity = ctx->ws.parity;
+    return SMC_OK;
+}
+
 smc_status smc_step(smc_ctx* ctx, const void* d_logits, int64_t row_stride_elems, int32_t t, double alpha_t,
                     double alpha_prev, double tau_t, int32_t* d_tokens_out)
 {

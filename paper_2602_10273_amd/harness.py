@@ -109,6 +109,11 @@ class Session:
         refcnt = flat[r0:r0 + self.B * Q * 4].view(torch.int32).cpu().numpy()
         return table, refcnt
 
+    def parity_view(self):
+        """int32 [R] device tensor aliasing the context's parity words (no copy, no synchronisation)."""
+        off = smc.smc_kv_parity(self.ctx) - self.workspace.data_ptr()
+        return self.workspace[off:off + 4 * self.R].view(torch.int32)
+
     def attention(self, k_tensor, v_tensor, q, length, scale):
         """Decode attention over the context's cache; q: bf16 [R, Hq, D] device tensor; returns float32 [R, Hq, D]."""
         Hq = q.shape[1]
