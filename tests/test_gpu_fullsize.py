@@ -179,3 +179,38 @@ def test_full_size_paged_reorder(name, P):
     for ten in range(2):
         assert torch.equal(logical(ten, table, len0 + steps), dense[ten][:, :, :len0 + steps]), ten
     s.close()
+
+
+@pytest.mark.parametrize("name,paged", [("cfg2", 0), ("cfg2", 16), ("cfg5", 0), ("cfg4", 64), ("cfg3", 0)])
+def test_full_size_attention_sampled_rows(name, paged):
+    """Decode attention at the full row geometry of a workload (one layer), sampled rows against the fp64 oracle."""
+    from oracle.attention import decode_attention
+    w = synth.scaled(synth.WORKLOADS[name], layers=1)
+    G = 7 if w.H == 4 else 4
+    Hq = G * w.H
+    s = Session(w.B, w.N, w.V, 8, w.dtype, w.kappa, 0, kv_geom=(2, w.H, w.S, w.D), with_hist=False, page_len=paged, len0=w.S)
+    g = torch.Generator(device="cuda"); g.manual_seed(21)
+    for t in (s.pools if paged else s.kvA):
+        t.normal_(generator=g)
+    rng = np.random.default_rng(4)
+    if not paged:                                                # rows in both buffers
+        flag = torch.ones(w.B, dtype=torch.int32, device="cuda")
+        s.reindex(w.S, 0, torch.as_tensor(synth.ancestors_numpy(w, 1)).cuda(), flag)
+    q = torch.randn((w.R, Hq, w.D), device="cuda", generator=g).to(torch.bfloat16)
+    scale = float(w.D) ** -0.5
+    for length in (w.S, w.S - 37):
+        out = s.attention(0, 1, q, length, scale).cpu().numpy()
+        rows = rng.choice(w.R, size=3, replace=False)
+        if paged:
+            table, _ = s.paged_state()
+            ncol = (w.S + paged - 1) // paged
+            def dense(ten, r):
+                pg = s.pools[ten].view(torch.int16)[torch.as_tensor(table[r, :ncol].astype(np.int64)).cuda()]   # [ncol, H, P, D]
+                return pg.permute(1, 0, 2, 3).reshape(w.H, ncol * paged, w.D)[:, :w.S].cpu().numpy().view(np.uint16)
+            kb = np.stack([dense(0, int(r)) for r in rows]); vb = np.stack([dense(1, int(r)) for r in rows])
+        else:
+            kb = s.live_kv(0, rows); vb = s.live_kv(1, rows)
+        qb = q[torch.as_tensor(rows).cuda()].view(torch.int16).cpu().numpy().view(np.uint16)
+        want = decode_attention(qb, kb, vb, length, scale)
+        assert np.abs(out[rows] - want).max() < TOL, (length, np.abs(out[rows] - want).max())
+    s.close()
