@@ -32,13 +32,12 @@ constexpr int kHeadsPad = 16;             // query heads of a group, padded to t
 constexpr float kLog2e = 1.4426950408889634f;
 
 struct AttnSrc {
-    void* const* bufA;          // dense: buffer A tensors; paged: the pools
-    void* const* bufB;          // dense: buffer B tensors
+    const char* kA; const char* vA;   // dense: the K and the V tensor in buffer A; paged: their pools
+    const char* kB; const char* vB;   // dense: the same tensors in buffer B
     const int32_t* parity;      // dense: which buffer holds row r
     const int32_t* table;       // paged: [R, M] page numbers
-    int paged, P, M;            // positions per page, pages per row
+    int P, M;                   // positions per page, pages per row
     int H, S;                   // KV heads, positions per row (dense)
-    int k_tensor, v_tensor;
 };
 
 __device__ __forceinline__ bf16x4 lo4(const vec16 v) { bf16x4 r; __builtin_memcpy(&r, &v, 8); return r; }
@@ -120,11 +119,11 @@ __global__ __launch_bounds__(kAttnWaves* kWave) void attn_decode_kernel(
     if (MODE == kDense) {
         const bool in_b = src.parity[row] != 0;
         const int64_t off = ((int64_t)row * src.H + head) * src.S * kPosBytes;
-        kbase = (const char*)(in_b ? src.bufB[src.k_tensor] : src.bufA[src.k_tensor]) + off;
-        vbase = (const char*)(in_b ? src.bufB[src.v_tensor] : src.bufA[src.v_tensor]) + off;
+        kbase = (in_b ? src.kB : src.kA) + off;
+        vbase = (in_b ? src.vB : src.vA) + off;
     } else {
-        kbase = (const char*)src.bufA[src.k_tensor] + (int64_t)head * P * kPosBytes;
-        vbase = (const char*)src.bufA[src.v_tensor] + (int64_t)head * P * kPosBytes;
+        kbase = src.kA + (int64_t)head * P * kPosBytes;
+        vbase = src.vA + (int64_t)head * P * kPosBytes;
     }
     // lane-constant parts of the addresses inside a tile
     const int k_lane_off = c * kPosBytes + 16 * j;                              // position c of the tile, 16-byte piece j of a 64-byte run
@@ -371,15 +370,17 @@ smc_status smc_attn_decode(smc_ctx* ctx, int32_t k_tensor, int32_t v_tensor, con
     if (paged && len > ctx->paged.len) return SMC_E_RANGE;       // positions that were never appended have no page
 
     AttnSrc src{};
-    src.paged = paged ? 1 : 0;
-    src.bufA = paged ? (void* const*)ctx->paged.pools : (void* const*)ctx->ws.kvA;
-    src.bufB = paged ? nullptr : (void* const*)ctx->ws.kvB;
+    if (paged) {
+        src.kA = (const char*)ctx->h_pools[k_tensor]; src.vA = (const char*)ctx->h_pools[v_tensor];
+    } else {
+        src.kA = (const char*)ctx->h_kvA[k_tensor]; src.vA = (const char*)ctx->h_kvA[v_tensor];
+        src.kB = (const char*)ctx->h_kvB[k_tensor]; src.vB = (const char*)ctx->h_kvB[v_tensor];
+    }
     src.parity = ctx->ws.parity;
     src.table = paged ? ctx->paged.table : nullptr;
     src.P = paged ? ctx->paged.P : 1;
     src.M = paged ? ctx->paged.M : 0;
     src.H = cfg.kv_H; src.S = cfg.kv_S;
-    src.k_tensor = k_tensor; src.v_tensor = v_tensor;
 
     const int G = n_q_heads / cfg.kv_H;
     const int n_tiles = (len + kTile - 1) / kTile;

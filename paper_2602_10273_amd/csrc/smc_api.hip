@@ -178,6 +178,8 @@ smc_status smc_kv_bind(smc_ctx* ctx, void* const* h_bufA, void* const* h_bufB, i
     void* hh[2] = {d_histA, d_histB};
     if (hipMemcpy(ctx->ws.histAB, hh, sizeof(hh), hipMemcpyHostToDevice) != hipSuccess) return SMC_E_HIP;
     ctx->kv_bound = n > 0;
+    ctx->h_kvA.assign(h_bufA, h_bufA + n);
+    ctx->h_kvB.assign(h_bufB, h_bufB + n);
     ctx->hist_bound = d_histA != nullptr;
     return SMC_OK;
 }

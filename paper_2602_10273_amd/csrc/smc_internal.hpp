@@ -91,6 +91,7 @@ struct smc_ctx {
     int resampler;                // 0 systematic (the paper's), 1 stratified, 2 multinomial, 3 residual
     int ancestor_order;           // 0 as drawn, 1 survivors stay in place
     int kv_bound;
+    std::vector<void*> h_kvA, h_kvB, h_pools;   // host copies of the registered device pointers (kernel arguments)
     int hist_bound;
     int gather_grid;              // workgroups of the persistent gather kernel
     int gather_variant;           // vectors per thread / non-temporal choice of the gather kernel
