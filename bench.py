@@ -199,6 +199,13 @@ def attention_only(args, w, K, W, smc, synth, Session, np, torch):
                      "frac": gbps / HBM_PEAK_GBPS, "traffic": None, "launches": int(n), "avg_launch_ms": ms / max(n, 1),
                      "algorithmic_bytes_per_launch": bytes_per_call},
     }
+    try:
+        ratio = json.load(open(os.path.join(ROOT, "profiles", "hbm_traffic_ratio.json"))).get(args.workload, {}).get("attn_decode_kernel")
+        if ratio and not P:
+            out["roofline"]["traffic"] = ratio * bytes_per_call
+            out["roofline"]["traffic_source"] = "profiles/hbm_traffic_ratio.json x algorithmic bytes of this run"
+    except OSError:
+        pass
     out["measured_ceilings_GBps"] = measured_ceilings(smc, torch, "cuda")
     print(json.dumps(out))
 
