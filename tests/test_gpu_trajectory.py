@@ -201,3 +201,12 @@ def test_survivors_in_place_lockstep():
     table = synth.bigram_table(w1.V, w1.sigma, seed=0)
     st = run_lockstep(synth.scaled(w1, B=300), 5, w1.steps, table=table, eos_id=3, in_place=True)
     assert st["resamples"] > 10
+
+
+def test_long_trajectory_512_steps():
+    """The number of decode steps the cfg2 workload names (512), at a reduced vocabulary and cache: no drift."""
+    w = synth.scaled(synth.WORKLOADS["cfg2"], B=4, N=8, V=2056, layers=1, H=1, S=512, D=16)
+    st = run_lockstep(w, seed=11, steps=512)
+    print(st)
+    assert st["resamples"] > 100 and st["token_ties"] + st["ess_band"] + st["pos_band"] <= 4
+    assert st["max_dw"] < 1e-4 and st["max_dess"] < 1e-4
