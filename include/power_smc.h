@@ -228,7 +228,8 @@ smc_status smc_paged_check(smc_ctx* ctx, int32_t* h_alloc_failures);
  * paged pools through the page table if smc_paged_bind was called (then len <= positions appended), else from the
  * live buffer of each row of the tensors given to smc_kv_bind.  d_q: bf16 [R, n_q_heads, kv_D]; d_out: float
  * [R, n_q_heads, kv_D]; both 16-byte aligned.  d_workspace: at least smc_attn_workspace_bytes (0 = invalid
- * geometry), 16-byte aligned, scratch for this call only.  Enqueues on the context's stream. */
+ * geometry), 16-byte aligned, scratch for this call only.  Enqueues on the context's stream.  With eos_id >= 0 the
+ * rows of terminated particles are not read and their output is 0 (App. D: the absorbing state is a no-op). */
 size_t smc_attn_workspace_bytes(const smc_config* cfg, int32_t n_q_heads);
 smc_status smc_attn_decode(smc_ctx* ctx, int32_t k_tensor, int32_t v_tensor, const void* d_q, int32_t n_q_heads,
                            int32_t len, float scale, void* d_workspace, size_t workspace_bytes, float* d_out);

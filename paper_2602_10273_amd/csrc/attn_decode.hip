@@ -36,6 +36,7 @@ struct AttnSrc {
     const char* kB; const char* vB;   // dense: the same tensors in buffer B
     const int32_t* parity;      // dense: which buffer holds row r
     const int32_t* table;       // paged: [R, M] page numbers
+    const int32_t* done;        // termination flags (nullptr: no absorbing state): a terminated row is not read
     int P, M;                   // positions per page, pages per row
     int H, S;                   // KV heads, positions per row (dense)
 };
@@ -84,6 +85,19 @@ __global__ __launch_bounds__(kAttnWaves* kWave) void attn_decode_kernel(
     const int split = blockIdx.x % n_splits;
     const int head = (blockIdx.x / n_splits) % src.H;
     const int row = blockIdx.x / (n_splits * src.H);
+
+    if (src.done && src.done[row]) {            // absorbing state (App. D): the particle's cache is not read, its output is 0
+        for (int e = tid; e < G * D; e += kAttnWaves * kWave) {
+            const int64_t hq = (int64_t)row * Hq + (int64_t)head * G + e / D;
+            if (n_splits == 1) out[hq * D + e % D] = 0.f;
+            else {
+                float* rec = partial + (hq * n_splits + split) * (D + 2);
+                if (e % D == 0) { rec[0] = 0.f; rec[1] = 1.f; }      // weight 1 on a zero vector: the merge gives 0
+                rec[2 + e % D] = 0.f;
+            }
+        }
+        return;
+    }
 
     // the group's query heads as B operands: lane (head c, j) holds dims 32u + 8j .. + 7 of head c
     bf16x4 qb[2 * NKL];
@@ -377,6 +391,7 @@ smc_status smc_attn_decode(smc_ctx* ctx, int32_t k_tensor, int32_t v_tensor, con
         src.kB = (const char*)ctx->h_kvB[k_tensor]; src.vB = (const char*)ctx->h_kvB[v_tensor];
     }
     src.parity = ctx->ws.parity;
+    src.done = cfg.eos_id >= 0 ? ctx->ws.done : nullptr;
     src.table = paged ? ctx->paged.table : nullptr;
     src.P = paged ? ctx->paged.P : 1;
     src.M = paged ? ctx->paged.M : 0;

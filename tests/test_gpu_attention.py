@@ -96,3 +96,21 @@ def test_attention_extremes_and_argument_errors():
         with pytest.raises((smc.SMCError, ValueError)):
             bad()
     s.close()
+
+
+def test_terminated_rows_are_skipped():
+    """With an EOS token configured, rows whose particle has terminated are not read: output 0, others unchanged."""
+    rng = np.random.default_rng(9)
+    B, N, Hkv, G, S, D = 2, 4, 2, 4, 600, 128
+    R, Hq = B * N, Hkv * G
+    k = _bits(rng, (R, Hkv, S, D)); v = _bits(rng, (R, Hkv, S, D))
+    s = Session(B, N, 64, 8, "f32", 0.5, 0, kv=[k, v], with_hist=False, eos_id=5)
+    qb = _bits(rng, (R, Hq, D))
+    done = np.array([0, 1, 0, 0, 1, 1, 0, 0], np.int32)
+    s.set_done(done)
+    for length in (S, 40):                                     # several splits / a single one
+        got = s.attention(0, 1, _q_dev(qb), length, 0.1).cpu().numpy()
+        want = decode_attention(qb, k, v, length, 0.1)
+        assert np.all(got[done == 1] == 0.0)
+        assert np.abs(got[done == 0] - want[done == 0]).max() < TOL
+    s.close()
