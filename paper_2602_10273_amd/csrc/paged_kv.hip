@@ -19,7 +19,7 @@
 //   paged_reindex_kernel  : table[k, :] = old table[anc[k], :]; old row a's pages gain copies(a) - 1 references
 //   paged_prepare_kernel  : one workgroup per prompt; finds the needy rows, the lowest free pages, writes the slot of
 //                           every row and the list of (source page, new page) pairs
-//   paged_copy_kernel     : grid-stride over (pair, tensor, head): 16-byte vector copy of the filled part of a page
+//   paged_copy_kernel     : grid-stride over (pair, tensor): 16-byte vector copy of the filled part of a page
 #include "smc_internal.hpp"
 
 namespace psmc {
@@ -212,26 +212,28 @@ __global__ __launch_bounds__(kPagedThreads) void paged_prepare_kernel(
 }
 
 // Copies the first copy_bytes bytes (a multiple of 16) of each of the n_heads head chunks of a page, for every tensor
-// and every (source page, new page) pair.
+// and every (source page, new page) pair.  One work item is a (pair, tensor): its n_heads * copy_bytes / 16 vectors
+// are spread over the workgroup's threads as one flat range, so short prefixes of a page still keep every lane busy.
 __global__ __launch_bounds__(kPagedThreads) void paged_copy_kernel(
     void* const* __restrict__ pools, int n_tensors, int n_heads, long long page_stride, long long head_stride,
-    long long copy_bytes, int n_pages, const int32_t* __restrict__ counters,
+    int vecs_per_head, int n_pages, const int32_t* __restrict__ counters,
     const int32_t* __restrict__ cow_src, const int32_t* __restrict__ cow_dst)
 {
     const int n_pairs = counters[counters[3] ^ 1];     // the prepare kernel flipped the phase after using it
-    const int64_t per_pair = (int64_t)n_tensors * n_heads;
-    const int64_t total = per_pair * n_pairs;
+    const int64_t total = (int64_t)n_tensors * n_pairs;
+    const int n_vec = n_heads * vecs_per_head;
     for (int64_t w = blockIdx.x; w < total; w += gridDim.x) {
-        const int pair = (int)(w / per_pair);
-        const int rem = (int)(w - (int64_t)pair * per_pair);
-        const int tensor = rem / n_heads, head = rem - tensor * n_heads;
+        const int pair = (int)(w / n_tensors);
+        const int tensor = (int)(w - (int64_t)pair * n_tensors);
         const int from = cow_src[pair], to = cow_dst[pair];
         if (from < 0 || from >= n_pages || to < 0 || to >= n_pages) continue;      // only after a corrupted table
-        char* base = (char*)pools[tensor] + (int64_t)head * head_stride;
-        const char* s = base + (int64_t)from * page_stride;
-        char* d = base + (int64_t)to * page_stride;
-        for (int64_t off = (int64_t)threadIdx.x * 16; off < copy_bytes; off += (int64_t)kPagedThreads * 16)
-            *(vec16*)(d + off) = *(const vec16*)(s + off);
+        const char* s = (const char*)pools[tensor] + (int64_t)from * page_stride;
+        char* d = (char*)pools[tensor] + (int64_t)to * page_stride;
+        for (int v = threadIdx.x; v < n_vec; v += kPagedThreads) {
+            const int head = v / vecs_per_head;
+            const int64_t off = (int64_t)head * head_stride + (int64_t)(v - head * vecs_per_head) * 16;
+            __builtin_nontemporal_store(*(const vec16*)(s + off), (vec16*)(d + off));
+        }
     }
 }
 
@@ -338,7 +340,7 @@ smc_status smc_paged_prepare_append(smc_ctx* ctx, int32_t pos, int32_t* d_slot_o
         ScopedKernelTimer timer(ctx, 2);
         hipLaunchKernelGGL(paged_copy_kernel, dim3(ctx->n_cus * 8), dim3(kPagedThreads), 0, ctx->stream,
                            (void* const*)p.pools, cfg.kv_tensors, cfg.kv_H, head_stride * cfg.kv_H, head_stride,
-                           pos_bytes * o, cfg.B * p.Q, p.counters, p.cow_src, p.cow_dst);
+                           (int)(pos_bytes * o / 16), cfg.B * p.Q, p.counters, p.cow_src, p.cow_dst);
     }
     if (hipGetLastError() != hipSuccess) return SMC_E_HIP;
     p.len = pos + 1;
