@@ -78,7 +78,7 @@ __global__ __launch_bounds__(kAttnWaves* kWave) void attn_decode_kernel(
     __shared__ __attribute__((aligned(16))) char sh_v[kAttnWaves][kTile * kRowBytes];
     __shared__ __attribute__((aligned(16))) float sh_alpha[kAttnWaves][kHeadsPad];
     __shared__ float sh_m[kAttnWaves][kHeadsPad], sh_l[kAttnWaves][kHeadsPad];
-    __shared__ float sh_o[kHeadsPad][D];
+    __shared__ float sh_o[kAttnWaves][kHeadsPad][D];           // each wave's scaled output, summed when written out
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int c = lane & 15, j = lane >> 4;
@@ -112,7 +112,6 @@ __global__ __launch_bounds__(kAttnWaves* kWave) void attn_decode_kernel(
             qb[2 * u + 1] = hi4(v);
         }
     }
-    for (int i = tid; i < kHeadsPad * D; i += kAttnWaves * kWave) (&sh_o[0][0])[i] = 0.f;
 
     const int n_tiles = (len + kTile - 1) / kTile;
     const int tile_begin = split * tiles_per_split;
@@ -296,7 +295,7 @@ __global__ __launch_bounds__(kAttnWaves* kWave) void attn_decode_kernel(
     l_run += __shfl_xor(l_run, 16);
     l_run += __shfl_xor(l_run, 32);
     if (j == 0) { sh_m[wave][c] = m_run; sh_l[wave][c] = l_run; }
-    __syncthreads();                            // also: sh_o is zeroed
+    __syncthreads();
     float M = -INFINITY;
 #pragma unroll
     for (int w = 0; w < kAttnWaves; ++w) M = fmaxf(M, sh_m[w][c]);
@@ -307,7 +306,7 @@ __global__ __launch_bounds__(kAttnWaves* kWave) void attn_decode_kernel(
 #pragma unroll
         for (int t = 0; t < NDB; ++t)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) atomicAdd(&sh_o[4 * j + i][16 * t + c], acc[t][i] * f4[i]);
+            for (int i = 0; i < 4; ++i) sh_o[wave][4 * j + i][16 * t + c] = acc[t][i] * f4[i];
     }
     __syncthreads();
     // head g < G: total weight L, then either the normalised output or this split's partial record
@@ -319,13 +318,16 @@ __global__ __launch_bounds__(kAttnWaves* kWave) void attn_decode_kernel(
         float L = 0.f;
 #pragma unroll
         for (int w = 0; w < kAttnWaves; ++w) L += sh_l[w][g] * sh_alpha[w][g];
+        float o = 0.f;
+#pragma unroll
+        for (int w = 0; w < kAttnWaves; ++w) o += sh_o[w][g][d];
         const int64_t hq = (int64_t)row * Hq + (int64_t)head * G + g;
         if (n_splits == 1) {
-            out[hq * D + d] = sh_o[g][d] / L;
+            out[hq * D + d] = o / L;
         } else {
             float* rec = partial + (hq * n_splits + split) * (D + 2);
             if (d == 0) { rec[0] = Mg; rec[1] = L; }
-            rec[2 + d] = sh_o[g][d];
+            rec[2 + d] = o;
         }
     }
 }
