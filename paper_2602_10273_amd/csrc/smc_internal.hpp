@@ -117,11 +117,11 @@ struct ScopedKernelTimer {
             if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) return;
             pool.push_back(a); pool.push_back(b);
         }
-        hipEventRecord(pool[c->ev_used[kind]], c->stream);
+        (void)hipEventRecord(pool[c->ev_used[kind]], c->stream);
         stop = pool[c->ev_used[kind] + 1];
         c->ev_used[kind] += 2;
     }
-    ~ScopedKernelTimer() { if (stop) hipEventRecord(stop, c->stream); }
+    ~ScopedKernelTimer() { if (stop) (void)hipEventRecord(stop, c->stream); }
 };
 
 // launchers (each enqueues on ctx->stream; returns hipGetLastError())

@@ -483,7 +483,6 @@ __global__ __launch_bounds__(kWave) void finalize_rows_kernel(
         }
         return;
     }
-    const char* rowp = (const char*)logits + (int64_t)row * row_stride_bytes;
     const Partial* pp = partials + (int64_t)row * kMaxSplit;
 
     // sums
@@ -507,7 +506,9 @@ __global__ __launch_bounds__(kWave) void finalize_rows_kernel(
     if (idx >= V) idx = -1;                            // never read outside the row, whatever the partial holds
     double key = -INFINITY, lv = 0.0;
     if (idx >= 0) {
-        lv = (double)load_scalar<DT>(rowp, idx);
+        // the finalist's logit travels in the partial record (an exact copy: bf16 and fp32 both fit a float), so no
+        // second, dependent read of the logits is needed here
+        lv = (double)((lane & 1) ? pp[lane >> 1].l2 : pp[lane >> 1].l1);
         const U4 blk = philox4x32_10((uint32_t)idx >> 2, row, step, 0u, key0, key1);
         key = beta * lv + gumbel_f64(pick_word(blk, (uint32_t)idx & 3u));
     }
