@@ -134,3 +134,43 @@ def test_hbm_probe_reports_plausible_ceilings():
                 lambda: smc.smc_hbm_probe(0, buf.data_ptr() + 8, n - 64, stream)):
         with pytest.raises(smc.SMCError):
             bad()
+
+
+def test_checkpoint_and_resume_reproduce_the_uninterrupted_run():
+    """The state of a run is small and explicit (weights, cumulative log p, termination flags, live histories and
+    caches) and the random stream is keyed by (seed, step, row): a run restored from a snapshot into a fresh context
+    continues exactly like the uninterrupted one."""
+    w = synth.scaled(synth.WORKLOADS["cfg2"], B=6, N=8, V=4104, layers=1, H=2, S=24, D=64)
+    T, cut, seed = 20, 9, 13
+    kv = synth.kv_numpy(w, 4)
+
+    def advance(s, t0, t1):
+        for t in range(t0, t1 + 1):
+            s.step(to_device_logits(synth.logits_numpy(w, t, seed), w.dtype), t, w.alpha, w.alpha)
+            s.resample(t)
+            s.reindex(w.S, t)
+
+    def snapshot(s, t):
+        logW, cum, _ = s.state()
+        return dict(logW=logW, cum=cum, done=s.done(), hist=s.live_hist(), kv=[s.live_kv(i) for i in range(len(kv))],
+                    tokens=s.tokens.cpu().numpy())
+
+    full = Session(w.B, w.N, w.V, T, w.dtype, w.kappa, seed, kv=kv, eos_id=7)
+    advance(full, 1, cut)
+    snap = snapshot(full, cut)
+    advance(full, cut + 1, T)
+    want = snapshot(full, T)
+    full.close()
+
+    resumed = Session(w.B, w.N, w.V, T, w.dtype, w.kappa, seed, kv=snap["kv"], eos_id=7)   # live rows go to buffer A
+    resumed.histA.copy_(torch.as_tensor(snap["hist"]))
+    resumed.set_state(snap["logW"], snap["cum"])
+    resumed.set_done(snap["done"])
+    advance(resumed, cut + 1, T)
+    got = snapshot(resumed, T)
+    resumed.close()
+    assert np.array_equal(got["tokens"], want["tokens"]) and np.array_equal(got["hist"][:, :T], want["hist"][:, :T])
+    assert np.array_equal(got["logW"], want["logW"]) and np.array_equal(got["cum"], want["cum"])
+    assert np.array_equal(got["done"], want["done"])
+    for a, b in zip(got["kv"], want["kv"]):
+        assert np.array_equal(a, b)
