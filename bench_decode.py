@@ -5,7 +5,8 @@ The paper's headline is a latency ratio over standard decoding (Sec. 7, Table 1)
 environment, so the language model here is a RANDOM-INIT decoder of the Qwen2.5-7B shape (28 layers, d = 3584,
 28 query / 4 KV heads of 128, d_ff = 18944, V = 152064; bf16) written in plain PyTorch-ROCm: its tokens mean nothing,
 its per-step cost (weight reads, attention over the cache, the LM head) is that of the real model.  Attention reads the
-cache in place through smc_attn_decode, the logits go straight from the LM head into smc_step.
+cache in place through smc_attn_decode, new keys and values are stored by smc_kv_append, and the logits go straight
+from the LM head into smc_step.
 
 Three loops over the same model, rows and cache length are timed:
   plain  : one token per row per step by Gumbel-max sampling at temperature 1/alpha in PyTorch, no weights, no reorder;
@@ -122,21 +123,11 @@ def run_mode(mode, args, model, torch, smc, Session):
     g = torch.Generator(device="cuda"); g.manual_seed(args.seed + 1)
     for t in (s.pools if paged else s.kvA):                       # the cache as start positions of earlier decoding left it
         t.normal_(generator=g)
-    parity = None if paged else s.parity_view()
     scale = 1.0 / math.sqrt(model.D)
     pos_state = dict(pos=start)
 
     def write_kv(layer, k, v):
-        pos = pos_state["pos"]
-        for ten, x in ((2 * layer, k), (2 * layer + 1, v)):
-            if paged:
-                s.pools[ten][s.slot.long(), :, pos % P, :] = x
-            elif mode == "plain":
-                s.kvA[ten][:, :, pos, :] = x                      # rows never change buffer without a reorder
-            else:
-                live_b = (parity != 0).view(R, 1, 1)
-                s.kvA[ten][:, :, pos, :] = torch.where(live_b, s.kvA[ten][:, :, pos, :], x)
-                s.kvB[ten][:, :, pos, :] = torch.where(live_b, x, s.kvB[ten][:, :, pos, :])
+        s.append(2 * layer, 2 * layer + 1, k, v, pos_state["pos"])     # one launch: each row's live buffer or page
 
     def attend(layer, q, length):
         return s.attention(2 * layer, 2 * layer + 1, q, length, scale)

@@ -234,6 +234,15 @@ size_t smc_attn_workspace_bytes(const smc_config* cfg, int32_t n_q_heads);
 smc_status smc_attn_decode(smc_ctx* ctx, int32_t k_tensor, int32_t v_tensor, const void* d_q, int32_t n_q_heads,
                            int32_t len, float scale, void* d_workspace, size_t workspace_bytes, float* d_out);
 
+/* The store a decoder makes before it attends: writes position pos of every row of KV tensor k_tensor (and of
+ * v_tensor unless it is -1) where that row's data lives -- the row's live buffer (dense) or the page that
+ * smc_paged_prepare_append gave it (paged: pos must be below the number of appended positions, else SMC_E_STATE).
+ * d_k_new / d_v_new: device, bf16 [R, kv_H, kv_D], rows k_row_stride / v_row_stride elements apart (>= kv_H*kv_D,
+ * multiples of 8; pointers 16-byte aligned, else SMC_E_ALIGN), read only.  0 <= pos < kv_S.  Terminated rows are
+ * written like any other.  Enqueues one launch on the context's stream.  Not part of the paper's method. */
+smc_status smc_kv_append(smc_ctx* ctx, int32_t k_tensor, int32_t v_tensor, const void* d_k_new, int64_t k_row_stride,
+                         const void* d_v_new, int64_t v_row_stride, int32_t pos);
+
 /* Optional timing of the dominant kernels.  While enabled, a pair of HIP events is recorded on the context's
  * stream around every launch of kind 0 (the vocabulary-pass kernel of smc_step), kind 1 (the KV gather kernel of
  * smc_kv_reindex), kind 2 (the page copy of smc_paged_prepare_append) and kind 3 (the attention kernel of

@@ -19,7 +19,7 @@ EXPORTS = ["smc_workspace_bytes", "smc_init", "smc_destroy", "smc_kv_bind", "smc
            "smc_set_tuning", "smc_set_resampler", "smc_set_ancestor_order", "smc_set_gather_tuning", "smc_profile_enable", "smc_profile_read", "smc_status_str",
            "smc_paged_workspace_bytes", "smc_paged_pool_bytes", "smc_paged_bind", "smc_paged_prepare_append",
            "smc_paged_reindex", "smc_paged_view", "smc_paged_check", "smc_hbm_probe",
-           "smc_attn_workspace_bytes", "smc_attn_decode", "smc_kv_parity"]
+           "smc_attn_workspace_bytes", "smc_attn_decode", "smc_kv_parity", "smc_kv_append"]
 
 
 class smc_config(C.Structure):
@@ -81,6 +81,7 @@ def lib():
         L.smc_attn_workspace_bytes.restype = C.c_size_t
         L.smc_attn_workspace_bytes.argtypes = [C.POINTER(smc_config), i32]
         L.smc_attn_decode.argtypes = [vp, i32, i32, vp, i32, i32, C.c_float, vp, C.c_size_t, vp]
+        L.smc_kv_append.argtypes = [vp, i32, i32, vp, C.c_int64, vp, C.c_int64, i32]
         L.smc_kv_parity.argtypes = [vp, C.POINTER(vp)]
         L.smc_hbm_probe.argtypes = [i32, vp, C.c_size_t, vp, C.POINTER(f64)]
         L.smc_status_str.restype = C.c_char_p
@@ -268,6 +269,11 @@ def smc_attn_workspace_bytes(cfg, n_q_heads):
 def smc_attn_decode(ctx, k_tensor, v_tensor, d_q, n_q_heads, length, scale, d_workspace, workspace_bytes, d_out):
     _check("smc_attn_decode", lib().smc_attn_decode(ctx, k_tensor, v_tensor, _ptr(d_q), n_q_heads, length, scale,
                                                     _ptr(d_workspace), workspace_bytes, _ptr(d_out)))
+
+
+def smc_kv_append(ctx, k_tensor, v_tensor, d_k_new, k_row_stride, d_v_new, v_row_stride, pos):
+    _check("smc_kv_append", lib().smc_kv_append(ctx, k_tensor, v_tensor, _ptr(d_k_new), k_row_stride,
+                                                None if d_v_new is None else _ptr(d_v_new), v_row_stride, pos))
 
 
 def smc_kv_parity(ctx):

@@ -6,7 +6,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpower_smc.so")
-SOURCES = ["smc_api.hip", "vocab_pass.hip", "weights.hip", "kv_gather.hip", "paged_kv.hip", "hbm_probe.hip", "attn_decode.hip"]
+SOURCES = ["smc_api.hip", "vocab_pass.hip", "weights.hip", "kv_gather.hip", "paged_kv.hip", "hbm_probe.hip", "attn_decode.hip", "kv_append.hip"]
 HEADERS = ["smc_internal.hpp", "device_rng.hpp", os.path.join(ROOT, "include", "power_smc.h")]
 
 

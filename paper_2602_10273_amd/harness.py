@@ -114,6 +114,14 @@ class Session:
         off = smc.smc_kv_parity(self.ctx) - self.workspace.data_ptr()
         return self.workspace[off:off + 4 * self.R].view(torch.int32)
 
+    def append(self, k_tensor, v_tensor, k_new, v_new, pos):
+        """k_new / v_new: [R, H, D] bf16 views whose rows may be strided; v_tensor = -1 writes K only."""
+        assert k_new.stride(-1) == 1 and k_new.stride(1) == k_new.shape[2]
+        if v_tensor >= 0:
+            assert v_new.stride(-1) == 1 and v_new.stride(1) == v_new.shape[2]
+        smc.smc_kv_append(self.ctx, k_tensor, v_tensor, k_new, k_new.stride(0), v_new if v_tensor >= 0 else None,
+                          v_new.stride(0) if v_tensor >= 0 else 0, pos)
+
     def attention(self, k_tensor, v_tensor, q, length, scale):
         """Decode attention over the context's cache; q: bf16 [R, Hq, D] device tensor; returns float32 [R, Hq, D]."""
         Hq = q.shape[1]

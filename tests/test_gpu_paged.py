@@ -30,6 +30,13 @@ def _write(s, pk, pos, new):
     """The decoder's append on both sides: new[ten] is [R, H, D] uint16."""
     o = pos % pk.P
     pk.write(pos, new)
+    if len(new) == 2 and pos % 2 == 0:                         # through the library's append; V from a strided view
+        R, H, D = new[0].shape
+        k = torch.as_tensor(new[0].view(np.int16)).cuda()
+        wide = torch.zeros((R, H * D + 8), dtype=torch.int16, device="cuda")
+        wide[:, :H * D] = torch.as_tensor(new[1].view(np.int16)).cuda().view(R, H * D)
+        s.append(0, 1, k, wide[:, :H * D].view(R, H, D), pos)
+        return
     for ten, x in enumerate(new):
         s.pools[ten].view(torch.int16)[s.slot.long(), :, o, :] = torch.as_tensor(x.view(np.int16)).cuda()
 
