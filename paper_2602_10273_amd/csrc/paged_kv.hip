@@ -15,7 +15,6 @@
 // tables can be compared bit for bit with a CPU model that follows them.
 //
 //   paged_init_kernel     : the state after len0 appends with no resampling (table[b*N+k, j] = b*Q + j*N + k)
-//   paged_snapshot_kernel : copies the table rows of resampled prompts aside
 //   paged_reindex_kernel  : table[k, :] = old table[anc[k], :]; old row a's pages gain copies(a) - 1 references
 //   paged_prepare_kernel  : one workgroup per prompt; finds the needy rows, the lowest free pages, writes the slot of
 //                           every row and the list of (source page, new page) pairs
@@ -26,7 +25,8 @@ namespace psmc {
 
 namespace {
 constexpr int kPagedThreads = 256;
-constexpr int kEntriesPerBlock = 2048;               // table entries one workgroup of the reorder handles
+constexpr int kEntriesPerBlock = 2048;               // table entries one workgroup of the reorder handles (>= SMC_MAX_PARTICLES)
+static_assert(kEntriesPerBlock >= SMC_MAX_PARTICLES, "one column of a prompt must fit in a workgroup's LDS tile");
 constexpr int kScanPerThread = 32;                  // reference counts one thread examines per sweep of the free-page search
 typedef unsigned int vec16 __attribute__((ext_vector_type(4)));
 
@@ -67,30 +67,19 @@ __global__ void paged_init_kernel(int R, int N, int M, int Q, int P, int len0, i
     if (i < 8) counters[i] = 0;                        // pair counters of the two phases, failures, phase, ticket
 }
 
-// Reorder, part 1: the in-use columns of a resampled prompt's table rows are copied aside.
-// Grid: prompts x chunks of kEntriesPerBlock table entries.
-__global__ __launch_bounds__(kPagedThreads) void paged_snapshot_kernel(
-    const int32_t* __restrict__ resampled, int N, int M, int ncol, int chunks, const int32_t* __restrict__ table,
-    int32_t* __restrict__ table_tmp)
-{
-    const int b = blockIdx.x / chunks;
-    if (!resampled[b]) return;
-    const int n = N * ncol;
-    const int e0 = (blockIdx.x % chunks) * kEntriesPerBlock;
-    for (int e = e0 + threadIdx.x; e < min(n, e0 + kEntriesPerBlock); e += kPagedThreads) {
-        const int64_t at = (int64_t)(b * N + e / ncol) * M + e % ncol;
-        table_tmp[at] = table[at];
-    }
-}
-
-// Reorder, part 2: table[k, j] = old table[anc[k], j].  Old row a's page for column j gains copies(a) - 1 references,
+// Reorder: table[k, j] = old table[anc[k], j].  Old row a's page for column j gains copies(a) - 1 references,
 // copies(a) being the number of rows that continue a; a page whose count reaches 0 is free from then on.
+// The permutation acts along the rows and every column is permuted on its own, so one workgroup takes all N rows of
+// `cols` columns of one prompt: it reads them into LDS, then writes them back permuted -- no other workgroup
+// touches these entries, so no copy of the old table is needed.  Grid: prompts x column chunks; N * cols <=
+// kEntriesPerBlock.
 __global__ __launch_bounds__(kPagedThreads) void paged_reindex_kernel(
-    const int32_t* __restrict__ anc, const int32_t* __restrict__ resampled, int N, int M, int Q, int ncol, int chunks,
-    int32_t* __restrict__ table, const int32_t* __restrict__ table_tmp, int32_t* __restrict__ refcnt)
+    const int32_t* __restrict__ anc, const int32_t* __restrict__ resampled, int N, int M, int Q, int ncol, int cols, int chunks,
+    int32_t* __restrict__ table, int32_t* __restrict__ refcnt)
 {
     __shared__ int32_t sh_anc[SMC_MAX_PARTICLES];
     __shared__ int32_t sh_copies[SMC_MAX_PARTICLES];
+    __shared__ int32_t sh_old[kEntriesPerBlock];
     const int b = blockIdx.x / chunks, tid = threadIdx.x;
     if (!resampled[b]) return;
     const int row0 = b * N, page0 = b * Q;
@@ -102,15 +91,21 @@ __global__ __launch_bounds__(kPagedThreads) void paged_reindex_kernel(
         sh_anc[k] = a;
         atomicAdd(&sh_copies[a], 1);
     }
+    const int j0 = (blockIdx.x % chunks) * cols;
+    const int nc = min(cols, ncol - j0);               // columns of this workgroup
+    const int n = N * nc;
+    for (int e = tid; e < n; e += kPagedThreads) {
+        const int k = e / nc, j = j0 + e % nc;
+        sh_old[e] = table[(int64_t)(row0 + k) * M + j];
+    }
     __syncthreads();
-    const int n = N * ncol;
-    const int e0 = (blockIdx.x % chunks) * kEntriesPerBlock;
-    for (int e = e0 + tid; e < min(n, e0 + kEntriesPerBlock); e += kPagedThreads) {
-        const int k = e / ncol, j = e % ncol;
-        table[(int64_t)(row0 + k) * M + j] = table_tmp[(int64_t)(row0 + sh_anc[k]) * M + j];
+    for (int e = tid; e < n; e += kPagedThreads) {
+        const int k = e / nc, c = e % nc;
+        const int a = sh_anc[k];
+        if (a != k) table[(int64_t)(row0 + k) * M + j0 + c] = sh_old[a * nc + c];
         const int gained = sh_copies[k] - 1;
         if (gained != 0) {
-            const int p = table_tmp[(int64_t)(row0 + k) * M + j];
+            const int p = sh_old[e];
             if (p >= page0 && p < page0 + Q) atomicAdd(&refcnt[p], gained);
         }
     }
@@ -269,7 +264,6 @@ size_t paged_layout(const smc_config* c, const PagedDims& d, char* base, PagedKV
     auto take = [&](size_t bytes) { char* q = base ? base + off : nullptr; off += up(bytes); return q; };
     char* q;
     q = take(d.n_table * 4); if (p) p->table = (int32_t*)q;
-    q = take(d.n_table * 4); if (p) p->table_tmp = (int32_t*)q;
     q = take(d.n_pages * 4); if (p) p->refcnt = (int32_t*)q;
     q = take(R * 4); if (p) p->cow_src = (int32_t*)q;
     q = take(R * 4); if (p) p->cow_dst = (int32_t*)q;
@@ -358,12 +352,11 @@ smc_status smc_paged_reindex(smc_ctx* ctx, const int32_t* d_anc, const int32_t* 
     const int ncol = (p.len + p.P - 1) / p.P;
     if (ncol > 0) {
         const int N = ctx->cfg.N;
-        const int chunks = (int)(((int64_t)N * ncol + kEntriesPerBlock - 1) / kEntriesPerBlock);
+        const int cols = kEntriesPerBlock / N < ncol ? kEntriesPerBlock / N : ncol;      // >= 1: N <= SMC_MAX_PARTICLES
+        const int chunks = (ncol + cols - 1) / cols;
         const dim3 grid((unsigned)((int64_t)chunks * ctx->cfg.B));
-        hipLaunchKernelGGL(paged_snapshot_kernel, grid, dim3(kPagedThreads), 0, ctx->stream, d_resampled, N, p.M, ncol, chunks,
-                           p.table, p.table_tmp);
         hipLaunchKernelGGL(paged_reindex_kernel, grid, dim3(kPagedThreads), 0, ctx->stream, d_anc, d_resampled, N, p.M, p.Q,
-                           ncol, chunks, p.table, p.table_tmp, p.refcnt);
+                           ncol, cols, chunks, p.table, p.refcnt);
         if (hipGetLastError() != hipSuccess) return SMC_E_HIP;
     }
     return SMC_OK;

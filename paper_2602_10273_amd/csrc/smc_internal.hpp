@@ -68,7 +68,6 @@ struct PagedKV {
     int P, M, Q;                  // positions per page, pages per row, pages per prompt (= N*M)
     int len;                      // positions appended so far (the same for every row)
     int32_t* table;               // [R*M] page of row r for positions [j*P, (j+1)*P), -1 while unused
-    int32_t* table_tmp;           // [R*M] the reorder's copy of the old table
     int32_t* refcnt;              // [B*Q] rows that reference a page; 0 = free
     int32_t* cow_src;             // [R] source page of each pending copy
     int32_t* cow_dst;             // [R] new page of each pending copy
