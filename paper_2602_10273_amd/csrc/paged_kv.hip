@@ -304,11 +304,12 @@ smc_status smc_paged_bind(smc_ctx* ctx, void* const* h_pools, int32_t page_len, 
     }
     if (hipStreamSynchronize(ctx->stream) != hipSuccess) return SMC_E_HIP;
     PagedKV& p = ctx->paged;
+    p.bound = 0;                                       // a failed (re)bind leaves the context unbound
     paged_layout(&ctx->cfg, d, (char*)d_workspace, &p);
     p.P = d.P; p.M = d.M; p.Q = d.Q; p.len = len0;
     if (hipMemcpy(p.pools, h_pools, (size_t)ctx->cfg.kv_tensors * sizeof(void*), hipMemcpyHostToDevice) != hipSuccess)
         return SMC_E_HIP;
-    ctx->h_pools.assign(h_pools, h_pools + ctx->cfg.kv_tensors);
+    try { ctx->h_pools.assign(h_pools, h_pools + ctx->cfg.kv_tensors); } catch (...) { return SMC_E_STATE; }
     const size_t n = d.n_table > d.n_pages ? d.n_table : d.n_pages;
     hipLaunchKernelGGL(paged_init_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, ctx->stream, ctx->R, ctx->cfg.N,
                        d.M, d.Q, d.P, len0, p.table, p.refcnt, p.counters);

@@ -177,9 +177,14 @@ smc_status smc_kv_bind(smc_ctx* ctx, void* const* h_bufA, void* const* h_bufB, i
     }
     void* hh[2] = {d_histA, d_histB};
     if (hipMemcpy(ctx->ws.histAB, hh, sizeof(hh), hipMemcpyHostToDevice) != hipSuccess) return SMC_E_HIP;
+    try {                                              // no exception may cross the C boundary
+        if (n > 0) { ctx->h_kvA.assign(h_bufA, h_bufA + n); ctx->h_kvB.assign(h_bufB, h_bufB + n); }
+        else { ctx->h_kvA.clear(); ctx->h_kvB.clear(); }
+    } catch (...) {
+        ctx->kv_bound = 0;
+        return SMC_E_STATE;
+    }
     ctx->kv_bound = n > 0;
-    ctx->h_kvA.assign(h_bufA, h_bufA + n);
-    ctx->h_kvB.assign(h_bufB, h_bufB + n);
     ctx->hist_bound = d_histA != nullptr;
     return SMC_OK;
 }
@@ -297,12 +302,14 @@ smc_status smc_get_diag(smc_ctx* ctx, double* h_delta, double* h_logZ1, double* 
         !get(h_gap, ctx->ws.d_gap, R * 8))
         return SMC_E_HIP;
     if (h_counters) {
-        std::vector<int32_t> st(3 * R);
-        if (hipMemcpy(st.data(), ctx->ws.d_rowstat, 3 * R * 4, hipMemcpyDeviceToHost) != hipSuccess) return SMC_E_HIP;
+        int32_t* st = new (std::nothrow) int32_t[3 * R];
+        if (!st) return SMC_E_STATE;
+        if (hipMemcpy(st, ctx->ws.d_rowstat, 3 * R * 4, hipMemcpyDeviceToHost) != hipSuccess) { delete[] st; return SMC_E_HIP; }
         h_counters[0] = h_counters[1] = h_counters[2] = 0;
         for (size_t r = 0; r < R; ++r) {
             h_counters[0] += (uint64_t)st[3 * r]; h_counters[1] += (uint64_t)st[3 * r + 1]; h_counters[2] += (uint64_t)st[3 * r + 2];
         }
+        delete[] st;
         h_counters[3] = (uint64_t)R * (uint64_t)ctx->cfg.V;
     }
     return SMC_OK;
@@ -365,11 +372,11 @@ smc_status smc_set_tuning(smc_ctx* ctx, int32_t n_split, int32_t dense, int32_t 
     if (!ctx) return SMC_E_NULL;
     if (n_split < 0 || n_split > kMaxSplit) return SMC_E_RANGE;
     if (wg_waves != 0 && wg_waves != 4 && wg_waves != 16) return SMC_E_RANGE;
+    if (dense < 0 || dense > 1) return SMC_E_RANGE;
     int aw, as;
     auto_shape(ctx->R, ctx->cfg.V, ctx->cfg.logits_dtype, &aw, &as);
     ctx->wg_waves = wg_waves == 0 ? aw : wg_waves;
     ctx->n_split = n_split == 0 ? (wg_waves == 0 || wg_waves == aw ? as : 1) : n_split;
-    if (dense < 0 || dense > 1) return SMC_E_RANGE;
     ctx->dense = dense;
     return SMC_OK;
 }

@@ -113,7 +113,9 @@ struct ScopedKernelTimer {
         auto& pool = c->ev_pool[kind];
         if (c->ev_used[kind] + 2 > pool.size()) {
             hipEvent_t a, b;
-            if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) return;
+            if (hipEventCreate(&a) != hipSuccess) return;
+            if (hipEventCreate(&b) != hipSuccess) { (void)hipEventDestroy(a); return; }
+            try { pool.reserve(pool.size() + 2); } catch (...) { (void)hipEventDestroy(a); (void)hipEventDestroy(b); return; }
             pool.push_back(a); pool.push_back(b);
         }
         (void)hipEventRecord(pool[c->ev_used[kind]], c->stream);
