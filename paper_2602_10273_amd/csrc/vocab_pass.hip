@@ -202,7 +202,7 @@ __device__ __forceinline__ float dec_bound(int i) { return __int_as_float(i >= 0
 // DENSE: every entry is scored in place (no filter, no ring) -- the plain definition, kept for cross-checks.
 // NW: waves per workgroup (4 or 16).
 template <int DT, int P, bool DENSE, int NW>
-__global__ __launch_bounds__(NW * kWave) void vocab_pass_kernel(
+__global__ __launch_bounds__(NW * kWave, 4) void vocab_pass_kernel(
     const void* __restrict__ logits, int64_t row_stride_bytes, int V, float beta, uint32_t key0, uint32_t key1,
     uint32_t step, int n_split, int vecs_per_split, Partial* __restrict__ partials, const int32_t* __restrict__ done)
 {
@@ -211,6 +211,12 @@ __global__ __launch_bounds__(NW * kWave) void vocab_pass_kernel(
     constexpr int THREADS = NW * kWave;
     constexpr int kRing = 1024;                        // candidate ring entries per wave (power of two)
     static_assert(kRing >= 2 * EPV * kWave, "a full vector of candidates must fit beside a partly filled ring");
+    // Queueing costs ~6 ps per queued entry, scoring a vector in place ~1.4 ps per entry whatever its content
+    // (measured on 2048 bf16 rows), so the two meet where a little under a quarter of the entries qualify, i.e.
+    // where a lane's EPV entries include a qualifying one with probability 1 - 0.77^EPV.  A vector with at least
+    // this many such lanes is scored in place.  (Deciding once per batch of vectors instead was tried: the
+    // threshold rises fast at the start of a slice and the stale decision cost more than the test.)
+    constexpr int kScoreInPlace = EPV == 8 ? 56 : 42;
     __shared__ uint2 ring[DENSE ? 1 : NW][DENSE ? 1 : kRing];     // (vocabulary index, logit bits)
     __shared__ int wg_bound;                           // best "cannot win below this" bound of the whole workgroup
 
@@ -342,16 +348,42 @@ __global__ __launch_bounds__(NW * kWave) void vocab_pass_kernel(
 #pragma unroll
             for (int j = 1; j < EPV; ++j) vm = fmaxf(vm, x[j]);
             if (__ballot(vm > m)) raise_max(wave_max_f32(vm));
+            if (__popcll(__ballot(vm >= thr)) >= kScoreInPlace) {           // wave-uniform
+                // So many entries may still win (a flat proposal: small beta, or logits that differ little) that
+                // queueing them one by one costs more than scoring the vector where it is, four entries per
+                // Philox block.
 #pragma unroll
-            for (int j = 0; j < EPV; ++j) {
-                const bool hit = x[j] >= thr;
-                const unsigned long long mk = __ballot(hit);
-                if (mk) {                                                   // wave-uniform
-                    if (hit) {
-                        const int slot = (q_head + q_count + mask_rank(mk)) & (kRing - 1);
-                        ring[wave][slot] = make_uint2((uint32_t)(v0 + j), __float_as_uint(x[j]));
+                for (int q4 = 0; q4 < EPV / 4; ++q4) {
+                    bool need = false;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) need = need || x[q4 * 4 + j] >= thr;
+                    if (need) {
+                        const U4 blk = philox4x32_10((uint32_t)(v0 >> 2) + q4, row, step, 0u, key0, key1);
+                        const uint32_t wd[4] = {blk.x, blk.y, blk.z, blk.w};
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            if (x[q4 * 4 + j] >= thr) {
+                                top.offer(beta, x[q4 * 4 + j], gumbel_f32(wd[j]), v0 + q4 * 4 + j);
+                                ++n_scored;
+                            }
+                        }
                     }
-                    q_count += __popcll(mk);
+                }
+                float bound = top.a.i >= 0 ? top.a.l + (top.a.g - kGumbelMax - kKeyMargin) / beta : -3.4e38f;
+                bound = uniform(wave_max_f32(bound));
+                thr = fmaxf(thr, lower(bound));
+            } else {
+#pragma unroll
+                for (int j = 0; j < EPV; ++j) {
+                    const bool hit = x[j] >= thr;
+                    const unsigned long long mk = __ballot(hit);
+                    if (mk) {                                               // wave-uniform
+                        if (hit) {
+                            const int slot = (q_head + q_count + mask_rank(mk)) & (kRing - 1);
+                            ring[wave][slot] = make_uint2((uint32_t)(v0 + j), __float_as_uint(x[j]));
+                        }
+                        q_count += __popcll(mk);
+                    }
                 }
             }
         }

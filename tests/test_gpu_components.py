@@ -88,6 +88,23 @@ def test_step_schedules_and_temperatures(alpha_t, alpha_prev, tau):
             check_step(w, seed=9, t=5, alpha_t=alpha_t, alpha_prev=alpha_prev, tau=tau, dense=mode)
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_step_flat_proposals_are_scored_in_place(dtype):
+    """Small beta or logits that differ little: most entries may win, the pass scores whole vectors where they are
+    (four entries per Philox block) instead of queueing them -- same tokens as the oracle and as dense scoring."""
+    w = synth.scaled(synth.WORKLOADS["cfg2"], B=2, N=6, V=152064, dtype=dtype)
+    x = synth.logits_numpy(synth.scaled(w, dtype="f32"), 1, 3)
+    x[w.R // 2:] *= np.float32(0.125)                    # rows whose logits barely differ: flat even at beta = 4
+    if dtype == "bf16":
+        x = synth.f32_to_bf16_bits(x)
+    for alpha, rows in ((1.0, slice(None)), (4.0, slice(w.R // 2, None))):
+        for ww, ns in ((4, 1), (16, 0)):
+            r1 = check_step(w, seed=3, t=1, alpha_t=alpha, alpha_prev=alpha, tau=-1.0, logits=x, wg_waves=ww, n_split=ns)
+            r2 = check_step(w, seed=3, t=1, alpha_t=alpha, alpha_prev=alpha, tau=-1.0, logits=x, dense=1, wg_waves=ww, n_split=ns)
+            assert np.array_equal(r1["tokens"], r2["tokens"])
+            assert r1["counters"][1] > 0.3 * r1["counters"][3]      # a large share of the entries was scored
+
+
 def test_step_degenerate_rows():
     V = 4096 + 24
     w = synth.scaled(synth.WORKLOADS["cfg4"], B=1, N=6, V=V)
