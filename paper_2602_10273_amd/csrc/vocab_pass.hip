@@ -348,7 +348,10 @@ __global__ __launch_bounds__(NW * kWave, 4) void vocab_pass_kernel(
 #pragma unroll
             for (int j = 1; j < EPV; ++j) vm = fmaxf(vm, x[j]);
             if (__ballot(vm > m)) raise_max(wave_max_f32(vm));
-            if (__popcll(__ballot(vm >= thr)) >= kScoreInPlace) {           // wave-uniform
+            const unsigned long long lanes = __ballot(vm >= thr);           // lanes that hold a qualifying entry
+            if (lanes == 0ull) {
+                // nothing in this vector can win: the common case once the threshold has risen
+            } else if (__popcll(lanes) >= kScoreInPlace) {                  // wave-uniform
                 // So many entries may still win (a flat proposal: small beta, or logits that differ little) that
                 // queueing them one by one costs more than scoring the vector where it is, four entries per
                 // Philox block.
