@@ -21,6 +21,7 @@ struct AppendDst {
     const int32_t* table;       // paged: [R, M]; nullptr = dense
     int n;                      // 1 or 2 tensors
     int P, M, H, S;
+    int n_pages;                // paged: pages in a pool
     int row_vecs;               // H * D * 2 / 16
     int head_vecs;              // D * 2 / 16
 };
@@ -39,6 +40,7 @@ __global__ __launch_bounds__(256) void kv_append_kernel(AppendDst d, int R, int 
     int span;                        // positions per unit
     if (d.table) {
         base = d.a[which]; unit = d.table[(int64_t)r * d.M + pos / d.P]; offset = pos % d.P; span = d.P;
+        if (unit < 0 || unit >= d.n_pages) return;    // never the case for a table the library maintains
     } else {
         base = d.parity[r] ? d.b[which] : d.a[which]; unit = r; offset = pos; span = d.S;
     }
@@ -86,6 +88,7 @@ extern "C" smc_status smc_kv_append(smc_ctx* ctx, int32_t k_tensor, int32_t v_te
     d.table = paged ? ctx->paged.table : nullptr;
     d.n = n;
     d.P = paged ? ctx->paged.P : 1; d.M = paged ? ctx->paged.M : 0;
+    d.n_pages = paged ? cfg.B * ctx->paged.Q : 0;
     d.H = cfg.kv_H; d.S = cfg.kv_S;
     d.head_vecs = cfg.kv_D / 8;
     d.row_vecs = cfg.kv_H * d.head_vecs;
