@@ -5,7 +5,6 @@ steps of Algorithm 1 together in the paper's order.  Only tests, the smoke check
 the bench's cpu_baseline leg may import this module; it never imports the HIP package.
 """
 import ctypes as C
-import os
 
 import numpy as np
 

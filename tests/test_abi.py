@@ -1,6 +1,5 @@
 """Host-side checks of the C ABI that need no GPU: the library loads, exports every declared symbol,
 sizes its workspace and rejects bad arguments before touching a device."""
-import ctypes as C
 import os
 import re
 

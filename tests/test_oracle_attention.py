@@ -1,6 +1,5 @@
 """Pins of the decode-attention oracle: closed forms and an independent library routine (torch CPU SDPA in fp64)."""
 import numpy as np
-import pytest
 import torch
 
 from oracle.attention import bf16_bits_to_f64, decode_attention

@@ -3,10 +3,8 @@ from fractions import Fraction
 
 import mpmath as mp
 import numpy as np
-import pytest
 
 from oracle import reference as orc
-from paper_2602_10273_amd import synth
 
 
 def test_ess_special_cases_and_definition():

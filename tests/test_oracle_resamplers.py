@@ -2,7 +2,6 @@
 unbiasedness E[#copies of j] = N w_j, and the whole-method normalising-constant check with each of them."""
 import numpy as np
 import pytest
-from scipy import stats
 
 from oracle import reference as orc
 from oracle.enumerate import enumerate_power_target
