@@ -15,7 +15,8 @@
 // tables can be compared bit for bit with a CPU model that follows them.
 //
 //   paged_init_kernel     : the state after len0 appends with no resampling (table[b*N+k, j] = b*Q + j*N + k)
-//   paged_reindex_kernel  : table[k, :] = old table[anc[k], :]; old row a's pages gain copies(a) - 1 references
+//   paged_reorder_kernel  : table[k, :] = old table[anc[k], :]; old row a's pages gain copies(a) - 1 references;
+//                           token histories, cumulative log p and termination flags follow in the same launch
 //   paged_prepare_kernel  : one workgroup per prompt; finds the needy rows, the lowest free pages, writes the slot of
 //                           every row and the list of (source page, new page) pairs
 //   paged_copy_kernel     : grid-stride over (pair, tensor): 16-byte vector copy of the filled part of a page
@@ -54,7 +55,8 @@ __device__ inline int block_exclusive_scan(int v, int32_t* sh_wave, int& total)
 }  // namespace
 
 __global__ void paged_init_kernel(int R, int N, int M, int Q, int P, int len0, int32_t* __restrict__ table,
-                                  int32_t* __restrict__ refcnt, int32_t* __restrict__ counters)
+                                  int32_t* __restrict__ refcnt, int32_t* __restrict__ counters,
+                                  int32_t* __restrict__ arrive)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int ncol = (len0 + P - 1) / P;
@@ -65,33 +67,96 @@ __global__ void paged_init_kernel(int R, int N, int M, int Q, int P, int len0, i
     }
     if (i < (int64_t)(R / N) * Q) refcnt[i] = (int)(i % Q) < ncol * N ? 1 : 0;
     if (i < 8) counters[i] = 0;                        // pair counters of the two phases, failures, phase, ticket
+    if (i < R / N) arrive[i] = 0;
 }
 
-// Reorder: table[k, j] = old table[anc[k], j].  Old row a's page for column j gains copies(a) - 1 references,
-// copies(a) being the number of rows that continue a; a page whose count reaches 0 is free from then on.
-// The permutation acts along the rows and every column is permuted on its own, so one workgroup takes all N rows of
-// `cols` columns of one prompt: it reads them into LDS, then writes them back permuted -- no other workgroup
-// touches these entries, so no copy of the old table is needed.  Grid: prompts x column chunks; N * cols <=
-// kEntriesPerBlock.
-__global__ __launch_bounds__(kPagedThreads) void paged_reindex_kernel(
-    const int32_t* __restrict__ anc, const int32_t* __restrict__ resampled, int N, int M, int Q, int ncol, int cols, int chunks,
-    int32_t* __restrict__ table, int32_t* __restrict__ refcnt)
+// The reorder in one launch.  Two kinds of workgroup, told apart by blockIdx:
+//
+// state workgroups (hb per prompt): token history (first hist_vecs 16-byte vectors of a row), cumulative log p and
+//   termination flags follow their ancestors exactly as in the dense reorder -- a moved row receives its ancestor's
+//   live history in its own inactive buffer, then its parity flips.  Every workgroup of a prompt first reads the
+//   prompt's ancestors, parities, sums and flags, copies its share of the history vectors and takes a ticket; the one
+//   with the last ticket writes sums, flags and parities (nobody reads them any more) and clears the ticket counter.
+//
+// table workgroups: table[k, j] = old table[anc[k], j].  Old row a's page for column j gains copies(a) - 1
+//   references, copies(a) being the number of rows that continue a; a page whose count reaches 0 is free from then on.
+//   The permutation acts along the rows and every column is permuted on its own, so one workgroup takes all N rows of
+//   `cols` columns of one prompt: it reads them into LDS, then writes them back permuted -- no other workgroup touches
+//   these entries, so no copy of the old table is needed.  N * cols <= kEntriesPerBlock.
+__global__ __launch_bounds__(kPagedThreads) void paged_reorder_kernel(
+    const int32_t* __restrict__ anc, const int32_t* __restrict__ resampled, int B, int N,
+    int hb, int hist_vecs, long long hist_row_bytes, int32_t* const* __restrict__ histAB, double* __restrict__ cumlogp,
+    int32_t* __restrict__ done, int32_t* __restrict__ parity, int32_t* __restrict__ bad_anc, int32_t* __restrict__ arrive,
+    int M, int Q, int ncol, int cols, int chunks, int32_t* __restrict__ table, int32_t* __restrict__ refcnt)
 {
     __shared__ int32_t sh_anc[SMC_MAX_PARTICLES];
-    __shared__ int32_t sh_copies[SMC_MAX_PARTICLES];
-    __shared__ int32_t sh_old[kEntriesPerBlock];
-    const int b = blockIdx.x / chunks, tid = threadIdx.x;
+    __shared__ int32_t sh_aux[SMC_MAX_PARTICLES];      // table: copies of each ancestor; state: parity of each row
+    __shared__ int32_t sh_old[kEntriesPerBlock];       // table: the old entries; state: termination flags
+    __shared__ double sh_cum[SMC_MAX_PARTICLES];
+    __shared__ int sh_last;
+    const int tid = threadIdx.x;
+    const int n_state = B * hb;
+    if ((int)blockIdx.x < n_state) {
+        const int b = blockIdx.x / hb, part = blockIdx.x % hb;
+        if (!resampled[b]) return;
+        const int row0 = b * N;
+        int bad = 0;
+        for (int k = tid; k < N; k += kPagedThreads) {
+            int a = anc[row0 + k] - row0;
+            if (a < 0 || a >= N) { a = -1; ++bad; }        // outside the prompt: the row is left untouched
+            if (a == k) a = -1;                            // its own ancestor: nothing to move
+            sh_anc[k] = a;
+            sh_aux[k] = parity[row0 + k];
+            sh_cum[k] = cumlogp[row0 + k];
+            sh_old[k] = done[row0 + k];
+        }
+        if (part == 0 && bad) atomicAdd(bad_anc, bad);
+        __syncthreads();
+        if (hist_vecs > 0) {
+            const char* hA = (const char*)histAB[0];
+            const char* hB = (const char*)histAB[1];
+            const int per = (hist_vecs + hb - 1) / hb;
+            const int lo = part * per, hi = min(hist_vecs, lo + per);
+            for (int k = 0; k < N; ++k) {
+                const int a = sh_anc[k];
+                if (a < 0) continue;
+                const char* src = (sh_aux[a] ? hB : hA) + (long long)(row0 + a) * hist_row_bytes;      // live
+                char* dst = (char*)(sh_aux[k] ? hA : hB) + (long long)(row0 + k) * hist_row_bytes;     // inactive
+                for (int v = lo + tid; v < hi; v += kPagedThreads) *(vec16*)(dst + (long long)v * 16) = *(const vec16*)(src + (long long)v * 16);
+            }
+        }
+        __syncthreads();
+        if (tid == 0) {
+            __threadfence();                                   // this workgroup's reads precede its ticket
+            sh_last = atomicAdd(&arrive[b], 1) == hb - 1;
+        }
+        __syncthreads();
+        if (sh_last) {
+            for (int k = tid; k < N; k += kPagedThreads) {
+                const int a = sh_anc[k];
+                if (a >= 0) {
+                    cumlogp[row0 + k] = sh_cum[a];
+                    done[row0 + k] = sh_old[a];
+                    parity[row0 + k] = sh_aux[k] ^ 1;
+                }
+            }
+            if (tid == 0) arrive[b] = 0;
+        }
+        return;
+    }
+    const int bid = blockIdx.x - n_state;
+    const int b = bid / chunks;
     if (!resampled[b]) return;
     const int row0 = b * N, page0 = b * Q;
-    for (int k = tid; k < N; k += kPagedThreads) sh_copies[k] = 0;
+    for (int k = tid; k < N; k += kPagedThreads) sh_aux[k] = 0;
     __syncthreads();
     for (int k = tid; k < N; k += kPagedThreads) {
         int a = anc[row0 + k] - row0;
         if (a < 0 || a >= N) a = k;                    // outside the prompt: the row keeps its own pages
         sh_anc[k] = a;
-        atomicAdd(&sh_copies[a], 1);
+        atomicAdd(&sh_aux[a], 1);
     }
-    const int j0 = (blockIdx.x % chunks) * cols;
+    const int j0 = (bid % chunks) * cols;
     const int nc = min(cols, ncol - j0);               // columns of this workgroup
     const int n = N * nc;
     for (int e = tid; e < n; e += kPagedThreads) {
@@ -103,7 +168,7 @@ __global__ __launch_bounds__(kPagedThreads) void paged_reindex_kernel(
         const int k = e / nc, c = e % nc;
         const int a = sh_anc[k];
         if (a != k) table[(int64_t)(row0 + k) * M + j0 + c] = sh_old[a * nc + c];
-        const int gained = sh_copies[k] - 1;
+        const int gained = sh_aux[k] - 1;
         if (gained != 0) {
             const int p = sh_old[e];
             if (p >= page0 && p < page0 + Q) atomicAdd(&refcnt[p], gained);
@@ -268,6 +333,7 @@ size_t paged_layout(const smc_config* c, const PagedDims& d, char* base, PagedKV
     q = take(R * 4); if (p) p->cow_src = (int32_t*)q;
     q = take(R * 4); if (p) p->cow_dst = (int32_t*)q;
     q = take(8 * 4); if (p) p->counters = (int32_t*)q;
+    q = take((size_t)c->B * 4); if (p) p->arrive = (int32_t*)q;
     q = take((size_t)c->kv_tensors * sizeof(void*)); if (p) p->pools = (void**)q;
     return off;
 }
@@ -312,7 +378,7 @@ smc_status smc_paged_bind(smc_ctx* ctx, void* const* h_pools, int32_t page_len, 
     try { ctx->h_pools.assign(h_pools, h_pools + ctx->cfg.kv_tensors); } catch (...) { return SMC_E_STATE; }
     const size_t n = d.n_table > d.n_pages ? d.n_table : d.n_pages;
     hipLaunchKernelGGL(paged_init_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, ctx->stream, ctx->R, ctx->cfg.N,
-                       d.M, d.Q, d.P, len0, p.table, p.refcnt, p.counters);
+                       d.M, d.Q, d.P, len0, p.table, p.refcnt, p.counters, p.arrive);
     if (hipGetLastError() != hipSuccess) return SMC_E_HIP;
     p.bound = 1;
     return SMC_OK;
@@ -348,19 +414,32 @@ smc_status smc_paged_reindex(smc_ctx* ctx, const int32_t* d_anc, const int32_t* 
     PagedKV& p = ctx->paged;
     if (!p.bound) return SMC_E_STATE;
     if (t < 0 || t > ctx->cfg.T_max) return SMC_E_RANGE;
-    // token history, cumulative log p and termination flags follow their ancestors as in the dense reorder
-    if (launch_reindex(ctx, d_anc, d_resampled, 0, t) != hipSuccess) return SMC_E_HIP;
-    const int ncol = (p.len + p.P - 1) / p.P;
-    if (ncol > 0) {
-        const int N = ctx->cfg.N;
-        const int cols = kEntriesPerBlock / N < ncol ? kEntriesPerBlock / N : ncol;      // >= 1: N <= SMC_MAX_PARTICLES
-        const int chunks = (ncol + cols - 1) / cols;
-        const dim3 grid((unsigned)((int64_t)chunks * ctx->cfg.B));
-        hipLaunchKernelGGL(paged_reindex_kernel, grid, dim3(kPagedThreads), 0, ctx->stream, d_anc, d_resampled, N, p.M, p.Q,
-                           ncol, cols, chunks, p.table, p.refcnt);
-        if (hipGetLastError() != hipSuccess) return SMC_E_HIP;
+    const auto& cfg = ctx->cfg;
+    const int N = cfg.N;
+    // token history: whole 16-byte vectors of the first t columns, as in the dense reorder
+    int hist_vecs = 0;
+    if (ctx->hist_bound && t > 0) {
+        int64_t bytes = (((int64_t)t * 4) + 15) & ~15ll;
+        if (bytes > (int64_t)cfg.T_max * 4) bytes = (int64_t)cfg.T_max * 4;
+        hist_vecs = (int)(bytes / 16);
     }
-    return SMC_OK;
+    int hb = (int)(((int64_t)N * hist_vecs * 16 + 65535) / 65536);          // ~64 KiB of history per state workgroup
+    if (hb > 64) hb = 64;
+    if (hb > hist_vecs) hb = hist_vecs;
+    if (hb < 1) hb = 1;
+    const int ncol = (p.len + p.P - 1) / p.P;
+    int cols = 1, chunks = 0;
+    if (ncol > 0) {
+        cols = kEntriesPerBlock / N < ncol ? kEntriesPerBlock / N : ncol;   // >= 1: N <= SMC_MAX_PARTICLES
+        chunks = (ncol + cols - 1) / cols;
+    }
+    const int64_t blocks = (int64_t)cfg.B * hb + (int64_t)cfg.B * chunks;
+    if (blocks > 0x7FFFFFFFll) return SMC_E_SHAPE;
+    hipLaunchKernelGGL(paged_reorder_kernel, dim3((unsigned)blocks), dim3(kPagedThreads), 0, ctx->stream, d_anc, d_resampled,
+                       cfg.B, N, hb, hist_vecs, (long long)cfg.T_max * 4, (int32_t* const*)ctx->ws.histAB, ctx->ws.cumlogp,
+                       ctx->ws.done, ctx->ws.parity, &ctx->ws.plan->bad_anc, p.arrive, p.M, p.Q, ncol, cols, chunks, p.table,
+                       p.refcnt);
+    return hipGetLastError() == hipSuccess ? SMC_OK : SMC_E_HIP;
 }
 
 smc_status smc_paged_view(smc_ctx* ctx, const int32_t** d_table, const int32_t** d_refcnt, int32_t* pages_per_row,
