@@ -136,7 +136,10 @@ smc_status smc_set_ancestor_order(smc_ctx* ctx, int32_t order);
  * tensor, the first t columns of the history -- gathers cumulative log p and the termination flags the same way,
  * then flips parity[k].  Rows that are their own ancestor move no bytes.  d_anc entries of a resampled prompt must
  * lie inside that prompt's row range (others are ignored and the row left as it is).  Each distinct ancestor row is
- * read once and written to all of its moved descendants. */
+ * read once and written to all of its moved descendants.  With eos_id >= 0 the KV rows of a terminated ancestor
+ * are not copied (App. D: a terminated particle is a no-op, its cache is never read again): its descendants
+ * receive its history, sum and flag, their parity flips like any moved row's, and the content of their KV rows is
+ * unspecified from then on. */
 smc_status smc_kv_reindex(smc_ctx* ctx, const int32_t* d_anc, const int32_t* d_resampled, int32_t valid_len,
                           int32_t t);
 

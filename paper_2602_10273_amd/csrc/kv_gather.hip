@@ -9,8 +9,8 @@
 // Moved rows that share an ancestor form a group: the ancestor's bytes are read ONCE into registers and stored to
 // every member, so a reindex moves (distinct ancestors of moved rows + moved rows) rows, the least the method allows.
 //
-//   plan_kernel    : one wave per prompt.  Builds the groups (ancestor row and which of its buffers is live, bit set
-//                    of moved descendants), gathers cumulative log p and termination flags the same way, and flips
+//   plan_kernel    : one wave per prompt.  Builds the groups (ancestor row, which of its buffers is live and whether
+//                    it has terminated, bit set of moved descendants), gathers cumulative log p and termination flags the same way, and flips
 //                    the parity of the moved rows -- so after it, a moved row's parity names the buffer to WRITE.
 //   gather_kernel  : persistent grid-stride loop over (group, tensor, head chunk, slab of 8..64 KiB) for the KV
 //                    tensors, followed in the same launch by the token-history rows.
@@ -74,7 +74,9 @@ __device__ void plan_prompt(const int32_t* __restrict__ anc, int N, int mask_wor
             const int g = sh_base + placed + mask_rank(mk);
             grp_src[g] = row0 + a;
             grp_base[g] = row0;
-            grp_srcpar[g] = parity[row0 + a];                      // the ancestor's live buffer, before any flip
+            // bit 0: the ancestor's live buffer, before any flip; bit 1: the ancestor has terminated -- its cache is
+            // never read again (App. D: the absorbing state is a no-op), so its KV rows are not copied
+            grp_srcpar[g] = parity[row0 + a] | (sh_done[a] ? 2 : 0);
             for (int w = 0; w < mask_words; ++w) grp_mask[(int64_t)g * mask_words + w] = 0ull;
             sh_group[a] = g;
         }
@@ -157,11 +159,13 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(
         const int chunk = (int)(rem / ge.slabs_per_chunk);
         const int slab = (int)(rem - (int64_t)chunk * ge.slabs_per_chunk);
 
+        const int src_state = grp_srcpar[g];
+        if (is_kv && (src_state & 2)) continue;                     // terminated ancestor: only its history moves
         const int src_row = grp_src[g];
         const int row0 = grp_base[g];
         char* const baseA = (char*)ge.bufA[tensor];
         char* const baseB = (char*)ge.bufB[tensor];
-        const char* src = grp_srcpar[g] ? baseB : baseA;            // the ancestor's live buffer
+        const char* src = (src_state & 1) ? baseB : baseA;          // the ancestor's live buffer
         const int64_t off0 = (int64_t)chunk * ge.chunk_stride + (int64_t)slab * kSlabBytes;
         const int64_t left = ge.copy_bytes - (int64_t)slab * kSlabBytes;    // bytes of this chunk from the slab start
 

@@ -258,6 +258,44 @@ def test_reindex_bytes_exact(B, N, H, S, D, valid):
     s.close()
 
 
+def test_reindex_leaves_the_cache_of_terminated_ancestors_alone():
+    """A terminated particle is a no-op (App. D): descendants of a terminated ancestor get its history, sum, flag and
+    a flipped parity like any moved row, but no KV bytes are read or written for them; everything else follows the
+    oracle's gather."""
+    B, N, H, S, D = 3, 6, 2, 10, 16
+    R = B * N
+    rng = np.random.default_rng(11)
+    kv = [rng.integers(0, 65536, (R, H, S, D), dtype=np.uint16) for _ in range(2)]
+    s = Session(B, N, 64, 8, "f32", 0.5, 0, kv=kv, eos_id=3)
+    o = orc.OracleSMC(B, N, 64, 8, 0.5, 0, "f32", kv=[k.copy() for k in kv], eos_id=3)
+    o.hist[:] = rng.integers(0, 64, (R, 8)); o.cumlogp[:] = -rng.random(R)
+    s.histA.copy_(torch.as_tensor(o.hist)); s.set_state(None, o.cumlogp)
+    for it in range(4):
+        done = (rng.random(R) < 0.4).astype(np.int32)
+        o.done[:] = done; s.set_done(done)
+        anc = np.concatenate([b * N + np.sort(rng.integers(0, N, N)) for b in range(B)]).astype(np.int32)
+        flag = np.array([1, 1, it % 2], np.int32)
+        _, _, par = s.state()
+        a_before = [t.view(torch.int16).cpu().numpy().copy() for t in s.kvA]
+        b_before = [t.view(torch.int16).cpu().numpy().copy() for t in s.kvB]
+        o.kv = [s.live_kv(i) for i in range(2)]                  # the oracle starts from what is live on the device
+        s.reindex(S, 5, torch.as_tensor(anc).cuda(), torch.as_tensor(flag).cuda())
+        o.reindex(anc, flag, S, 5)
+        moved = (anc != np.arange(R)) & (np.repeat(flag, N) != 0)
+        dead = moved & (done[anc] != 0)                          # rows that continue a terminated ancestor
+        assert dead.any() and (moved & ~dead).any()
+        _, cum_g, par2 = s.state()
+        assert np.array_equal(par2, par ^ moved.astype(np.int32))
+        assert np.array_equal(cum_g, o.cumlogp) and np.array_equal(s.done(), o.done)
+        assert np.array_equal(s.live_hist()[:, :5], o.hist[:, :5])
+        for ten in range(2):
+            got = s.live_kv(ten)
+            assert np.array_equal(got[~dead], o.kv[ten][~dead])              # every other row as the gather defines
+            a_now = s.kvA[ten].view(torch.int16).cpu().numpy(); b_now = s.kvB[ten].view(torch.int16).cpu().numpy()
+            assert np.array_equal(a_now[dead], a_before[ten][dead]) and np.array_equal(b_now[dead], b_before[ten][dead])
+    s.close()
+
+
 def test_reindex_rejects_foreign_ancestors_without_touching_memory():
     B, N = 2, 4
     w = synth.scaled(synth.WORKLOADS["cfg2"], B=B, N=N, H=1, S=4, D=8, layers=1)
