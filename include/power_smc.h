@@ -171,7 +171,8 @@ smc_status smc_get_diag(smc_ctx* ctx, double* h_delta, double* h_logZ1, double* 
                         double* h_gap, uint64_t* h_counters);
 
 /* Tuning knobs of the vocabulary pass (defaults chosen at smc_init): n_split = workgroups a row is split over
- * (1..32; 0 = automatic); dense = 1 scores every entry instead of only those that can win (dense = 0, the default);
+ * (1..32; 0 = automatic); dense = 1 scores every entry instead of only those that can win (dense = 0, the default,
+ * which itself scores whole 16-byte vectors in place where most of their entries can still win);
  * wg_waves = waves per workgroup, 4 or 16 (0 = automatic).  Every setting returns the same tokens. */
 smc_status smc_set_tuning(smc_ctx* ctx, int32_t n_split, int32_t dense, int32_t wg_waves);
 
