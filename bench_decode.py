@@ -47,6 +47,7 @@ def parse():
     ap.add_argument("--page", type=int, default=16)
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--modes", default="plain,dense,paged")
+    ap.add_argument("--in-place", action="store_true", help="ancestor vectors permuted so that survivors keep their rows")
     return ap.parse_args()
 
 
@@ -120,6 +121,8 @@ def run_mode(mode, args, model, torch, smc, Session):
     T_max = (W + K + 3) // 4 * 4
     s = Session(B, N, model.V, T_max, "bf16", args.kappa if mode != "plain" else 0.0, args.seed,
                 kv_geom=(2 * model.L, model.Hkv, S, model.D), page_len=P if paged else 0, len0=start if paged else 0)
+    if args.in_place and mode != "plain":
+        smc.smc_set_ancestor_order(s.ctx, 1)
     g = torch.Generator(device="cuda"); g.manual_seed(args.seed + 1)
     for t in (s.pools if paged else s.kvA):                       # the cache as start positions of earlier decoding left it
         t.normal_(generator=g)
@@ -184,7 +187,8 @@ def main():
            "unit": "ms per step", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "data": "synthetic (random-init weights)",
            "config": {"shape": args.shape, "parameters": model.n_params, "prompts": args.prompts, "particles": args.particles,
                       "rows": args.prompts * args.particles, "positions": args.positions, "alpha": args.alpha,
-                      "kappa": args.kappa, "page": args.page}}
+                      "kappa": args.kappa, "page": args.page,
+                      "ancestor_order": "survivors-in-place" if args.in_place else "as-drawn"}}
     for mode in args.modes.split(","):
         ms, frac, start = run_mode(mode, args, model, torch, smc, Session)
         out[f"{mode}_ms_per_step"] = ms
