@@ -166,8 +166,10 @@ __device__ __forceinline__ void block_epilogue(float beta, float m_wave, float M
         const float wM1 = hw ? red_f[lane][0] : -INFINITY, wMb = hw ? red_f[lane][2] : -INFINITY;
         const float gM1 = wave_max_f32(wM1), gMb = wave_max_f32(wMb);
         const float gm = wave_max_f32(hw ? red_f[lane][4] : -3.0e38f);
-        const float t1 = wave_sum_f32(hw ? red_f[lane][1] * fast_exp2(wM1 - gM1) : 0.f);
-        const float tb = wave_sum_f32(hw ? red_f[lane][3] * fast_exp2(wMb - gMb) : 0.f);
+        // a wave that saw nothing but masked (-inf) entries has reference -inf and sum 0; when every wave of the
+        // slice is like that the difference of the references is not a number, hence the explicit zero
+        const float t1 = wave_sum_f32(hw && wM1 > -INFINITY ? red_f[lane][1] * fast_exp2(wM1 - gM1) : 0.f);
+        const float tb = wave_sum_f32(hw && wMb > -INFINITY ? red_f[lane][3] * fast_exp2(wMb - gMb) : 0.f);
         uint32_t nsc = hw ? red_n[lane][0] : 0u, ndr = hw ? red_n[lane][1] : 0u;
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) { nsc += __shfl_xor(nsc, o); ndr += __shfl_xor(ndr, o); }

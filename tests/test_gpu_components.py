@@ -105,6 +105,29 @@ def test_step_flat_proposals_are_scored_in_place(dtype):
             assert r1["counters"][1] > 0.3 * r1["counters"][3]      # a large share of the entries was scored
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_step_with_masked_vocabulary_entries(dtype):
+    """Logit masks (-inf entries: padded vocabulary ids, constrained decoding): a masked entry has probability 0 under
+    both p and q, is never drawn, and leaves the sums of the others exact -- from a third of the vocabulary masked
+    to all but three entries."""
+    w = synth.scaled(synth.WORKLOADS["cfg2"], B=2, N=4, V=152064, dtype=dtype)
+    x = synth.logits_numpy(synth.scaled(w, dtype="f32"), 1, 5)
+    rng = np.random.default_rng(5)
+    keep = np.ones((w.R, w.V), bool)
+    keep[0:4] = rng.random((4, w.V)) > 0.33
+    keep[4:6] = rng.random((2, w.V)) > 0.999
+    keep[6:8] = False
+    for r in (6, 7):
+        keep[r, rng.choice(w.V, 3, replace=False)] = True
+    keep[7, -1] = True                                        # the very last entry of a row
+    x[~keep] = -np.inf
+    xs = synth.f32_to_bf16_bits(x) if dtype == "bf16" else x
+    for alpha in (4.0, 1.5):
+        for ww in (4, 16):
+            res = check_step(w, seed=5, t=2, alpha_t=alpha, alpha_prev=alpha, tau=-1.0, logits=xs, wg_waves=ww)
+            assert np.all(keep[np.arange(w.R), res["tokens"]])
+
+
 def test_step_degenerate_rows():
     V = 4096 + 24
     w = synth.scaled(synth.WORKLOADS["cfg4"], B=1, N=6, V=V)
