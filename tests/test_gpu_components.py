@@ -79,7 +79,9 @@ def test_step_matches_oracle_full_vocab(name, V):
 
 
 @pytest.mark.parametrize("alpha_t,alpha_prev,tau", [(1.0, 1.0, -1.0), (1.0234375, 1.0, -1.0), (2.5, 2.4765625, -1.0),
-                                                     (4.0, 4.0, 0.5), (4.0, 3.0, 1.0), (6.0, 6.0, -1.0), (3.0, 3.0, 0.3)])
+                                                     (4.0, 4.0, 0.5), (4.0, 3.0, 1.0), (6.0, 6.0, -1.0), (3.0, 3.0, 0.3),
+                                                     (2.0, 2.0, 2.5), (10.0, 10.0, -1.0), (8.0, 8.0, -1.0), (7.0, 7.0, -1.0),
+                                                     (12.0, 12.0, 0.02)])
 def test_step_schedules_and_temperatures(alpha_t, alpha_prev, tau):
     """Bridging stages (non-integer exponents, boundary term) and proposals other than tau = 1/alpha."""
     for name in ("cfg4", "cfg2"):
