@@ -54,7 +54,7 @@ def check_step(w, seed, t, alpha_t, alpha_prev, tau, n_split=0, dense=0, logits=
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
-@pytest.mark.parametrize("V", [8, 257, 5000, 40000])
+@pytest.mark.parametrize("V", [1, 2, 3, 8, 9, 257, 5000, 40000])
 def test_step_matches_oracle_small(dtype, V):
     w = synth.scaled(synth.WORKLOADS["cfg2"], B=3, N=4, V=V, dtype=dtype)
     pad = (-V) % (8 if dtype == "bf16" else 4)
