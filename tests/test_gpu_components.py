@@ -21,7 +21,8 @@ def check_step(w, seed, t, alpha_t, alpha_prev, tau, n_split=0, dense=0, logits=
     from paper_2602_10273_amd import binding as smc
     x = synth.logits_numpy(w, t, seed) if logits is None else logits
     if stride_pad:
-        pad = np.zeros((w.R, stride_pad), x.dtype)
+        # NaN (bf16 bits 0x7FC0 / float NaN) behind every row: nothing past V may be read
+        pad = np.full((w.R, stride_pad), 0x7FC0 if x.dtype == np.uint16 else np.nan, x.dtype)
         xs = np.concatenate([x, pad], axis=1)
     else:
         xs = x
