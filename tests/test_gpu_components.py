@@ -150,7 +150,7 @@ def test_ess_and_resample_match_oracle():
     from paper_2602_10273_amd import binding as smc
     rng = np.random.default_rng(0)
     for (B, N, kappa) in [(1, 4, 0.5), (16, 8, 0.5), (8, 16, 0.5), (64, 32, 0.5), (4, 64, 0.7), (3, 100, 0.9),
-                          (2, 1024, 0.6), (5, 1, 0.5)]:
+                          (2, 1024, 0.6), (5, 1, 0.5), (6, 8, 0.0), (6, 8, 1.0), (3, 33, 1.0), (1, 1, 1.0)]:
         s = Session(B, N, 64, 8, "f32", kappa, seed=123, with_hist=False)
         for scale in (0.1, 1.0, 5.0, 40.0):
             logW = rng.standard_normal(B * N) * scale
