@@ -117,6 +117,29 @@ def test_paged_argument_errors_and_foreign_ancestors():
     s.close(); s2.close()
 
 
+def test_paged_reindex_before_any_append_moves_only_the_state():
+    """No position appended yet: the table has no column in use; histories, sums and parities still follow."""
+    B, N, T = 3, 5, 8
+    R = B * N
+    rng = np.random.default_rng(4)
+    s = Session(B, N, 64, T, "f32", 0.5, 0, kv_geom=(2, 1, 12, 8), page_len=4, len0=0)
+    o = orc.OracleSMC(B, N, 64, T, 0.5, 0, "f32")
+    o.hist[:] = rng.integers(0, 64, (R, T)); o.cumlogp[:] = -rng.random(R)
+    s.histA.copy_(torch.as_tensor(o.hist)); s.set_state(None, o.cumlogp)
+    for it in range(3):
+        anc = np.concatenate([b * N + rng.integers(0, N, N) for b in range(B)]).astype(np.int32)
+        flag = np.array([1, it % 2, 1], np.int32)
+        t = 3 + 2 * it
+        o.hist = s.live_hist().copy()                          # columns beyond an earlier t are unspecified after a copy
+        s.paged_reindex(t, torch.as_tensor(anc).cuda(), torch.as_tensor(flag).cuda())
+        o.reindex(anc, flag, 0, t)
+        _, cum, _ = s.state()
+        assert np.array_equal(cum, o.cumlogp) and np.array_equal(s.live_hist()[:, :t], o.hist[:, :t])
+        table, refcnt = s.paged_state()
+        assert np.all(table == -1) and np.all(refcnt == 0)
+    s.close()
+
+
 def test_paged_lockstep_with_the_sampler():
     """The whole step with a paged cache: histories, weights and the logical cache follow the oracle's dense run."""
     w = synth.scaled(synth.WORKLOADS["cfg2"], B=8, N=8, V=4104, layers=1, H=2, S=40, D=64)
