@@ -140,6 +140,30 @@ def test_paged_reindex_before_any_append_moves_only_the_state():
     s.close()
 
 
+@pytest.mark.parametrize("B,N,T", [(3, 64, 2048), (2, 100, 4096), (1, 1024, 512), (5, 8, 4096)])
+def test_paged_reorder_with_long_histories(B, N, T):
+    """Histories long enough that several workgroups share a prompt's copy (the last one to finish flips the
+    parities): repeated calls, unsorted ancestors, every prefix length."""
+    R = B * N
+    rng = np.random.default_rng(B * 7 + N)
+    s = Session(B, N, 64, T, "f32", 0.5, 0, kv_geom=(2, 1, 8, 8), page_len=4, len0=5)
+    o = orc.OracleSMC(B, N, 64, T, 0.5, 0, "f32", eos_id=-1)
+    o.hist[:] = rng.integers(0, 64, (R, T)); o.cumlogp[:] = -rng.random(R)
+    s.histA.copy_(torch.as_tensor(o.hist)); s.set_state(None, o.cumlogp)
+    par = np.zeros(R, np.int32)
+    for t in (T, T - 3, T // 2 + 1, 7, T):
+        anc = np.concatenate([b * N + rng.integers(0, N, N) for b in range(B)]).astype(np.int32)
+        flag = (rng.random(B) < 0.8).astype(np.int32); flag[0] = 1
+        o.hist = s.live_hist().copy()
+        s.paged_reindex(t, torch.as_tensor(anc).cuda(), torch.as_tensor(flag).cuda())
+        o.reindex(anc, flag, 0, t)
+        _, cum, par2 = s.state()
+        moved = (anc != np.arange(R)) & (np.repeat(flag, N) != 0)
+        assert np.array_equal(par2, par ^ moved.astype(np.int32)); par = par2
+        assert np.array_equal(cum, o.cumlogp) and np.array_equal(s.live_hist()[:, :t], o.hist[:, :t]), t
+    s.close()
+
+
 def test_paged_lockstep_with_the_sampler():
     """The whole step with a paged cache: histories, weights and the logical cache follow the oracle's dense run."""
     w = synth.scaled(synth.WORKLOADS["cfg2"], B=8, N=8, V=4104, layers=1, H=2, S=40, D=64)
