@@ -64,6 +64,17 @@ def test_step_matches_oracle_small(dtype, V):
             check_step(w, seed=5, t=3, alpha_t=4.0, alpha_prev=4.0, tau=-1.0, dense=mode, stride_pad=pad, wg_waves=ww)
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_step_with_a_million_entry_vocabulary(dtype):
+    """Wider than any current model: 1 048 583 entries (not a multiple of the vector width), 32 slices per row."""
+    V = 1048583
+    w = synth.scaled(synth.WORKLOADS["cfg2"], B=1, N=3, V=V, dtype=dtype)
+    pad = (-V) % (8 if dtype == "bf16" else 4)
+    r1 = check_step(w, seed=8, t=1, alpha_t=4.0, alpha_prev=4.0, tau=-1.0, stride_pad=pad)
+    r2 = check_step(w, seed=8, t=1, alpha_t=4.0, alpha_prev=4.0, tau=-1.0, stride_pad=pad, wg_waves=4, n_split=1)
+    assert np.array_equal(r1["tokens"], r2["tokens"])
+
+
 @pytest.mark.parametrize("name,V", [("cfg2", 152064), ("cfg3", 128256), ("cfg4", 152064), ("cfg5", 152064)])
 def test_step_matches_oracle_full_vocab(name, V):
     """Full vocabulary width of every workload on a reduced number of rows; lazy and dense scoring agree."""
