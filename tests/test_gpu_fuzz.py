@@ -15,7 +15,7 @@ TOL = 1e-4
 
 
 def _random_logits(rng, R, V, dtype):
-    kind = rng.integers(0, 6)
+    kind = rng.integers(0, 8)
     scale = float(rng.uniform(0.3, 6.0))
     if kind == 0:
         x = rng.standard_normal((R, V)) * scale
@@ -33,13 +33,20 @@ def _random_logits(rng, R, V, dtype):
         x = rng.standard_normal((R, V)) * scale + rng.uniform(-500, 500)
         x[rng.random((R, V)) < 0.3] = -np.inf
         x[:, rng.integers(0, V)] = rng.uniform(-2, 2)         # at least one finite entry per row
-    else:                                                     # heavy ties: few distinct values
+    elif kind == 5:                                           # heavy ties: few distinct values
         x = rng.integers(-3, 4, (R, V)).astype(np.float64) * scale
+    elif kind == 6:                                           # all but a handful of entries masked: whole slices are empty
+        x = np.full((R, V), -np.inf)
+        for r in range(R):
+            idx = rng.choice(V, size=min(V, int(rng.integers(1, 6))), replace=False)
+            x[r, idx] = rng.standard_normal(idx.size) * scale
+    else:                                                     # logits that barely differ: every entry can win
+        x = rng.standard_normal((R, V)) * rng.uniform(0.01, 0.2) + rng.uniform(-50, 50)
     x = np.ascontiguousarray(x, np.float32)
     return synth.f32_to_bf16_bits(x) if dtype == "bf16" else x
 
 
-@pytest.mark.parametrize("case", range(48))
+@pytest.mark.parametrize("case", range(72))
 def test_vocab_pass_random_case(case):
     rng = np.random.default_rng([2602, case])
     dtype = "bf16" if rng.random() < 0.5 else "f32"
