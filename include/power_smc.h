@@ -52,7 +52,7 @@ typedef enum {
 
 typedef enum { SMC_BF16 = 0, SMC_F32 = 1 } smc_dtype;
 
-enum { SMC_MAX_PARTICLES = 1024, SMC_MAX_KV_TENSORS = 512 };
+enum { SMC_MAX_PARTICLES = 1024, SMC_MAX_KV_TENSORS = 512, SMC_NOALLOC_MAX_ROWS = 4096 };
 
 typedef struct {
     int32_t B;             /* prompts                                  >= 1 */
@@ -105,6 +105,25 @@ smc_status smc_kv_parity(smc_ctx* ctx, const int32_t** d_parity);
  * reweight touches its weight; a particle that draws eos_id becomes terminated. */
 smc_status smc_step(smc_ctx* ctx, const void* d_logits, int64_t row_stride_elems, int32_t t, double alpha_t,
                     double alpha_prev, double tau_t, int32_t* d_tokens_out);
+
+/* smc_step for callers that cannot allocate device memory: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  The same a0 + a1 + a2, the same kernels, but no context and no workspace: the
+ * scratch of the vocabulary pass (one 48-byte record per row and slice, per-row diagnostics) lives in a device array
+ * inside the library (about 6.5 MB, held by every GPU the library runs on until the process ends), and the state is
+ * the caller's:
+ *   cfg: as for smc_init (B, N, V, logits_dtype, eos_id, seed are used); B*N <= SMC_NOALLOC_MAX_ROWS, else SMC_E_SHAPE.
+ *   hip_stream: the stream to enqueue on (NULL = default stream).
+ *   d_logits, row_stride_elems, t (>= 1), alpha_t, alpha_prev, tau_t, d_tokens_out: as for smc_step.
+ *   d_logW_inout, d_cumlogp_inout: device double [R], log W~ and cumulative log p, read and updated in place.
+ *   d_done_inout: device int32 [R] termination flags, read and updated; required when eos_id >= 0, else ignored.
+ * No token history is written.  Calls nothing that allocates (no hipMalloc / hipFree, no workspace); argument errors
+ * are detected on the host before anything is enqueued.  Every call on one GPU uses that GPU's one scratch array,
+ * which keeps the previous call's contents (nothing in it has to start at zero: each call writes what it reads):
+ * calls that overlap in time on one GPU -- other streams, other threads -- race on it and must be serialised by
+ * the caller. */
+smc_status smc_step_noalloc(const smc_config* cfg, void* hip_stream, const void* d_logits, int64_t row_stride_elems,
+                            int32_t t, double alpha_t, double alpha_prev, double tau_t, double* d_logW_inout,
+                            double* d_cumlogp_inout, int32_t* d_done_inout, int32_t* d_tokens_out);
 
 /* a3 on the context's weights: d_ess_out double [B]; d_lognormw_out double [R] = log W (nullable). */
 smc_status smc_ess(smc_ctx* ctx, double* d_ess_out, double* d_lognormw_out);

@@ -19,7 +19,7 @@ EXPORTS = ["smc_workspace_bytes", "smc_init", "smc_destroy", "smc_kv_bind", "smc
            "smc_set_tuning", "smc_set_resampler", "smc_set_ancestor_order", "smc_set_gather_tuning", "smc_profile_enable", "smc_profile_read", "smc_status_str",
            "smc_paged_workspace_bytes", "smc_paged_pool_bytes", "smc_paged_bind", "smc_paged_prepare_append",
            "smc_paged_reindex", "smc_paged_view", "smc_paged_check", "smc_hbm_probe",
-           "smc_attn_workspace_bytes", "smc_attn_decode", "smc_kv_parity", "smc_kv_append"]
+           "smc_attn_workspace_bytes", "smc_attn_decode", "smc_kv_parity", "smc_kv_append", "smc_step_noalloc"]
 
 
 class smc_config(C.Structure):
@@ -52,6 +52,7 @@ def lib():
         L.smc_destroy.argtypes = [vp]
         L.smc_kv_bind.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), vp, vp]
         L.smc_step.argtypes = [vp, vp, i64, i32, f64, f64, f64, vp]
+        L.smc_step_noalloc.argtypes = [C.POINTER(smc_config), vp, vp, i64, i32, f64, f64, f64, vp, vp, vp, vp]
         L.smc_ess.argtypes = [vp, vp, vp]
         L.smc_resample.argtypes = [vp, i32, vp, vp, vp]
         L.smc_kv_reindex.argtypes = [vp, vp, vp, i32, i32]
@@ -142,6 +143,13 @@ def smc_kv_bind(ctx, bufA, bufB, d_histA=None, d_histB=None):
 def smc_step(ctx, d_logits, row_stride_elems, t, alpha_t, alpha_prev, tau_t, d_tokens_out):
     _check("smc_step", lib().smc_step(ctx, _ptr(d_logits), row_stride_elems, t, alpha_t, alpha_prev, tau_t,
                                       _ptr(d_tokens_out)))
+
+
+def smc_step_noalloc(cfg, hip_stream, d_logits, row_stride_elems, t, alpha_t, alpha_prev, tau_t, d_logW_inout,
+                     d_cumlogp_inout, d_done_inout, d_tokens_out):
+    _check("smc_step_noalloc", lib().smc_step_noalloc(C.byref(cfg), hip_stream, _ptr(d_logits), row_stride_elems, t, alpha_t,
+                                                      alpha_prev, tau_t, _ptr(d_logW_inout), _ptr(d_cumlogp_inout),
+                                                      _ptr(d_done_inout), _ptr(d_tokens_out)))
 
 
 def smc_ess(ctx, d_ess_out, d_lognormw_out=None):

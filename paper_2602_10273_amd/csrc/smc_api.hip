@@ -62,6 +62,12 @@ size_t layout(const smc_config* c, char* base, Workspace* w)
     return off;
 }
 
+}  // namespace
+
+namespace psmc {
+
+smc_status validate_config(const smc_config* c) { return check_config(c); }
+
 // Launch shape of the vocabulary pass.  Few rows: big workgroups (16 waves share their bound through LDS) and just
 // enough slices per row to put about one workgroup on each of the 256 CUs.  Many rows: 4-wave workgroups, one per row.
 void auto_shape(int R, int V, int dtype, int* wg_waves, int* n_split)
@@ -78,7 +84,7 @@ void auto_shape(int R, int V, int dtype, int* wg_waves, int* n_split)
     *n_split = s;
 }
 
-}  // namespace
+}  // namespace psmc
 
 extern "C" {
 

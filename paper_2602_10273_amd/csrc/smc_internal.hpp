@@ -126,6 +126,12 @@ struct ScopedKernelTimer {
     ~ScopedKernelTimer() { if (stop) (void)hipEventRecord(stop, c->stream); }
 };
 
+// the checks smc_init applies to a configuration
+smc_status validate_config(const smc_config* c);
+
+// default launch shape of the vocabulary pass for R rows of V entries: waves per workgroup and workgroups per row
+void auto_shape(int R, int V, int dtype, int* wg_waves, int* n_split);
+
 // launchers (each enqueues on ctx->stream; returns hipGetLastError())
 hipError_t launch_init_state(smc_ctx* c);
 hipError_t launch_vocab_pass(smc_ctx* c, const void* logits, int64_t row_stride, int t, double alpha_t,
