@@ -9,7 +9,13 @@ whenever the weights say so; how often is an observed quantity and is reported.
 Prints ONE JSON line.  `value` is particle-steps/s over the timed steps.  `roofline` describes the kernel that
 took the most time in a second, instrumented run of the same number of steps (HIP events recorded by the library
 on its own stream around each launch); `roofline_other` the other dominant kernel.  `cpu_baseline` times the CPU
-oracle on a bounded sample of the same workload.
+oracle on a bounded sample of the same workload, on all host cores and (in a child process) on one.
+
+The default workload is the largest configuration (cfg4: 2048 rows of fp32 logits, 2 x 120 GB of KV cache), timed
+in the regime it is defined for: the 128 steps of the exponent ramp run first, untimed, as a prologue (so the timed
+steps see the weights, sums and histories the ramp leaves behind), then alpha is held at 4, resampling fires
+whenever the accumulated weights say so, and the whole double-buffered cache is bound, so vocabulary pass,
+resampling and gather run in the same step.
 """
 import argparse
 import json
@@ -29,7 +35,10 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=0, help="timed steps (0: per-workload default)")
     ap.add_argument("--warmup", type=int, default=4)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--workload", default="cfg4", choices=["cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--no-prologue", action="store_true",
+                    help="skip the untimed steps through the workload's exponent ramp (the run then starts at t = 1)")
+    ap.add_argument("--cpu-single-leg", action="store_true", help=argparse.SUPPRESS)
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kv", action="store_true", help="vocabulary pass + weights only (no cache bound)")
@@ -46,33 +55,8 @@ def parse():
     return ap.parse_args()
 
 
-def cpu_baseline(w, seed, gpu_resample_frac):
-    """The oracle as it stands, on the host cores: a few full-width steps on all rows, plus the KV gather of one
-    prompt's rows scaled to the number of prompts that resample per step."""
-    import numpy as np
-    from oracle import reference as orc
-    from paper_2602_10273_amd import synth
-
-    threads = orc.threads()
-    o = orc.OracleSMC(w.B, w.N, w.V, 4096, w.kappa, seed, w.dtype)
-    n_buf = 2 if w.R * w.V > 1e8 else 3
-    x = [synth.logits_torch(w, 1000 + i, seed, device="cpu") for i in range(n_buf)]
-    if w.dtype == "bf16":
-        import torch
-        x = [t.view(torch.int16).numpy().view(np.uint16) for t in x]
-    else:
-        x = [t.numpy() for t in x]
-    # full-width steps on all rows until about 10 s of CPU work have been timed (at least 3 steps)
-    t0 = time.perf_counter()
-    n_res = n_steps = 0
-    while n_steps < 3 or (time.perf_counter() - t0 < 10.0 and n_steps < 4000):
-        i = n_steps
-        o.step(x[i % n_buf], i + 1, w.alpha_at(i + 1), w.alpha_at(i), -1.0)
-        _, flag, _ = o.resample(i + 1)
-        n_res += int(flag.sum())
-        n_steps += 1
-    t_step = (time.perf_counter() - t0) / n_steps
-    # KV gather: one prompt (N rows) of a few tensors, timed and scaled linearly to all tensors
+def _cpu_gather_leg(w, seed, orc, np):
+    """Oracle KV gather of one prompt (N rows) of a few tensors, scaled linearly to all tensors; seconds per prompt."""
     n_t = max(1, min(w.kv_tensors, int(1.5e9 // (w.N * w.kv_row_bytes))))
     rng = np.random.default_rng(seed)
     src = [rng.integers(0, 65535, size=(w.N, w.H, w.S, w.D), dtype=np.uint16) for _ in range(n_t)]
@@ -82,15 +66,84 @@ def cpu_baseline(w, seed, gpu_resample_frac):
     t0 = time.perf_counter()
     for a, d in zip(src, dst):
         orc.gather_kv(a, anc, flag, w.N, w.S, d)
-    t_gather_prompt = (time.perf_counter() - t0) * (w.kv_tensors / n_t)
+    return (time.perf_counter() - t0) * (w.kv_tensors / n_t), n_t
+
+
+def _cpu_step_leg(w, seed, x, first_t, budget_s, orc):
+    """Full-width oracle steps (vocabulary pass, ESS, resampling) on the rows of x until budget_s seconds of CPU work
+    have been timed (at least 2 steps); seconds per step."""
+    B = x[0].shape[0] // w.N
+    o = orc.OracleSMC(B, w.N, w.V, first_t + 4096, w.kappa, seed, w.dtype)
+    t0 = time.perf_counter()
+    n_steps = 0
+    while n_steps < 2 or (time.perf_counter() - t0 < budget_s and n_steps < 4000):
+        t = first_t + n_steps
+        o.step(x[n_steps % len(x)], t, w.alpha_at(t), w.alpha_at(t - 1), -1.0)
+        o.resample(t)
+        n_steps += 1
+    return (time.perf_counter() - t0) / n_steps, n_steps
+
+
+def _as_oracle_input(t, w):
+    import numpy as np
+    import torch
+    t = t.cpu()
+    return t.view(torch.int16).numpy().view(np.uint16) if w.dtype == "bf16" else t.numpy()
+
+
+def cpu_single_leg(args):
+    """Child process (OMP_NUM_THREADS=1 set by the parent before the oracle's library loads): the oracle on ONE core,
+    on a few prompts of the same recipe.  Prints one JSON line; touches no GPU."""
+    import numpy as np
+    from oracle import reference as orc
+    from paper_2602_10273_amd import synth
+    w = synth.WORKLOADS[args.workload]
+    sub = synth.scaled(w, B=max(1, 32 // w.N))
+    x = [_as_oracle_input(synth.logits_torch(sub, 1000 + i, args.seed, device="cpu"), w) for i in range(2)]
+    import ctypes
+    ctypes.CDLL("libgomp.so.1").omp_set_num_threads(1)      # the OpenMP runtime the oracle links: one thread from here on
+    first_t = w.ramp + 1
+    t_step, n_steps = _cpu_step_leg(w, args.seed, x, first_t, 6.0, orc)
+    t_gather, n_t = _cpu_gather_leg(w, args.seed, orc, np)
+    print(json.dumps({"threads": orc.threads(), "rows": sub.R, "steps": n_steps, "step_s": t_step,
+                      "gather_prompt_s": t_gather, "gather_tensors": n_t}))
+
+
+def cpu_baseline(w, seed, gpu_resample_frac, ring, first_t, args):
+    """The oracle as it stands, on the host cores: full-width steps on all rows of the same logits the GPU saw, plus
+    the KV gather of one prompt's rows scaled to the number of prompts that resample per step.  A second leg runs
+    the same oracle on one core in a child process (on a few prompts, scaled to all rows)."""
+    import subprocess
+    import numpy as np
+    from oracle import reference as orc
+
+    threads = orc.threads()
+    x = [_as_oracle_input(ring[i], w) for i in range(min(2, len(ring)))]
+    t_step, n_steps = _cpu_step_leg(w, seed, x, first_t, 10.0, orc)
+    t_gather_prompt, n_t = _cpu_gather_leg(w, seed, orc, np)
     t_total = t_step + t_gather_prompt * gpu_resample_frac * w.B
-    return {
+    out = {
         "value": w.R / t_total, "unit": "particle-steps/s", "cores": threads, "kind": "oracle",
-        "sample": (f"{n_steps} full-width steps (vocabulary pass + ESS + resampling) on all {w.R} rows; KV gather of one "
-                   f"prompt ({w.N} rows x {n_t} of {w.kv_tensors} tensors) scaled to all tensors and to the "
+        "sample": (f"{n_steps} full-width steps (vocabulary pass + ESS + resampling) on all {w.R} rows, t >= {first_t}; KV "
+                   f"gather of one prompt ({w.N} rows x {n_t} of {w.kv_tensors} tensors) scaled to all tensors and to the "
                    f"{gpu_resample_frac * w.B:.2f} prompts/step that resampled on the GPU"),
         "step_s": t_step, "gather_prompt_s": t_gather_prompt,
     }
+    env = dict(os.environ, OMP_NUM_THREADS="1")
+    cmd = [sys.executable, os.path.abspath(__file__), "--cpu-single-leg", "--workload", args.workload, "--seed", str(seed)]
+    try:
+        r = subprocess.run(cmd, env=env, capture_output=True, text=True, timeout=240, check=True)
+        leg = json.loads(r.stdout.strip().splitlines()[-1])
+        t1 = leg["step_s"] * (w.R / leg["rows"]) + leg["gather_prompt_s"] * gpu_resample_frac * w.B
+        out["single_core"] = {
+            "value": w.R / t1, "unit": "particle-steps/s", "cores": leg["threads"], "kind": "oracle",
+            "sample": (f"{leg['steps']} full-width steps on {leg['rows']} rows scaled to {w.R}; KV gather of one prompt "
+                       f"({leg['gather_tensors']} of {w.kv_tensors} tensors) scaled as above; child process, OpenMP limited to one thread"),
+            "step_s_scaled": leg["step_s"] * (w.R / leg["rows"]), "gather_prompt_s": leg["gather_prompt_s"],
+        }
+    except (subprocess.SubprocessError, ValueError, KeyError, IndexError) as e:
+        out["single_core"] = {"error": repr(e)[:200]}
+    return out
 
 
 def measured_ceilings(smc, torch, dev):
@@ -102,6 +155,36 @@ def measured_ceilings(smc, torch, dev):
            for kind, name in enumerate(("read", "write", "copy_1r1w", "fanout_1r3w"))}
     del buf
     return out
+
+
+def check_rows_after_reorder(s, w, anc_before, torch, np, n_rows=6):
+    """One more reorder with the ancestors `anc_before`, then sampled destination rows of the first, a middle and the
+    last tensor are compared byte for byte with their ancestors' rows as they were before it (moved rows of both
+    parities and a row that stayed).  Raises on any mismatch: a timed cache that was never checked proves nothing."""
+    _, _, par0 = s.state()
+    anc = anc_before.cpu().numpy()
+    moved = np.nonzero(anc != np.arange(w.R))[0]
+    stay = np.nonzero(anc == np.arange(w.R))[0]
+    pick = []
+    for p in (0, 1):                                   # destination rows whose ancestors lived in buffer A / buffer B
+        cand = moved[par0[anc[moved]] == p]
+        pick += list(cand[:: max(1, len(cand) // (n_rows // 2))][: n_rows // 2])
+    pick += list(stay[:1])
+    tensors = sorted({0, w.kv_tensors // 2, w.kv_tensors - 1})
+    want = {}
+    for ten in tensors:
+        for k in pick:
+            a = int(anc[k])
+            src = s.kvB[ten] if par0[a] else s.kvA[ten]
+            want[(ten, int(k))] = src[a].clone()
+    flag = torch.ones(w.B, dtype=torch.int32, device="cuda")
+    s.reindex(w.S, 4, anc_before, flag)
+    _, _, par1 = s.state()
+    for (ten, k), ref in want.items():
+        dst = s.kvB[ten] if par1[k] else s.kvA[ten]
+        if not torch.equal(dst[k].view(torch.int16), ref.view(torch.int16)):
+            raise RuntimeError(f"reorder check failed: tensor {ten}, row {k} differs from its ancestor {int(anc[k])}")
+    assert all(par1[k] != par0[k] for k in pick[:-1] if anc[k] != k)
 
 
 def reindex_only(args, w, K, W, smc, synth, Session, np, torch):
@@ -124,6 +207,7 @@ def reindex_only(args, w, K, W, smc, synth, Session, np, torch):
     elapsed = time.perf_counter() - t0
     ms_gather, n_gather = smc.smc_profile_read(s.ctx, 1)
     smc.smc_profile_enable(s.ctx, 0)
+    check_rows_after_reorder(s, w, d_anc[W + K - 1], torch, np)
     ident = np.arange(w.R)
     rows_written = rows_read = 0
     for a in ancs[W:]:
@@ -216,6 +300,8 @@ def main():
         print("bench.py: this build measures one GPU only (the path shards by prompt with no communication); "
               "run with --gpus 1", file=sys.stderr)
         sys.exit(2)
+    if args.cpu_single_leg:
+        return cpu_single_leg(args)
     import numpy as np
     import torch
     from paper_2602_10273_amd import binding as smc
@@ -233,12 +319,35 @@ def main():
         return attention_only(args, w, K, min(W, 2), smc, synth, Session, np, torch)
     dev = "cuda"
     torch.cuda.set_device(0)
-    T_max = (W + 2 * K + 8 + 3) // 4 * 4
+    # untimed prologue: the steps of the exponent ramp where the workload has one (cfg4: t = 1..128), so that the timed
+    # steps run at the held exponent (the integer-exponent instantiation of the vocabulary pass) on the state a real
+    # run has there
+    prologue = 0 if args.no_prologue else w.ramp
+    first_t = 1
+    T_max = (prologue + W + 2 * K + 8 + 3) // 4 * 4
 
     kv_geom = None if args.no_kv else (w.kv_tensors, w.H, w.S, w.D)
     P = 0 if args.no_kv else args.paged
-    len0 = max(0, w.S - (W + 2 * K) - 1)           # paged runs: the cache is this full when the run starts
-    s = Session(w.B, w.N, w.V, T_max, w.dtype, w.kappa, args.seed, kv_geom=kv_geom, page_len=P, len0=len0)
+    len0 = max(0, w.S - (prologue + W + 2 * K) - 1)           # paged runs: the cache is this full when the run starts
+    kv_note = None
+    s = None
+    try:
+        s = Session(w.B, w.N, w.V, T_max, w.dtype, w.kappa, args.seed, kv_geom=kv_geom, page_len=P, len0=len0)
+    except torch.OutOfMemoryError:
+        if args.workload != "cfg4" or args.no_kv:
+            raise
+    if s is None:
+        # the 2 x 120 GB cache did not fit beside whatever else holds device memory: the next largest configuration
+        import gc
+        gc.collect()
+        torch.cuda.empty_cache()
+        args.workload = "cfg3"
+        w = synth.WORKLOADS["cfg3"]
+        kv_note = "cfg4's 246 GB allocation failed on this box; fell back to cfg3"
+        prologue = 0
+        kv_geom = (w.kv_tensors, w.H, w.S, w.D)
+        len0 = max(0, w.S - (prologue + W + 2 * K) - 1)
+        s = Session(w.B, w.N, w.V, T_max, w.dtype, w.kappa, args.seed, kv_geom=kv_geom, page_len=P, len0=len0)
     if args.n_split:
         smc.smc_set_tuning(s.ctx, args.n_split, 0)
     if args.in_place:
@@ -248,10 +357,20 @@ def main():
         for t in (s.pools if P else s.kvA):
             t.normal_(generator=g)
     n_ring = 4 if w.dtype == "f32" else 16       # distinct logits buffers: more bytes than the 256 MB last-level cache
-    ring = [synth.logits_torch(w, i, args.seed) for i in range(n_ring)]
+    # Each buffer holds kExtraRows more i.i.d. rows than the workload has, and the window of R rows a step reads slides
+    # by one row every n_ring steps: no particle slot meets the same logits row twice within n_ring * (kExtraRows + 1)
+    # steps.  (Re-using a buffer unshifted would hit the same rows with the same increments every n_ring steps, which
+    # is not the recipe's fresh draw per step: the weights would degenerate differently.)
+    kExtraRows = 256
+    w_gen = synth.scaled(w, B=w.B + (kExtraRows + w.N - 1) // w.N)
+    ring = [synth.logits_torch(w_gen, i, args.seed) for i in range(n_ring)]
     torch.cuda.synchronize()
 
-    step_no = [0]
+    def logits_of(t):
+        shift = ((t - 1) // n_ring) % (kExtraRows + 1)
+        return ring[t % n_ring][shift:shift + w.R]
+
+    step_no = [first_t - 1]
 
     def reorder(t):
         if P:
@@ -263,14 +382,19 @@ def main():
         step_no[0] += 1
         t = step_no[0]
         if P:
-            s.prepare_append(len0 + t - 1)          # the decoder would now write position len0+t-1 and emit logits
-        s.step(ring[t % n_ring], t, w.alpha_at(t), w.alpha_at(t - 1), -1.0)
+            s.prepare_append(len0 + (t - first_t))  # the decoder would now write this position and emit logits
+        s.step(logits_of(t), t, w.alpha_at(t), w.alpha_at(t - 1), -1.0)
         s.resample(t)
         reorder(t)
 
+    n_pro_resampled = 0
+    for _ in range(prologue):
+        one_step()
+        n_pro_resampled += s.resampled          # device tensor: no synchronisation inside the prologue
     for _ in range(W):
         one_step()
     torch.cuda.synchronize()
+    t_first_timed = step_no[0] + 1
     t0 = time.perf_counter()
     for _ in range(K):
         one_step()
@@ -285,12 +409,12 @@ def main():
         step_no[0] += 1
         t = step_no[0]
         if P:
-            s.prepare_append(len0 + t - 1)
-        s.step(ring[t % n_ring], t, w.alpha_at(t), w.alpha_at(t - 1), -1.0)
+            s.prepare_append(len0 + (t - first_t))
+        s.step(logits_of(t), t, w.alpha_at(t), w.alpha_at(t - 1), -1.0)
         s.resample(t)
         anc_log[i].copy_(s.anc); flag_log[i].copy_(s.resampled)
         reorder(t)
-    first_t = step_no[0] - K + 1
+    first_logged = step_no[0] - K + 1
     ms_vocab, n_vocab = smc.smc_profile_read(s.ctx, 0)
     ms_gather, n_gather = smc.smc_profile_read(s.ctx, 2 if P else 1)
     smc.smc_profile_enable(s.ctx, 0)
@@ -301,15 +425,16 @@ def main():
     # per resampled prompt: rows whose ancestor is another row are written once; their distinct ancestors are read once
     local = anc_h - (np.arange(w.B)[None, :, None] * w.N)
     moved = (local != np.arange(w.N)[None, None, :]) & (flag_h[:, :, None] != 0)
-    rows_moved = int(moved.sum()) + sum(len(np.unique(local[i, b][moved[i, b]])) for i in range(K) for b in range(w.B))
-    gather_bytes_total = float(rows_moved) * w.kv_row_bytes * w.kv_tensors
+    rows_written = int(moved.sum())
+    rows_read = sum(len(np.unique(local[i, b][moved[i, b]])) for i in range(K) for b in range(w.B))
+    gather_bytes_total = float(rows_written + rows_read) * w.kv_row_bytes * w.kv_tensors
     if P:
         # an append at offset o = pos % P copies o positions (read + write) for every sharer of a page but one: the
         # rows of the prompts that resampled at the previous step, minus their distinct ancestors
         gather_bytes_total = 0.0
         pos_bytes = w.kv_row_bytes // w.S
         for i in range(1, K):
-            o = (len0 + first_t + i - 1) % P
+            o = (len0 + first_logged - first_t + i) % P
             needy = sum(w.N - len(np.unique(local[i - 1, b])) for b in range(w.B) if flag_h[i - 1, b])
             gather_bytes_total += 2.0 * needy * o * pos_bytes * w.kv_tensors
     resample_frac = float(flag_h.mean())
@@ -323,8 +448,9 @@ def main():
                 "frac": gbps / HBM_PEAK_GBPS, "traffic": None, "launches": int(launches),
                 "avg_launch_ms": ms / launches, "algorithmic_bytes_per_launch": total_bytes / launches}
 
-    # HBM traffic per launch: measured offline with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (calibrated on a copy of
-    # known size) as a multiple of the algorithmic bytes; the committed ratio is applied to this run's bytes.
+    # HBM traffic per launch is not a counter of this run: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this same
+    # command (calibrated on a copy of known size) gave traffic as a multiple of the algorithmic bytes; that committed
+    # ratio is applied to this run's algorithmic bytes and labelled as derived.
     ratios = {}
     try:
         ratios = json.load(open(os.path.join(ROOT, "profiles", "hbm_traffic_ratio.json"))).get(args.workload, {})
@@ -337,21 +463,28 @@ def main():
     for r in (r_vocab, r_gather):
         if r["kernel"] in ratios and r.get("algorithmic_bytes_per_launch"):
             r["traffic"] = ratios[r["kernel"]] * r["algorithmic_bytes_per_launch"]
-            r["traffic_source"] = "profiles/hbm_traffic_ratio.json x algorithmic bytes of this run"
+            r["traffic_source"] = ("derived, not measured in this run: the FETCH_SIZE+WRITE_SIZE / algorithmic-bytes ratio "
+                                   "in profiles/hbm_traffic_ratio.json x the algorithmic bytes of this run")
     dominant, other = (r_gather, r_vocab) if ms_gather >= ms_vocab else (r_vocab, r_gather)
 
     out = {
         "metric": "particle-steps/s (SMC step + KV reindex), 1 MI355X",
         "value": w.R * K / elapsed, "unit": "particle-steps/s", "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": elapsed / K * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
+        "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "N": w.N, "V": w.V, "logits_dtype": w.dtype, "alpha": w.alpha,
+                   "prologue_steps": prologue, "first_timed_step": t_first_timed,
+                   "alpha_timed": [w.alpha_at(t_first_timed), w.alpha_at(t_first_timed + 2 * K - 1)],
+                   "prologue_resampled_prompt_fraction": (float(n_pro_resampled.sum()) / (prologue * w.B)) if prologue else None,
                    "kappa": w.kappa, "ancestor_order": "survivors-in-place" if args.in_place else "as-drawn", "kv": None if args.no_kv else (f"{w.layers}x2 paged pools [{w.B}x{s.Q},{w.H},{P},{w.D}] bf16, {len0} positions filled at start"
                                                  if P else f"{w.layers}x2 tensors [{w.R},{w.H},{w.S},{w.D}] bf16 x2 buffers"),
                    "valid_len": w.S, "resampled_prompt_fraction": resample_frac,
-                   "logits_ring": n_ring},
+                   "rows_read_per_row_written": rows_read / max(rows_written, 1),
+                   "logits_ring": f"{n_ring} buffers of {w_gen.R} rows, window of {w.R} rows sliding one row per {n_ring} steps"},
         "roofline": dominant, "roofline_other": other,
     }
+    if kv_note:
+        out["config"]["note"] = kv_note
     s.close()
     del s
     torch.cuda.empty_cache()
@@ -359,7 +492,7 @@ def main():
     out["measured_ceilings_GBps"] = measured_ceilings(smc, torch, dev)
     out["device_copy_GBps"] = out["measured_ceilings_GBps"]["copy_1r1w"]
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, args.seed, resample_frac if not args.no_kv else 0.0)
+        out["cpu_baseline"] = cpu_baseline(w, args.seed, resample_frac if not args.no_kv else 0.0, [r[:w.R] for r in ring], t_first_timed, args)
     print(json.dumps(out))
 
 
