@@ -155,12 +155,17 @@ smc_status smc_set_ancestor_order(smc_ctx* ctx, int32_t order);
  * tensor, the first t columns of the history -- gathers cumulative log p and the termination flags the same way,
  * then flips parity[k].  Rows that are their own ancestor move no bytes.  d_anc entries of a resampled prompt must
  * lie inside that prompt's row range (others are ignored and the row left as it is).  Each distinct ancestor row is
- * read once and written to all of its moved descendants.  With eos_id >= 0 the KV rows of a terminated ancestor
- * are not copied (App. D: a terminated particle is a no-op, its cache is never read again): its descendants
- * receive its history, sum and flag, their parity flips like any moved row's, and the content of their KV rows is
- * unspecified from then on. */
+ * read once and written to all of its moved descendants: afterwards the live KV rows equal the gather by ancestor
+ * byte for byte.  See smc_set_kv_skip_terminated for the opt-in shortcut for terminated ancestors. */
 smc_status smc_kv_reindex(smc_ctx* ctx, const int32_t* d_anc, const int32_t* d_resampled, int32_t valid_len,
                           int32_t t);
+
+/* Opt-in shortcut of smc_kv_reindex (enable = 1; default 0; only acts with eos_id >= 0): the KV rows of a terminated
+ * ancestor are not copied (App. D: the absorbing state is a no-op, a terminated particle's cache is never read
+ * again).  Its descendants still receive its history, sum and flag and their parity flips like any moved row's, but
+ * from then on the content of the KV rows of terminated particles is unspecified.  Late in a run, when most
+ * particles have terminated, the reorder then moves almost nothing. */
+smc_status smc_set_kv_skip_terminated(smc_ctx* ctx, int32_t enable);
 
 /* Explicit-input forms of a3 / a4 for component checks: same arithmetic on caller-provided weights.
  * smc_resample_from writes the reset weights to d_logW_inout. */
@@ -172,6 +177,15 @@ smc_status smc_resample_from(smc_ctx* ctx, double* d_logW_inout, int32_t t, int3
  * weights (particle order) with one uniform of the Philox stream (domain 2, row := prompt, v := 0):
  * I = min{ j : sum_{k<=j} W_k >= u }.  d_choice_out int32 [B] receives the global row index b*N + I. */
 smc_status smc_final_draw(smc_ctx* ctx, int32_t t, int32_t* d_choice_out);
+
+/* log of the SMC estimate of the normalising constant Z_alpha = sum_y p(y)^alpha of the power target, per prompt
+ * (host double [B]; synchronous): smc_resample adds log(mean unnormalised weight) = LSE_i(log W~_i) - log N to a
+ * running sum whenever a prompt resamples (Alg. 1 resets the weights there), and this call returns that sum plus the
+ * same term of the current weights.  E[exp(.)] = Z_alpha for any N (the estimate is unbiased).  h_banked (host double
+ * [B]) receives the running sum alone, which is what smc_set_log_zhat restores when a run is resumed from a saved
+ * state.  Either output may be NULL, not both. */
+smc_status smc_get_log_zhat(smc_ctx* ctx, double* h_logZhat, double* h_banked);
+smc_status smc_set_log_zhat(smc_ctx* ctx, const double* h_banked);
 
 /* Synchronous access to the termination flags (host int32 [R]; only meaningful with eos_id >= 0). */
 smc_status smc_get_done(smc_ctx* ctx, int32_t* h_done);
@@ -227,12 +241,15 @@ smc_status smc_paged_bind(smc_ctx* ctx, void* const* h_pools, int32_t page_len, 
  * else SMC_E_STATE) of every row: gives every row a page of its own for that position -- a fresh page at a page
  * start, otherwise a fresh page plus a copy of the pos % page_len positions already filled for every sharer of a
  * page but the lowest -- and writes d_slot_out int32 [R]: the page of each row; the decoder stores K/V of the new
- * position at pool[page, h, pos % page_len, :]. */
+ * position at pool[page, h, pos % page_len, :].  The number of appended positions is host-side state of the context:
+ * the call returns SMC_E_STATE while its stream is being captured into a HIP graph (a replay would repeat `pos`). */
 smc_status smc_paged_prepare_append(smc_ctx* ctx, int32_t pos, int32_t* d_slot_out);
 
 /* a5 in paged form: for prompts with d_resampled[b] != 0, table[k, :] = old table[d_anc[k], :] over the columns in
  * use and reference counts recounted; token history (first t columns), cumulative log p and termination flags are
- * gathered as in smc_kv_reindex.  Ancestors outside the prompt's rows leave the row as it is. */
+ * gathered as in smc_kv_reindex.  Ancestors outside the prompt's rows leave the row as it is.  Under stream capture
+ * all columns of the table are permuted (unused ones hold -1 everywhere), so a captured reorder stays valid on
+ * replays that follow later appends; `t` is baked into the capture like any launch argument. */
 smc_status smc_paged_reindex(smc_ctx* ctx, const int32_t* d_anc, const int32_t* d_resampled, int32_t t);
 
 /* Device pointers to the table [R, M] and the reference counts [B*Q], M, Q and the number of appended positions

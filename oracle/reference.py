@@ -155,7 +155,7 @@ class OracleSMC:
     """Algorithm 1 for B independent prompts, state held in fp64 / numpy, one call per step of the path."""
 
     def __init__(self, B, N, V, T_max, kappa, seed, dtype="f32", kv=None, eos_id=-1, scheme="systematic",
-                 in_place=False):
+                 in_place=False, skip_terminated_kv=False):
         self.B, self.N, self.V, self.T_max, self.R = B, N, V, T_max, B * N
         self.kappa, self.seed, self.dtype = float(kappa), int(seed), dtype
         self.logW = np.zeros(self.R, np.float64)          # Alg. 1: W~_0 = 1
@@ -167,6 +167,12 @@ class OracleSMC:
         self.in_place = bool(in_place)                    # survivors keep their slot (same particle system)
         self.eos_id = int(eos_id)                         # -1: EOS is not special
         self.done = np.zeros(self.R, np.int32)            # Alg. 1 termination flags
+        # Reading of App. D ("skipping cache updates" for terminated particles) as an option: when on, the reorder is
+        # not required to move the KV rows of a terminated ancestor (nothing reads them again), so the KV content of a
+        # row that continues one is unspecified from then on.  kv_specified[r] says whether row r's KV bytes are
+        # defined by the gather; with the option off (the default: Alg. 1 "reorder KV cache by A" as written) all are.
+        self.skip_terminated_kv = bool(skip_terminated_kv) and self.eos_id >= 0
+        self.kv_specified = np.ones(self.R, bool)
 
     def step(self, logits, t, alpha_t, alpha_prev, tau_t=-1.0, row_stride=None):
         """a0..a2. logits: [R, >=V] array of self.dtype storage. Returns dict of per-row arrays."""
@@ -207,6 +213,14 @@ class OracleSMC:
         R, N = self.R, self.N
         hist2 = self.hist.copy(); cum2 = self.cumlogp.copy(); done2 = self.done.copy()
         anc = np.ascontiguousarray(anc, np.int32); resampled = np.ascontiguousarray(resampled, np.int32)
+        # which rows hold gather-defined KV bytes afterwards: a row that receives another row's data inherits that
+        # row's status, except that data of a terminated ancestor need not be moved when the option is on
+        spec2 = self.kv_specified.copy()
+        for k in range(R):
+            a = int(anc[k])
+            if resampled[k // N] and a != k and (k // N) * N <= a < (k // N + 1) * N:
+                spec2[k] = self.kv_specified[a] and not (self.skip_terminated_kv and self.done[a] != 0)
+        self.kv_specified = spec2
         lib().orc_gather_state(_p(self.hist), _p(hist2), C.c_int32(self.T_max), C.c_int32(t),
                                _p(self.cumlogp), _p(cum2), _p(anc), _p(resampled), C.c_int32(R), C.c_int32(N),
                                _p(self.done), _p(done2))

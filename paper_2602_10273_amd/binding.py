@@ -19,7 +19,8 @@ EXPORTS = ["smc_workspace_bytes", "smc_init", "smc_destroy", "smc_kv_bind", "smc
            "smc_set_tuning", "smc_set_resampler", "smc_set_ancestor_order", "smc_set_gather_tuning", "smc_profile_enable", "smc_profile_read", "smc_status_str",
            "smc_paged_workspace_bytes", "smc_paged_pool_bytes", "smc_paged_bind", "smc_paged_prepare_append",
            "smc_paged_reindex", "smc_paged_view", "smc_paged_check", "smc_hbm_probe",
-           "smc_attn_workspace_bytes", "smc_attn_decode", "smc_kv_parity", "smc_kv_append", "smc_step_noalloc"]
+           "smc_attn_workspace_bytes", "smc_attn_decode", "smc_kv_parity", "smc_kv_append", "smc_step_noalloc",
+           "smc_get_log_zhat", "smc_set_log_zhat", "smc_set_kv_skip_terminated"]
 
 
 class smc_config(C.Structure):
@@ -57,6 +58,9 @@ def lib():
         L.smc_resample.argtypes = [vp, i32, vp, vp, vp]
         L.smc_kv_reindex.argtypes = [vp, vp, vp, i32, i32]
         L.smc_final_draw.argtypes = [vp, i32, vp]
+        L.smc_get_log_zhat.argtypes = [vp, vp, vp]
+        L.smc_set_log_zhat.argtypes = [vp, vp]
+        L.smc_set_kv_skip_terminated.argtypes = [vp, i32]
         L.smc_get_done.argtypes = [vp, vp]
         L.smc_set_done.argtypes = [vp, vp]
         L.smc_ess_from.argtypes = [vp, vp, vp, vp]
@@ -166,6 +170,18 @@ def smc_kv_reindex(ctx, d_anc, d_resampled, valid_len, t):
 
 def smc_final_draw(ctx, t, d_choice_out):
     _check("smc_final_draw", lib().smc_final_draw(ctx, t, _ptr(d_choice_out)))
+
+
+def smc_get_log_zhat(ctx, h_logZhat=None, h_banked=None):
+    _check("smc_get_log_zhat", lib().smc_get_log_zhat(ctx, _ptr(h_logZhat), _ptr(h_banked)))
+
+
+def smc_set_log_zhat(ctx, h_banked):
+    _check("smc_set_log_zhat", lib().smc_set_log_zhat(ctx, _ptr(h_banked)))
+
+
+def smc_set_kv_skip_terminated(ctx, enable=1):
+    _check("smc_set_kv_skip_terminated", lib().smc_set_kv_skip_terminated(ctx, enable))
 
 
 def smc_get_done(ctx, h_done):

@@ -28,7 +28,7 @@ typedef unsigned int vec16 __attribute__((ext_vector_type(4)));    // one 16-byt
 __device__ void plan_prompt(const int32_t* __restrict__ anc, int N, int mask_words, int phase, GatherPlan* __restrict__ plan,
                             int32_t* __restrict__ grp_src, int32_t* __restrict__ grp_base, int32_t* __restrict__ grp_srcpar,
                             unsigned long long* __restrict__ grp_mask, double* __restrict__ cumlogp,
-                            int32_t* __restrict__ done, int32_t* __restrict__ parity)
+                            int32_t* __restrict__ done, int32_t* __restrict__ parity, int skip_terminated)
 {
     __shared__ int32_t sh_anc[SMC_MAX_PARTICLES];
     __shared__ double sh_cum[SMC_MAX_PARTICLES];
@@ -74,9 +74,10 @@ __device__ void plan_prompt(const int32_t* __restrict__ anc, int N, int mask_wor
             const int g = sh_base + placed + mask_rank(mk);
             grp_src[g] = row0 + a;
             grp_base[g] = row0;
-            // bit 0: the ancestor's live buffer, before any flip; bit 1: the ancestor has terminated -- its cache is
-            // never read again (App. D: the absorbing state is a no-op), so its KV rows are not copied
-            grp_srcpar[g] = parity[row0 + a] | (sh_done[a] ? 2 : 0);
+            // bit 0: the ancestor's live buffer, before any flip; bit 1 (only where the caller opted in and an
+            // end-of-sequence token is configured): the ancestor has terminated -- its cache is never read again
+            // (App. D: the absorbing state is a no-op), so its KV rows are not copied
+            grp_srcpar[g] = parity[row0 + a] | ((skip_terminated && sh_done[a]) ? 2 : 0);
             for (int w = 0; w < mask_words; ++w) grp_mask[(int64_t)g * mask_words + w] = 0ull;
             sh_group[a] = g;
         }
@@ -108,11 +109,12 @@ __global__ __launch_bounds__(kWave) void plan_kernel(const int32_t* __restrict__
                                                      int32_t* __restrict__ grp_srcpar,
                                                      unsigned long long* __restrict__ grp_mask,
                                                      double* __restrict__ cumlogp, int32_t* __restrict__ done,
-                                                     int32_t* __restrict__ parity)
+                                                     int32_t* __restrict__ parity, int skip_terminated)
 {
     const int phase = plan->phase;
     if (resampled[blockIdx.x])
-        plan_prompt(anc, N, mask_words, phase, plan, grp_src, grp_base, grp_srcpar, grp_mask, cumlogp, done, parity);
+        plan_prompt(anc, N, mask_words, phase, plan, grp_src, grp_base, grp_srcpar, grp_mask, cumlogp, done, parity,
+                    skip_terminated);
     if (threadIdx.x == 0) {
         __threadfence();                                           // the read of plan->phase precedes the ticket
         if (atomicAdd(&plan->ticket, 1) == (int)gridDim.x - 1) {
@@ -238,7 +240,8 @@ hipError_t launch_reindex(smc_ctx* c, const int32_t* anc, const int32_t* resampl
     const bool have_kv = c->kv_bound && cfg.kv_tensors > 0 && valid_len > 0;
     const bool have_hist = c->hist_bound && t > 0;
     hipLaunchKernelGGL(plan_kernel, dim3(cfg.B), dim3(kWave), 0, c->stream, anc, resampled, cfg.N, c->mask_words,
-                       w.plan, w.grp_src, w.grp_base, w.grp_srcpar, w.grp_mask, w.cumlogp, w.done, w.parity);
+                       w.plan, w.grp_src, w.grp_base, w.grp_srcpar, w.grp_mask, w.cumlogp, w.done, w.parity,
+                       (c->kv_skip_terminated && cfg.eos_id >= 0) ? 1 : 0);
     if (have_kv || have_hist) {
         GatherGeom kv{}, hist{};
         if (have_kv) {

@@ -179,7 +179,9 @@ __global__ __launch_bounds__(kPagedThreads) void paged_reorder_kernel(
 // counters: [0], [1] number of (source, new page) pairs, alternating between successive calls; [2] rows that found no
 // free page; [3] the pair counter the next call uses; [4] workgroups of the running call that have finished.  Every
 // workgroup reads counters[3] first and takes a ticket last; the one with the last ticket clears the other pair
-// counter and flips counters[3] (no host-side state, so a captured launch sequence can be replayed).
+// counter and flips counters[3] on the device (no memset between calls).  The page column j and offset o are launch
+// arguments derived from the host-side count of appended positions, so smc_paged_prepare_append refuses to be
+// captured into a graph.
 __global__ __launch_bounds__(kPagedThreads) void paged_prepare_kernel(
     int N, int M, int Q, int j, int o, int32_t* __restrict__ table, int32_t* __restrict__ refcnt,
     int32_t* __restrict__ counters, int32_t* __restrict__ cow_src, int32_t* __restrict__ cow_dst,
@@ -307,6 +309,13 @@ inline size_t up(size_t x) { return (x + kAlign - 1) & ~(kAlign - 1); }
 
 struct PagedDims { int P, M, Q; size_t n_table, n_pages; };
 
+bool stream_is_capturing(hipStream_t s)
+{
+    hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(s, &st) != hipSuccess) { (void)hipGetLastError(); return false; }
+    return st != hipStreamCaptureStatusNone;
+}
+
 bool paged_dims(const smc_config* c, int page_len, PagedDims* d)
 {
     if (!c || c->kv_tensors < 1 || c->kv_S < 1 || c->N < 1 || c->B < 1 || page_len < 1 || page_len > c->kv_S) return false;
@@ -391,6 +400,9 @@ smc_status smc_paged_prepare_append(smc_ctx* ctx, int32_t pos, int32_t* d_slot_o
     if (!p.bound) return SMC_E_STATE;
     if (pos < 0 || pos >= ctx->cfg.kv_S) return SMC_E_RANGE;
     if (pos != p.len) return SMC_E_STATE;              // positions are appended one by one, the same for every row
+    // The appended length is host-side state and the page column / offset of `pos` are launch arguments: a captured
+    // call would replay the same position for ever.  Refuse rather than corrupt the table silently.
+    if (stream_is_capturing(ctx->stream)) return SMC_E_STATE;
     const auto& cfg = ctx->cfg;
     const int j = pos / p.P, o = pos % p.P;
     hipLaunchKernelGGL(paged_prepare_kernel, dim3(cfg.B), dim3(kPagedThreads), 0, ctx->stream, cfg.N, p.M, p.Q, j, o,
@@ -427,7 +439,10 @@ smc_status smc_paged_reindex(smc_ctx* ctx, const int32_t* d_anc, const int32_t* 
     if (hb > 64) hb = 64;
     if (hb > hist_vecs) hb = hist_vecs;
     if (hb < 1) hb = 1;
-    const int ncol = (p.len + p.P - 1) / p.P;
+    // Columns in use.  The count is a launch argument, so under stream capture (where later replays may follow
+    // appends that this call cannot see) every column is permuted: unused columns hold -1 in every row, and
+    // permuting them changes nothing.
+    const int ncol = stream_is_capturing(ctx->stream) ? p.M : (p.len + p.P - 1) / p.P;
     int cols = 1, chunks = 0;
     if (ncol > 0) {
         cols = kEntriesPerBlock / N < ncol ? kEntriesPerBlock / N : ncol;   // >= 1: N <= SMC_MAX_PARTICLES

@@ -44,6 +44,8 @@ size_t layout(const smc_config* c, char* base, Workspace* w)
     p = take(R * 8); if (w) w->cumlogp = (double*)p;
     p = take(R * 4); if (w) w->parity = (int32_t*)p;
     p = take(R * 4); if (w) w->done = (int32_t*)p;
+    p = take((size_t)c->B * 8); if (w) w->logZhat = (double*)p;
+    p = take((size_t)c->B * 8); if (w) w->logZest = (double*)p;
     p = take(R * kMaxSplit * sizeof(Partial)); if (w) w->partials = (Partial*)p;
     p = take(R * 8); if (w) w->d_delta = (double*)p;
     p = take(R * 8); if (w) w->d_logZ1 = (double*)p;
@@ -130,6 +132,7 @@ smc_status smc_init(const smc_config* cfg, void* d_workspace, size_t workspace_b
     c->mask_words = (cfg->N + 63) / 64;
     c->resampler = 0;
     c->ancestor_order = 0;
+    c->kv_skip_terminated = 0;
     c->kv_bound = 0;
     c->hist_bound = 0;
     c->profiling = 0;
@@ -318,6 +321,32 @@ smc_status smc_get_diag(smc_ctx* ctx, double* h_delta, double* h_logZ1, double* 
         delete[] st;
         h_counters[3] = (uint64_t)R * (uint64_t)ctx->cfg.V;
     }
+    return SMC_OK;
+}
+
+smc_status smc_get_log_zhat(smc_ctx* ctx, double* h_logZhat, double* h_banked)
+{
+    if (!ctx || (!h_logZhat && !h_banked)) return SMC_E_NULL;
+    if (h_logZhat && launch_log_zhat(ctx, ctx->ws.logZest) != hipSuccess) return SMC_E_HIP;
+    if (hipStreamSynchronize(ctx->stream) != hipSuccess) return SMC_E_HIP;
+    const size_t n = (size_t)ctx->cfg.B * 8;
+    if (h_logZhat && hipMemcpy(h_logZhat, ctx->ws.logZest, n, hipMemcpyDeviceToHost) != hipSuccess) return SMC_E_HIP;
+    if (h_banked && hipMemcpy(h_banked, ctx->ws.logZhat, n, hipMemcpyDeviceToHost) != hipSuccess) return SMC_E_HIP;
+    return SMC_OK;
+}
+
+smc_status smc_set_log_zhat(smc_ctx* ctx, const double* h_banked)
+{
+    if (!ctx || !h_banked) return SMC_E_NULL;
+    if (hipStreamSynchronize(ctx->stream) != hipSuccess) return SMC_E_HIP;
+    return hipMemcpy(ctx->ws.logZhat, h_banked, (size_t)ctx->cfg.B * 8, hipMemcpyHostToDevice) == hipSuccess ? SMC_OK : SMC_E_HIP;
+}
+
+smc_status smc_set_kv_skip_terminated(smc_ctx* ctx, int32_t enable)
+{
+    if (!ctx) return SMC_E_NULL;
+    if (enable < 0 || enable > 1) return SMC_E_RANGE;
+    ctx->kv_skip_terminated = enable;
     return SMC_OK;
 }
 

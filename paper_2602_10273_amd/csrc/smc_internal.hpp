@@ -45,6 +45,8 @@ struct Workspace {                // device pointers carved out of the caller's 
     double* cumlogp;              // [R]
     int32_t* parity;              // [R] which of its two buffers holds a row's live KV / history
     int32_t* done;                // [R] termination flags (Alg. 1)
+    double* logZhat;              // [B] log of the product of the mean unnormalised weights at the resampling times
+    double* logZest;              // [B] read-out scratch of smc_get_log_zhat
     Partial* partials;            // [R * kMaxSplit]
     double* d_delta;              // [R] diagnostics of the last step
     double* d_logZ1;              // [R]
@@ -90,6 +92,7 @@ struct smc_ctx {
     int mask_words;               // 64-bit words per descendant bit set = ceil(N/64)
     int resampler;                // 0 systematic (the paper's), 1 stratified, 2 multinomial, 3 residual
     int ancestor_order;           // 0 as drawn, 1 survivors stay in place
+    int kv_skip_terminated;       // 1: the reorder moves no KV bytes for descendants of a terminated ancestor
     int kv_bound;
     std::vector<void*> h_kvA, h_kvB, h_pools;   // host copies of the registered device pointers (kernel arguments)
     int hist_bound;
@@ -140,5 +143,6 @@ hipError_t launch_ess(smc_ctx* c, const double* logW, double* ess_out, double* l
 hipError_t launch_resample(smc_ctx* c, double* logW, int t, int32_t* anc, int32_t* resampled, double* ess_out);
 hipError_t launch_reindex(smc_ctx* c, const int32_t* anc, const int32_t* resampled, int valid_len, int t);
 hipError_t launch_final_draw(smc_ctx* c, int t, int32_t* choice);
+hipError_t launch_log_zhat(smc_ctx* c, double* out);
 
 }  // namespace psmc

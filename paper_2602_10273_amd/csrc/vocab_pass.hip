@@ -21,18 +21,6 @@
 
 namespace psmc {
 
-#ifdef PSMC_TRACE
-// Debug-only phase timestamps (100 MHz wall clock), 8 slots per wave; never compiled into the shipped library.
-__device__ unsigned long long g_trace[1 << 17];
-#define PSMC_STAMP(k) do { if (lane == 0) g_trace[((blockIdx.x * NW + wave) & 16383) * 8 + (k)] = wall_clock64(); } while (0)
-extern "C" int smc_debug_trace(unsigned long long* h_out, size_t n)
-{
-    return (int)hipMemcpyFromSymbol(h_out, HIP_SYMBOL(g_trace), n * sizeof(unsigned long long));
-}
-#else
-#define PSMC_STAMP(k) do { } while (0)
-#endif
-
 namespace {
 
 constexpr float kLog2e = 1.4426950408889634f;
@@ -227,7 +215,6 @@ __global__ __launch_bounds__(NW * kWave, 4) void vocab_pass_kernel(
     const uint32_t row = blockIdx.x / n_split;
     const char* rowp = (const char*)logits + (int64_t)row * row_stride_bytes;
     if (done && done[row]) return;                     // terminated particle (App. D): its logits are not read
-    PSMC_STAMP(0);
     if (tid == 0) wg_bound = enc_bound(-INFINITY);
     __syncthreads();
 
@@ -452,7 +439,6 @@ __global__ __launch_bounds__(NW * kWave, 4) void vocab_pass_kernel(
             vm = wave_max_f32(vm);
             if (vm > m) raise_max(vm);
             if constexpr (!DENSE) { publish(); adopt(); }      // no waiting: whatever the other waves have found so far
-            PSMC_STAMP(1);
         }
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
@@ -475,11 +461,9 @@ __global__ __launch_bounds__(NW * kWave, 4) void vocab_pass_kernel(
         }
         process(x, nvec_full * EPV);
     }
-    PSMC_STAMP(2);
     if constexpr (!DENSE) {
         // every wave has streamed its share: the workgroup's bound now reflects the maximum of the whole slice
         __syncthreads();
-        PSMC_STAMP(3);
         adopt();
         while (q_count > 0) {
             compact();
@@ -487,9 +471,7 @@ __global__ __launch_bounds__(NW * kWave, 4) void vocab_pass_kernel(
         }
     }
 
-    PSMC_STAMP(4);
     block_epilogue<NW>(beta, m, M1, Mb, s1, sb, top, n_scored, n_drains, partials + (int64_t)row * kMaxSplit + split);
-    PSMC_STAMP(5);
 }
 
 // ------------------------------------------------------------------------------------------------

@@ -74,7 +74,7 @@ __device__ __forceinline__ double resampling_uniform(uint32_t i, uint32_t b, uin
 __global__ __launch_bounds__(kWave) void resample_kernel(double* __restrict__ logW, int N, double kappa, uint32_t key0,
                                                          uint32_t key1, uint32_t step, int scheme, int order,
                                                          int32_t* __restrict__ anc, int32_t* __restrict__ resampled,
-                                                         double* __restrict__ ess_out)
+                                                         double* __restrict__ ess_out, double* __restrict__ logZhat)
 {
     __shared__ double sh_a[SMC_MAX_PARTICLES], sh_b[SMC_MAX_PARTICLES];
     __shared__ int sh_k;
@@ -86,6 +86,8 @@ __global__ __launch_bounds__(kWave) void resample_kernel(double* __restrict__ lo
     if (lane == 0 && ess_out) ess_out[b] = ess;
     const bool fire = ess < kappa * (double)N;           // strict; false for NaN
     if (lane == 0) resampled[b] = fire ? 1 : 0;
+    // running estimate of the normalising constant: every resampling contributes the mean unnormalised weight
+    if (lane == 0 && fire && logZhat) logZhat[b] += L1 - log((double)N);
     if (!fire) {
         for (int i = lane; i < N; i += kWave) anc[(int64_t)b * N + i] = b * N + i;
         return;
@@ -158,6 +160,24 @@ __global__ __launch_bounds__(kWave) void resample_kernel(double* __restrict__ lo
     }
 }
 
+// log of the SMC estimate of the normalising constant Z_alpha of the power target, per prompt: the factors
+// accumulated at the resampling times (mean unnormalised weight each) times the current mean weight.
+__global__ __launch_bounds__(kWave) void log_zhat_kernel(const double* __restrict__ logW, int N,
+                                                         const double* __restrict__ logZhat, double* __restrict__ out)
+{
+    __shared__ double sh_a[SMC_MAX_PARTICLES], sh_b[SMC_MAX_PARTICLES];
+    const int b = blockIdx.x;
+    double L1, L2;
+    prompt_lse(logW + (int64_t)b * N, N, sh_a, sh_b, L1, L2);
+    if (threadIdx.x == 0) out[b] = logZhat[b] + L1 - log((double)N);
+}
+
+hipError_t launch_log_zhat(smc_ctx* c, double* out)
+{
+    hipLaunchKernelGGL(log_zhat_kernel, dim3(c->cfg.B), dim3(kWave), 0, c->stream, c->ws.logW, c->cfg.N, c->ws.logZhat, out);
+    return hipGetLastError();
+}
+
 // Output of Alg. 1: I ~ Categorical(W) by inversion of the running sum of the normalised weights (particle order).
 __global__ __launch_bounds__(kWave) void final_draw_kernel(const double* __restrict__ logW, int N, uint32_t key0,
                                                            uint32_t key1, uint32_t step, int32_t* __restrict__ choice)
@@ -188,9 +208,10 @@ hipError_t launch_final_draw(smc_ctx* c, int t, int32_t* choice)
 
 // Alg. 1 initialisation: W~ = 1, empty prefixes; all rows live in buffer A; diagnostics cleared.
 __global__ void init_state_kernel(double* logW, double* cumlogp, int32_t* parity, int32_t* done, int R, int B, int32_t* rowstat,
-                                  GatherPlan* plan)
+                                  GatherPlan* plan, double* logZhat)
 {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < B) logZhat[i] = 0.0;
     if (i < R) { logW[i] = 0.0; cumlogp[i] = 0.0; done[i] = 0; parity[i] = 0; rowstat[3 * i] = 0; rowstat[3 * i + 1] = 0; rowstat[3 * i + 2] = 0; }
     if (i == 0) {
         plan->n_groups[0] = 0; plan->n_groups[1] = 0; plan->bad_anc = 0; plan->phase = 0; plan->ticket = 0;
@@ -201,7 +222,7 @@ hipError_t launch_init_state(smc_ctx* c)
 {
     const int n = c->R > c->cfg.B ? c->R : c->cfg.B;
     hipLaunchKernelGGL(init_state_kernel, dim3((n + 255) / 256), dim3(256), 0, c->stream, c->ws.logW, c->ws.cumlogp,
-                       c->ws.parity, c->ws.done, c->R, c->cfg.B, c->ws.d_rowstat, c->ws.plan);
+                       c->ws.parity, c->ws.done, c->R, c->cfg.B, c->ws.d_rowstat, c->ws.plan, c->ws.logZhat);
     return hipGetLastError();
 }
 
@@ -215,7 +236,7 @@ hipError_t launch_resample(smc_ctx* c, double* logW, int t, int32_t* anc, int32_
 {
     hipLaunchKernelGGL(resample_kernel, dim3(c->cfg.B), dim3(kWave), 0, c->stream, logW, c->cfg.N, c->cfg.kappa,
                        (uint32_t)c->cfg.seed, (uint32_t)(c->cfg.seed >> 32), (uint32_t)t, c->resampler, c->ancestor_order, anc,
-                       resampled, ess_out);
+                       resampled, ess_out, logW == c->ws.logW ? c->ws.logZhat : nullptr);
     return hipGetLastError();
 }
 

@@ -137,6 +137,21 @@ class Session:
     def final_draw(self, t):
         smc.smc_final_draw(self.ctx, t, self.choice)
 
+    def log_Zhat(self):
+        """log of the normalising-constant estimate per prompt (numpy [B]), computed by the library."""
+        out = np.empty(self.B, np.float64)
+        smc.smc_get_log_zhat(self.ctx, out)
+        return out
+
+    def banked_log_Zhat(self):
+        """The part of the estimate accumulated at the resampling times so far (what a resumed run restores)."""
+        out = np.empty(self.B, np.float64)
+        smc.smc_get_log_zhat(self.ctx, None, out)
+        return out
+
+    def set_banked_log_Zhat(self, x):
+        smc.smc_set_log_zhat(self.ctx, np.ascontiguousarray(x, np.float64))
+
     def done(self):
         d = np.empty(self.R, np.int32)
         smc.smc_get_done(self.ctx, d)

@@ -8,6 +8,7 @@ import pytest
 import torch
 
 from oracle import reference as orc
+from paper_2602_10273_amd import binding as smc
 from paper_2602_10273_amd import synth
 from paper_2602_10273_amd.harness import Session, to_device_logits
 
@@ -295,16 +296,42 @@ def test_reindex_bytes_exact(B, N, H, S, D, valid):
     s.close()
 
 
+@pytest.mark.parametrize("eos_id,skip", [(3, 0), (-1, 0), (-1, 1)])
+def test_reindex_copies_the_cache_of_terminated_ancestors_by_default(eos_id, skip):
+    """Without the opt-in shortcut -- and always when no end-of-sequence token is configured, whatever flags
+    smc_set_done stored -- the reorder is the plain gather: every live KV byte equals the oracle's."""
+    B, N, H, S, D = 3, 6, 2, 10, 16
+    R = B * N
+    rng = np.random.default_rng(12)
+    kv = [rng.integers(0, 65536, (R, H, S, D), dtype=np.uint16) for _ in range(2)]
+    s = Session(B, N, 64, 8, "f32", 0.5, 0, kv=kv, eos_id=eos_id)
+    smc.smc_set_kv_skip_terminated(s.ctx, skip)
+    o = orc.OracleSMC(B, N, 64, 8, 0.5, 0, "f32", kv=[k.copy() for k in kv], eos_id=eos_id, skip_terminated_kv=bool(skip))
+    for it in range(4):
+        done = (rng.random(R) < 0.4).astype(np.int32)
+        o.done[:] = done; s.set_done(done)
+        anc = np.concatenate([b * N + np.sort(rng.integers(0, N, N)) for b in range(B)]).astype(np.int32)
+        flag = np.array([1, 1, it % 2], np.int32)
+        s.reindex(S, 5, torch.as_tensor(anc).cuda(), torch.as_tensor(flag).cuda())
+        o.reindex(anc, flag, S, 5)
+        assert o.kv_specified.all()
+        for ten in range(2):
+            assert np.array_equal(s.live_kv(ten), o.kv[ten])
+        assert np.array_equal(s.done(), o.done)
+    s.close()
+
+
 def test_reindex_leaves_the_cache_of_terminated_ancestors_alone():
-    """A terminated particle is a no-op (App. D): descendants of a terminated ancestor get its history, sum, flag and
-    a flipped parity like any moved row, but no KV bytes are read or written for them; everything else follows the
-    oracle's gather."""
+    """smc_set_kv_skip_terminated(1).  A terminated particle is a no-op (App. D): descendants of a terminated ancestor
+    get its history, sum, flag and a flipped parity like any moved row, but no KV bytes are read or written for them;
+    everything else follows the oracle's gather, and the oracle (same option) names the rows it leaves unspecified."""
     B, N, H, S, D = 3, 6, 2, 10, 16
     R = B * N
     rng = np.random.default_rng(11)
     kv = [rng.integers(0, 65536, (R, H, S, D), dtype=np.uint16) for _ in range(2)]
     s = Session(B, N, 64, 8, "f32", 0.5, 0, kv=kv, eos_id=3)
-    o = orc.OracleSMC(B, N, 64, 8, 0.5, 0, "f32", kv=[k.copy() for k in kv], eos_id=3)
+    smc.smc_set_kv_skip_terminated(s.ctx, 1)
+    o = orc.OracleSMC(B, N, 64, 8, 0.5, 0, "f32", kv=[k.copy() for k in kv], eos_id=3, skip_terminated_kv=True)
     o.hist[:] = rng.integers(0, 64, (R, 8)); o.cumlogp[:] = -rng.random(R)
     s.histA.copy_(torch.as_tensor(o.hist)); s.set_state(None, o.cumlogp)
     for it in range(4):
@@ -316,11 +343,12 @@ def test_reindex_leaves_the_cache_of_terminated_ancestors_alone():
         a_before = [t.view(torch.int16).cpu().numpy().copy() for t in s.kvA]
         b_before = [t.view(torch.int16).cpu().numpy().copy() for t in s.kvB]
         o.kv = [s.live_kv(i) for i in range(2)]                  # the oracle starts from what is live on the device
+        o.kv_specified[:] = True
         s.reindex(S, 5, torch.as_tensor(anc).cuda(), torch.as_tensor(flag).cuda())
         o.reindex(anc, flag, S, 5)
         moved = (anc != np.arange(R)) & (np.repeat(flag, N) != 0)
-        dead = moved & (done[anc] != 0)                          # rows that continue a terminated ancestor
-        assert dead.any() and (moved & ~dead).any()
+        dead = ~o.kv_specified                                   # rows that continue a terminated ancestor
+        assert dead.any() and (moved & ~dead).any() and not (dead & ~moved).any()
         _, cum_g, par2 = s.state()
         assert np.array_equal(par2, par ^ moved.astype(np.int32))
         assert np.array_equal(cum_g, o.cumlogp) and np.array_equal(s.done(), o.done)

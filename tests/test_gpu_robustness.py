@@ -20,23 +20,15 @@ def _run_bigram_gpu(B, N, T, alphas, seed, eos_id=-1, scheme=0):
     s = Session(B, N, w.V, 8, "f32", 0.5, seed, eos_id=eos_id)
     smc.smc_set_resampler(s.ctx, scheme)
     table_d = torch.as_tensor(TABLE).cuda()
-    log_Zhat = torch.zeros(B, dtype=torch.float64, device="cuda")
-    lnw = torch.zeros(w.R, dtype=torch.float64, device="cuda")
     prev = torch.zeros(w.R, dtype=torch.long, device="cuda")
     for t in range(1, T + 1):
         x = table_d[prev].contiguous()
         s.step(x, t, alphas[t], alphas[t - 1])
-        # running estimate of Z: at every resampling the mean unnormalised weight is banked (plumbing, torch only)
-        logW, _, _ = s.state()
-        L1 = torch.logsumexp(torch.as_tensor(logW).cuda().view(B, N), dim=1)
-        s.resample(t)
-        log_Zhat += torch.where(s.resampled != 0, L1 - np.log(N), torch.zeros_like(L1))
+        s.resample(t)                 # banks the mean unnormalised weight of every prompt that resamples
         s.reindex(0, t)
         hist = torch.as_tensor(s.live_hist()[:, t - 1]).cuda()
         prev = hist.long()
-    logW, _, _ = s.state()
-    L1 = torch.logsumexp(torch.as_tensor(logW).cuda().view(B, N), dim=1)
-    return s, (log_Zhat + L1 - np.log(N)).cpu().numpy()
+    return s, s.log_Zhat()            # the library's own estimate: banked factors times the current mean weight
 
 
 @pytest.mark.parametrize("mode", ["constant", "ramp", "eos", "residual"])
@@ -154,7 +146,7 @@ def test_checkpoint_and_resume_reproduce_the_uninterrupted_run():
     def snapshot(s, t):
         logW, cum, _ = s.state()
         return dict(logW=logW, cum=cum, done=s.done(), hist=s.live_hist(), kv=[s.live_kv(i) for i in range(len(kv))],
-                    tokens=s.tokens.cpu().numpy())
+                    tokens=s.tokens.cpu().numpy(), banked=s.banked_log_Zhat(), logZ=s.log_Zhat())
 
     full = Session(w.B, w.N, w.V, T, w.dtype, w.kappa, seed, kv=kv, eos_id=7)
     advance(full, 1, cut)
@@ -167,13 +159,15 @@ def test_checkpoint_and_resume_reproduce_the_uninterrupted_run():
     resumed.histA.copy_(torch.as_tensor(snap["hist"]))
     resumed.set_state(snap["logW"], snap["cum"])
     resumed.set_done(snap["done"])
+    resumed.set_banked_log_Zhat(snap["banked"])
     advance(resumed, cut + 1, T)
     got = snapshot(resumed, T)
     resumed.close()
     assert np.array_equal(got["tokens"], want["tokens"]) and np.array_equal(got["hist"][:, :T], want["hist"][:, :T])
     assert np.array_equal(got["logW"], want["logW"]) and np.array_equal(got["cum"], want["cum"])
     assert np.array_equal(got["done"], want["done"])
-    live = want["done"] == 0                                       # the cache of a terminated particle is dead
-    assert 0 < live.sum() < w.R
+    assert 0 < (want["done"] == 0).sum() < w.R
     for a, b in zip(got["kv"], want["kv"]):
-        assert np.array_equal(a[live], b[live])
+        assert np.array_equal(a, b)                                # every row, terminated or not (no shortcut is on)
+    assert np.array_equal(got["banked"], want["banked"]) and np.array_equal(got["logZ"], want["logZ"])
+    assert np.abs(want["banked"]).max() > 0

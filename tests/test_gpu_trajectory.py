@@ -39,15 +39,18 @@ def _ambiguous_resample(o, lnw, t):
     return out
 
 
-def run_lockstep(w, seed, steps, tau=-1.0, table=None, grow_kv=True, kv_seed=3, eos_id=-1, in_place=False):
+def run_lockstep(w, seed, steps, tau=-1.0, table=None, grow_kv=True, kv_seed=3, eos_id=-1, in_place=False,
+                 skip_terminated_kv=False):
+    from paper_2602_10273_amd import binding as smc
     kv = synth.kv_numpy(w, kv_seed)
     T_max = (steps + 3) // 4 * 4
     s = Session(w.B, w.N, w.V, T_max, w.dtype, w.kappa, seed, kv=kv, eos_id=eos_id)
     if in_place:
-        from paper_2602_10273_amd import binding as smc
         smc.smc_set_ancestor_order(s.ctx, 1)
+    if skip_terminated_kv:
+        smc.smc_set_kv_skip_terminated(s.ctx, 1)
     o = orc.OracleSMC(w.B, w.N, w.V, T_max, w.kappa, seed, w.dtype, kv=[k.copy() for k in kv], eos_id=eos_id,
-                      in_place=in_place)
+                      in_place=in_place, skip_terminated_kv=skip_terminated_kv)
     kv_rng = np.random.default_rng([seed, 99])
     stats = dict(token_ties=0, ess_band=0, pos_band=0, resamples=0, steps=0, max_dw=0.0, max_dess=0.0, done=0,
                  draw_band=0, rows_moved=0)
@@ -119,13 +122,16 @@ def run_lockstep(w, seed, steps, tau=-1.0, table=None, grow_kv=True, kv_seed=3, 
         assert np.abs(logW - o.logW).max() < TOL and np.abs(cum - o.cumlogp).max() < TOL, t
         assert np.array_equal(s.live_hist()[:, :t], o.hist[:, :t]), t
         if t % 8 == 0 or t == steps:
-            live = o.done == 0 if eos_id >= 0 else np.ones(w.R, bool)    # the cache of a terminated particle is dead
+            ok = o.kv_specified                 # all rows, unless the terminated-ancestor shortcut is on (the oracle says)
             for ten in range(len(kv)):
-                assert np.array_equal(s.live_kv(ten)[live][:, :, :valid], o.kv[ten][live][:, :, :valid]), (t, ten)
+                assert np.array_equal(s.live_kv(ten)[ok][:, :, :valid], o.kv[ten][ok][:, :, :valid]), (t, ten)
         if eos_id >= 0:
             assert np.array_equal(s.done(), o.done), t          # ... and after they followed their ancestors
         stats["steps"] += 1
     stats["done"] = int(o.done.sum())
+    stats["kv_unspecified"] = int((~o.kv_specified).sum())
+    if stats["ess_band"] == 0:              # same resampling times on both sides: the estimates of log Z_alpha agree
+        assert np.abs(s.log_Zhat() - o.log_Z_estimate()).max() < TOL
     # output of Alg. 1: one particle per prompt from the final weights
     pick_ref = o.final_draw(steps)
     s.final_draw(steps)
@@ -178,6 +184,18 @@ def test_eos_absorbing_state_lockstep():
     # a wider vocabulary with an exponent ramp (the boundary reweight reaches terminated particles too)
     w = synth.scaled(synth.WORKLOADS["cfg4"], B=8, N=16, V=264, layers=1, H=1, S=32, D=32, ramp=16)
     st = run_lockstep(w, seed=2, steps=32, eos_id=5)
+    assert st["done"] > 0 and st["kv_unspecified"] == 0          # default: every KV byte follows the gather
+
+
+def test_eos_lockstep_with_the_terminated_ancestor_shortcut():
+    """smc_set_kv_skip_terminated(1): KV rows of terminated ancestors are not moved; the oracle (same option) says which
+    rows' bytes are unspecified from then on, every other byte is compared."""
+    w1 = synth.WORKLOADS["cfg1"]
+    table = synth.bigram_table(w1.V, w1.sigma, seed=0)
+    st = run_lockstep(synth.scaled(w1, B=400), 77, w1.steps, table=table, eos_id=3, skip_terminated_kv=True)
+    assert st["done"] > 100 and st["resamples"] > 10 and st["kv_unspecified"] > 0
+    w = synth.scaled(synth.WORKLOADS["cfg4"], B=8, N=16, V=264, layers=1, H=1, S=32, D=32, ramp=16)
+    st = run_lockstep(w, seed=2, steps=32, eos_id=5, skip_terminated_kv=True)
     assert st["done"] > 0
 
 

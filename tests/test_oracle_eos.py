@@ -124,3 +124,33 @@ def test_final_draw_returns_the_power_target(exact_eos):
         p = np.exp(log_pi[s])
         freq = np.mean(np.all(chosen == seqs[s][None, :], axis=1))
         assert abs(freq - p) < 4 * np.sqrt(p * (1 - p) / B) + 0.03 * p      # N = 128: small finite-N bias allowed
+
+
+def test_kv_specified_mask_of_the_terminated_ancestor_option():
+    """What the oracle says about KV bytes after a reorder.  Default (Alg. 1 "reorder KV cache by A" as written):
+    every row is defined by the gather.  With the option on (a reading of App. D's skipped cache updates): exactly the
+    moved rows that continue a terminated ancestor become unspecified, they are all terminated themselves, rows that
+    stay keep their status, and a slot that later receives a live ancestor's data is specified again."""
+    B, N = 2, 4
+    R = B * N
+    done = np.array([1, 0, 0, 0, 0, 0, 1, 0], np.int32)
+    anc = np.array([0, 0, 2, 2, 4, 6, 6, 7], np.int32)          # row 1 continues terminated row 0, row 5 terminated row 6
+    flag = np.array([1, 1], np.int32)
+    for skip, want_unspec in ((False, []), (True, [1, 5])):
+        o = orc.OracleSMC(B, N, 8, 8, 0.5, 0, "f32", eos_id=3, skip_terminated_kv=skip)
+        o.done[:] = done
+        o.reindex(anc, flag, 0, 1)
+        assert list(np.nonzero(~o.kv_specified)[0]) == want_unspec
+        assert np.all(o.done[~o.kv_specified] == 1)             # only terminated rows can be unspecified
+        assert list(o.done) == [1, 1, 0, 0, 0, 1, 1, 0]
+        # prompt 0 does not resample next: nothing changes there; prompt 1: slot 5 receives live row 4 -> specified
+        o.reindex(np.array([0, 1, 2, 3, 4, 4, 6, 7], np.int32), np.array([0, 1], np.int32), 0, 2)
+        assert list(np.nonzero(~o.kv_specified)[0]) == ([1] if skip else [])
+        # a copy of an unspecified row is unspecified (row 1 -> slot 3), whatever else happens
+        o.reindex(np.array([0, 1, 2, 1, 4, 5, 6, 7], np.int32), np.array([1, 0], np.int32), 0, 3)
+        assert list(np.nonzero(~o.kv_specified)[0]) == ([1, 3] if skip else [])
+    # without an end-of-sequence token the option does nothing
+    o = orc.OracleSMC(B, N, 8, 8, 0.5, 0, "f32", eos_id=-1, skip_terminated_kv=True)
+    o.done[:] = done
+    o.reindex(anc, flag, 0, 1)
+    assert o.kv_specified.all()
