@@ -106,6 +106,33 @@ smc_status smc_kv_parity(smc_ctx* ctx, const int32_t** d_parity);
 smc_status smc_step(smc_ctx* ctx, const void* d_logits, int64_t row_stride_elems, int32_t t, double alpha_t,
                     double alpha_prev, double tau_t, int32_t* d_tokens_out);
 
+/* a0 .. a4 in ONE launch: smc_step followed by smc_resample, with the same arguments, outputs and results as the
+ * two calls.  The workgroup that completes a row finalizes it, and the wave that finalizes the last row of a prompt
+ * goes on to normalise and resample that prompt, so no second launch (and no launch gap) is needed.  Follow it with
+ * smc_kv_reindex / smc_paged_reindex on d_anc_out / d_resampled_out as after smc_resample. */
+smc_status smc_step_resample(smc_ctx* ctx, const void* d_logits, int64_t row_stride_elems, int32_t t, double alpha_t,
+                             double alpha_prev, double tau_t, int32_t* d_tokens_out, int32_t* d_anc_out,
+                             int32_t* d_resampled_out, double* d_ess_out);
+
+/* ---- Step kept on the device: for launch sequences captured once (HIP graph) and replayed every token -----------
+ * The step number t and the exponents alpha_t, alpha_{t-1} are launch arguments, so a captured step would redraw the
+ * same random numbers on every replay.  With the step kept on the device, the kernels of smc_step, smc_step_resample,
+ * smc_resample(_from) and smc_final_draw read t from a counter in the workspace and the exponents from a schedule
+ * uploaded beforehand; their t / alpha_t / alpha_prev arguments are then ignored (still validated), and tau_t <= 0
+ * means tau = 1/alpha_t of the schedule (tau_t > 0 stays a fixed temperature).  smc_kv_reindex and smc_paged_reindex
+ * move whole history rows in this mode (the host does not know t); valid_len stays a launch argument.
+ *   smc_set_schedule: h_alpha[0..n) = alpha_0, alpha_1, ... (2 <= n <= T_max + 2; steps beyond n-1 use the last entry;
+ *     alpha_0 >= 0, the others > 0).  Synchronous copy.
+ *   smc_set_device_step(enable = 1, t): the counter is set to t (the next step to run, 1-based) and the mode switched
+ *     on (SMC_E_STATE without a schedule); enable = 0 returns to by-value arguments.  Synchronous.
+ *   smc_advance_step: enqueues counter += 1 (one tiny launch, capturable): call it once per token, after the last call
+ *     of the token's sequence.
+ *   smc_get_device_step: synchronous read of the counter. */
+smc_status smc_set_schedule(smc_ctx* ctx, const double* h_alpha, int32_t n);
+smc_status smc_set_device_step(smc_ctx* ctx, int32_t enable, int32_t t);
+smc_status smc_advance_step(smc_ctx* ctx);
+smc_status smc_get_device_step(smc_ctx* ctx, int32_t* h_t);
+
 /* smc_step for callers that cannot allocate device memory: code under HIP graph capture, tight serving loops,
  * harnesses that forbid hipMalloc.  The same a0 + a1 + a2, the same kernels, but no context and no workspace: the
  * scratch of the vocabulary pass (one 48-byte record per row and slice, per-row diagnostics) lives in a device array
@@ -206,7 +233,7 @@ smc_status smc_get_diag(smc_ctx* ctx, double* h_delta, double* h_logZ1, double* 
 /* Tuning knobs of the vocabulary pass (defaults chosen at smc_init): n_split = workgroups a row is split over
  * (1..32; 0 = automatic); dense = 1 scores every entry instead of only those that can win (dense = 0, the default,
  * which itself scores whole 16-byte vectors in place where most of their entries can still win);
- * wg_waves = waves per workgroup, 4 or 16 (0 = automatic).  Every setting returns the same tokens. */
+ * wg_waves = waves per workgroup, 4, 8 or 16 (0 = automatic).  Every setting returns the same tokens. */
 smc_status smc_set_tuning(smc_ctx* ctx, int32_t n_split, int32_t dense, int32_t wg_waves);
 
 /* Tuning knobs of the KV gather: persistent workgroups per compute unit (1..64) and the kernel variant

@@ -20,7 +20,8 @@ EXPORTS = ["smc_workspace_bytes", "smc_init", "smc_destroy", "smc_kv_bind", "smc
            "smc_paged_workspace_bytes", "smc_paged_pool_bytes", "smc_paged_bind", "smc_paged_prepare_append",
            "smc_paged_reindex", "smc_paged_view", "smc_paged_check", "smc_hbm_probe",
            "smc_attn_workspace_bytes", "smc_attn_decode", "smc_kv_parity", "smc_kv_append", "smc_step_noalloc",
-           "smc_get_log_zhat", "smc_set_log_zhat", "smc_set_kv_skip_terminated"]
+           "smc_get_log_zhat", "smc_set_log_zhat", "smc_set_kv_skip_terminated",
+           "smc_step_resample", "smc_set_schedule", "smc_set_device_step", "smc_advance_step", "smc_get_device_step"]
 
 
 class smc_config(C.Structure):
@@ -54,6 +55,11 @@ def lib():
         L.smc_kv_bind.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), vp, vp]
         L.smc_step.argtypes = [vp, vp, i64, i32, f64, f64, f64, vp]
         L.smc_step_noalloc.argtypes = [C.POINTER(smc_config), vp, vp, i64, i32, f64, f64, f64, vp, vp, vp, vp]
+        L.smc_step_resample.argtypes = [vp, vp, i64, i32, f64, f64, f64, vp, vp, vp, vp]
+        L.smc_set_schedule.argtypes = [vp, vp, i32]
+        L.smc_set_device_step.argtypes = [vp, i32, i32]
+        L.smc_advance_step.argtypes = [vp]
+        L.smc_get_device_step.argtypes = [vp, C.POINTER(i32)]
         L.smc_ess.argtypes = [vp, vp, vp]
         L.smc_resample.argtypes = [vp, i32, vp, vp, vp]
         L.smc_kv_reindex.argtypes = [vp, vp, vp, i32, i32]
@@ -154,6 +160,33 @@ def smc_step_noalloc(cfg, hip_stream, d_logits, row_stride_elems, t, alpha_t, al
     _check("smc_step_noalloc", lib().smc_step_noalloc(C.byref(cfg), hip_stream, _ptr(d_logits), row_stride_elems, t, alpha_t,
                                                       alpha_prev, tau_t, _ptr(d_logW_inout), _ptr(d_cumlogp_inout),
                                                       _ptr(d_done_inout), _ptr(d_tokens_out)))
+
+
+def smc_step_resample(ctx, d_logits, row_stride_elems, t, alpha_t, alpha_prev, tau_t, d_tokens_out, d_anc_out,
+                      d_resampled_out, d_ess_out=None):
+    _check("smc_step_resample", lib().smc_step_resample(ctx, _ptr(d_logits), row_stride_elems, t, alpha_t, alpha_prev, tau_t,
+                                                        _ptr(d_tokens_out), _ptr(d_anc_out), _ptr(d_resampled_out),
+                                                        _ptr(d_ess_out)))
+
+
+def smc_set_schedule(ctx, h_alpha):
+    import numpy as np
+    a = np.ascontiguousarray(h_alpha, np.float64)
+    _check("smc_set_schedule", lib().smc_set_schedule(ctx, _ptr(a), a.size))
+
+
+def smc_set_device_step(ctx, enable=1, t=1):
+    _check("smc_set_device_step", lib().smc_set_device_step(ctx, enable, t))
+
+
+def smc_advance_step(ctx):
+    _check("smc_advance_step", lib().smc_advance_step(ctx))
+
+
+def smc_get_device_step(ctx):
+    t = C.c_int32()
+    _check("smc_get_device_step", lib().smc_get_device_step(ctx, C.byref(t)))
+    return t.value
 
 
 def smc_ess(ctx, d_ess_out, d_lognormw_out=None):

@@ -238,7 +238,7 @@ hipError_t launch_reindex(smc_ctx* c, const int32_t* anc, const int32_t* resampl
     const auto& cfg = c->cfg;
     auto& w = c->ws;
     const bool have_kv = c->kv_bound && cfg.kv_tensors > 0 && valid_len > 0;
-    const bool have_hist = c->hist_bound && t > 0;
+    const bool have_hist = c->hist_bound && (t > 0 || c->device_step);
     hipLaunchKernelGGL(plan_kernel, dim3(cfg.B), dim3(kWave), 0, c->stream, anc, resampled, cfg.N, c->mask_words,
                        w.plan, w.grp_src, w.grp_base, w.grp_srcpar, w.grp_mask, w.cumlogp, w.done, w.parity,
                        (c->kv_skip_terminated && cfg.eos_id >= 0) ? 1 : 0);
@@ -261,7 +261,8 @@ hipError_t launch_reindex(smc_ctx* c, const int32_t* anc, const int32_t* resampl
             hist.row_stride = (int64_t)cfg.T_max * 4;
             hist.chunk_stride = hist.row_stride;
             hist.copy_bytes = (((int64_t)t * 4) + 15) & ~15ll;                              // whole 16-byte vectors
-            if (hist.copy_bytes > hist.row_stride) hist.copy_bytes = hist.row_stride;
+            // with the step kept on the device the host does not know how long the prefixes are: whole rows move
+            if (hist.copy_bytes > hist.row_stride || c->device_step) hist.copy_bytes = hist.row_stride;
         }
         ScopedKernelTimer timer(c, 1);
         launch_gather_variant(c, c->gather_variant, kv, hist);

@@ -8,8 +8,8 @@
 // The array exists once per GPU (each device that loads the library holds its own copy until the process ends).
 // Its device address is looked up once per device with hipGetSymbolAddress and kept; host code never passes the
 // array's name to a kernel.  Every call on a GPU uses that GPU's one array: calls that overlap in time on one GPU
-// (different streams, or different threads) race on it.  Nothing in it has to start at zero: every record that the
-// finalizer reads is written by the vocabulary pass of the same call.
+// (different streams, or different threads) race on it.  Only the per-row ticket counters have to start at zero; each call
+// clears them first.  Every record that the finalizer reads is written by the vocabulary pass of the same call.
 #include <math.h>
 
 #include <mutex>
@@ -32,7 +32,8 @@ constexpr size_t kOffLogZb = kOffLogZ1 + up256((size_t)kNoAllocMaxRows * 8);
 constexpr size_t kOffGap = kOffLogZb + up256((size_t)kNoAllocMaxRows * 8);
 constexpr size_t kOffSecond = kOffGap + up256((size_t)kNoAllocMaxRows * 8);
 constexpr size_t kOffRowstat = kOffSecond + up256((size_t)kNoAllocMaxRows * 4);
-constexpr size_t kScratchBytes = kOffRowstat + up256((size_t)kNoAllocMaxRows * 12);
+constexpr size_t kOffTicket = kOffRowstat + up256((size_t)kNoAllocMaxRows * 12);
+constexpr size_t kScratchBytes = kOffTicket + up256((size_t)kNoAllocMaxRows * 4);
 static_assert(kScratchBytes <= (size_t)8 << 20, "the static scratch array is meant to stay modest");
 
 constexpr int kMaxDevices = 64;
@@ -42,6 +43,12 @@ char* g_scratch_ptr[kMaxDevices] = {};     // device address of `scratch` on eac
 }  // namespace
 
 static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+__global__ void clear_tickets_kernel(int32_t* tickets, int n)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) tickets[i] = 0;
+}
 
 namespace {
 
@@ -107,9 +114,15 @@ extern "C" smc_status smc_step_noalloc(const smc_config* cfg, void* hip_stream, 
     c.ws.d_gap = (double*)(base + kOffGap);
     c.ws.d_second = (int32_t*)(base + kOffSecond);
     c.ws.d_rowstat = (int32_t*)(base + kOffRowstat);
+    c.ws.row_ticket = (int32_t*)(base + kOffTicket);
     c.paged = PagedKV{};
     auto_shape(c.R, cfg->V, cfg->logits_dtype, &c.wg_waves, &c.n_split);
     c.mask_words = (cfg->N + 63) / 64;
-    return launch_vocab_pass(&c, d_logits, row_stride_elems, t, alpha_t, alpha_prev, beta, d_tokens_out) == hipSuccess
+    // The per-row ticket counters of the kernel must start at zero.  They return to zero by themselves, but the array is
+    // shared by every call on this GPU, so it is cleared here rather than trusted (a fill kernel, not a memset node: the
+    // call may be under stream capture).
+    hipLaunchKernelGGL(clear_tickets_kernel, dim3((unsigned)((R + 255) / 256)), dim3(256), 0, c.stream, c.ws.row_ticket, (int)R);
+    if (hipGetLastError() != hipSuccess) return SMC_E_HIP;
+    return launch_vocab_pass(&c, d_logits, row_stride_elems, t, alpha_t, alpha_prev, tau_t, d_tokens_out, nullptr) == hipSuccess
                ? SMC_OK : SMC_E_HIP;
 }

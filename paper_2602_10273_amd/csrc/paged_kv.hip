@@ -430,9 +430,10 @@ smc_status smc_paged_reindex(smc_ctx* ctx, const int32_t* d_anc, const int32_t* 
     const int N = cfg.N;
     // token history: whole 16-byte vectors of the first t columns, as in the dense reorder
     int hist_vecs = 0;
-    if (ctx->hist_bound && t > 0) {
+    if (ctx->hist_bound && (t > 0 || ctx->device_step)) {
         int64_t bytes = (((int64_t)t * 4) + 15) & ~15ll;
-        if (bytes > (int64_t)cfg.T_max * 4) bytes = (int64_t)cfg.T_max * 4;
+        // with the step kept on the device the host does not know how long the prefixes are: whole rows move
+        if (bytes > (int64_t)cfg.T_max * 4 || ctx->device_step) bytes = (int64_t)cfg.T_max * 4;
         hist_vecs = (int)(bytes / 16);
     }
     int hb = (int)(((int64_t)N * hist_vecs * 16 + 65535) / 65536);          // ~64 KiB of history per state workgroup

@@ -47,6 +47,10 @@ size_t layout(const smc_config* c, char* base, Workspace* w)
     p = take((size_t)c->B * 8); if (w) w->logZhat = (double*)p;
     p = take((size_t)c->B * 8); if (w) w->logZest = (double*)p;
     p = take(R * kMaxSplit * sizeof(Partial)); if (w) w->partials = (Partial*)p;
+    p = take(R * 4); if (w) w->row_ticket = (int32_t*)p;
+    p = take((size_t)c->B * 4); if (w) w->prompt_ticket = (int32_t*)p;
+    p = take(4); if (w) w->d_step = (int32_t*)p;
+    p = take(((size_t)c->T_max + 2) * 8); if (w) w->d_sched = (double*)p;
     p = take(R * 8); if (w) w->d_delta = (double*)p;
     p = take(R * 8); if (w) w->d_logZ1 = (double*)p;
     p = take(R * 8); if (w) w->d_logZb = (double*)p;
@@ -133,6 +137,9 @@ smc_status smc_init(const smc_config* cfg, void* d_workspace, size_t workspace_b
     c->resampler = 0;
     c->ancestor_order = 0;
     c->kv_skip_terminated = 0;
+    c->device_step = 0;
+    c->n_sched = 0;
+    c->sched_integer_power = 0;
     c->kv_bound = 0;
     c->hist_bound = 0;
     c->profiling = 0;
@@ -217,7 +224,25 @@ smc_status smc_step(smc_ctx* ctx, const void* d_logits, int64_t row_stride_elems
     if (!isfinite(tau_t)) return SMC_E_RANGE;
     const double beta = tau_t <= 0.0 ? alpha_t : 1.0 / tau_t;
     if (!(beta > 0.0) || !isfinite(beta) || beta > 1.0e4) return SMC_E_RANGE;
-    return launch_vocab_pass(ctx, d_logits, row_stride_elems, t, alpha_t, alpha_prev, beta, d_tokens_out) == hipSuccess
+    return launch_vocab_pass(ctx, d_logits, row_stride_elems, t, alpha_t, alpha_prev, tau_t, d_tokens_out, nullptr) == hipSuccess
+               ? SMC_OK : SMC_E_HIP;
+}
+
+smc_status smc_step_resample(smc_ctx* ctx, const void* d_logits, int64_t row_stride_elems, int32_t t, double alpha_t,
+                             double alpha_prev, double tau_t, int32_t* d_tokens_out, int32_t* d_anc_out,
+                             int32_t* d_resampled_out, double* d_ess_out)
+{
+    if (!ctx || !d_logits || !d_tokens_out || !d_anc_out || !d_resampled_out) return SMC_E_NULL;
+    const int esz = ctx->cfg.logits_dtype == SMC_BF16 ? 2 : 4;
+    if (row_stride_elems < ctx->cfg.V) return SMC_E_SHAPE;
+    if (!aligned16(d_logits) || (row_stride_elems * esz) % 16 != 0) return SMC_E_ALIGN;
+    if (t < 1 || t > ctx->cfg.T_max) return SMC_E_RANGE;
+    if (!(alpha_t > 0.0) || !(alpha_prev >= 0.0) || !isfinite(alpha_t) || !isfinite(alpha_prev)) return SMC_E_RANGE;
+    if (!isfinite(tau_t)) return SMC_E_RANGE;
+    const double beta = tau_t <= 0.0 ? alpha_t : 1.0 / tau_t;
+    if (!(beta > 0.0) || !isfinite(beta) || beta > 1.0e4) return SMC_E_RANGE;
+    const FusedResample f{d_anc_out, d_resampled_out, d_ess_out};
+    return launch_vocab_pass(ctx, d_logits, row_stride_elems, t, alpha_t, alpha_prev, tau_t, d_tokens_out, &f) == hipSuccess
                ? SMC_OK : SMC_E_HIP;
 }
 
@@ -350,6 +375,49 @@ smc_status smc_set_kv_skip_terminated(smc_ctx* ctx, int32_t enable)
     return SMC_OK;
 }
 
+smc_status smc_set_schedule(smc_ctx* ctx, const double* h_alpha, int32_t n)
+{
+    if (!ctx || !h_alpha) return SMC_E_NULL;
+    if (n < 2 || n > ctx->cfg.T_max + 2) return SMC_E_SHAPE;
+    if (!(h_alpha[0] >= 0.0) || !isfinite(h_alpha[0])) return SMC_E_RANGE;
+    for (int i = 1; i < n; ++i)
+        if (!(h_alpha[i] > 0.0) || !isfinite(h_alpha[i]) || h_alpha[i] > 1.0e4) return SMC_E_RANGE;
+    if (hipStreamSynchronize(ctx->stream) != hipSuccess) return SMC_E_HIP;
+    if (hipMemcpy(ctx->ws.d_sched, h_alpha, (size_t)n * 8, hipMemcpyHostToDevice) != hipSuccess) return SMC_E_HIP;
+    ctx->n_sched = n;
+    int P = integer_power(h_alpha[1]);
+    for (int i = 2; i < n && P; ++i)
+        if (h_alpha[i] != h_alpha[1]) P = 0;
+    ctx->sched_integer_power = P;
+    return SMC_OK;
+}
+
+smc_status smc_set_device_step(smc_ctx* ctx, int32_t enable, int32_t t)
+{
+    if (!ctx) return SMC_E_NULL;
+    if (enable < 0 || enable > 1) return SMC_E_RANGE;
+    if (enable && (t < 1 || t > ctx->cfg.T_max)) return SMC_E_RANGE;
+    if (enable && ctx->n_sched < 2) return SMC_E_STATE;            // the exponents have to be on the device too
+    if (hipStreamSynchronize(ctx->stream) != hipSuccess) return SMC_E_HIP;
+    if (enable && hipMemcpy(ctx->ws.d_step, &t, 4, hipMemcpyHostToDevice) != hipSuccess) return SMC_E_HIP;
+    ctx->device_step = enable;
+    return SMC_OK;
+}
+
+smc_status smc_get_device_step(smc_ctx* ctx, int32_t* h_t)
+{
+    if (!ctx || !h_t) return SMC_E_NULL;
+    if (hipStreamSynchronize(ctx->stream) != hipSuccess) return SMC_E_HIP;
+    return hipMemcpy(h_t, ctx->ws.d_step, 4, hipMemcpyDeviceToHost) == hipSuccess ? SMC_OK : SMC_E_HIP;
+}
+
+smc_status smc_advance_step(smc_ctx* ctx)
+{
+    if (!ctx) return SMC_E_NULL;
+    if (!ctx->device_step) return SMC_E_STATE;
+    return launch_advance_step(ctx) == hipSuccess ? SMC_OK : SMC_E_HIP;
+}
+
 smc_status smc_set_resampler(smc_ctx* ctx, int32_t scheme)
 {
     if (!ctx) return SMC_E_NULL;
@@ -406,7 +474,7 @@ smc_status smc_set_tuning(smc_ctx* ctx, int32_t n_split, int32_t dense, int32_t 
 {
     if (!ctx) return SMC_E_NULL;
     if (n_split < 0 || n_split > kMaxSplit) return SMC_E_RANGE;
-    if (wg_waves != 0 && wg_waves != 4 && wg_waves != 16) return SMC_E_RANGE;
+    if (wg_waves != 0 && wg_waves != 4 && wg_waves != 8 && wg_waves != 16) return SMC_E_RANGE;
     if (dense < 0 || dense > 1) return SMC_E_RANGE;
     int aw, as;
     auto_shape(ctx->R, ctx->cfg.V, ctx->cfg.logits_dtype, &aw, &as);

@@ -40,6 +40,42 @@ struct GatherPlan {
     int32_t pad[3];
 };
 
+// What one wave needs to normalise and resample one prompt (a3 + a4).
+struct ResampleArgs {
+    int N;
+    double kappa;
+    uint32_t key0, key1;
+    int scheme, order;
+    int32_t* anc;                 // [R] out: ancestors as global row indices
+    int32_t* resampled;           // [B] out
+    double* ess_out;              // [B] out, nullable
+    double* logZhat;              // [B] in/out, nullable: running log of the normalising-constant estimate
+};
+
+// Outputs of a resampling folded into the vocabulary-pass launch.
+struct FusedResample { int32_t* anc; int32_t* resampled; double* ess_out; };
+
+// Everything the vocabulary-pass kernel and its tail (row finalizer, optional resampling) take.
+struct StepArgs {
+    const void* logits; int64_t row_stride_bytes; int V;
+    uint32_t key0, key1;
+    // the step's scalars by value ...
+    uint32_t step; double alpha_t, alpha_prev, beta, tau_by_value;
+    // ... or, when d_step is not null, from the device: the step counter and the exponent schedule alpha[0..n_sched)
+    const int32_t* d_step; const double* d_sched; int n_sched;
+    int n_split, vecs_per_split;
+    Partial* partials;            // [R * kMaxSplit]
+    int32_t* row_ticket;          // [R] slices of a row that have delivered their record (returns to 0)
+    // row state and outputs of the finalizer
+    double* logW; double* cumlogp; const int32_t* parity; int32_t* const* histAB; int T_max; int32_t* tokens_out;
+    double* d_delta; double* d_logZ1; double* d_logZb; double* d_gap; int32_t* d_second; int32_t* d_rowstat;
+    int eos_id; int32_t* done;
+    // resampling folded into the same launch
+    int fuse_resample;
+    int32_t* prompt_ticket;       // [B] rows of a prompt that are final (returns to 0)
+    ResampleArgs rs;
+};
+
 struct Workspace {                // device pointers carved out of the caller's workspace
     double* logW;                 // [R]
     double* cumlogp;              // [R]
@@ -48,6 +84,10 @@ struct Workspace {                // device pointers carved out of the caller's 
     double* logZhat;              // [B] log of the product of the mean unnormalised weights at the resampling times
     double* logZest;              // [B] read-out scratch of smc_get_log_zhat
     Partial* partials;            // [R * kMaxSplit]
+    int32_t* row_ticket;          // [R] ticket counters of the vocabulary pass (zero between launches)
+    int32_t* prompt_ticket;       // [B]
+    int32_t* d_step;              // [1] device-resident step counter (smc_set_device_step)
+    double* d_sched;              // [T_max + 2] device-resident exponent schedule alpha_0 .. (smc_set_schedule)
     double* d_delta;              // [R] diagnostics of the last step
     double* d_logZ1;              // [R]
     double* d_logZb;              // [R]
@@ -93,6 +133,9 @@ struct smc_ctx {
     int resampler;                // 0 systematic (the paper's), 1 stratified, 2 multinomial, 3 residual
     int ancestor_order;           // 0 as drawn, 1 survivors stay in place
     int kv_skip_terminated;       // 1: the reorder moves no KV bytes for descendants of a terminated ancestor
+    int device_step;              // 1: kernels read the step and the exponents from the device (graph replay advances)
+    int n_sched;                  // entries of the device-resident schedule
+    int sched_integer_power;      // the integer every schedule entry from index 1 on equals (1..8 except 7), else 0
     int kv_bound;
     std::vector<void*> h_kvA, h_kvB, h_pools;   // host copies of the registered device pointers (kernel arguments)
     int hist_bound;
@@ -137,8 +180,11 @@ void auto_shape(int R, int V, int dtype, int* wg_waves, int* n_split);
 
 // launchers (each enqueues on ctx->stream; returns hipGetLastError())
 hipError_t launch_init_state(smc_ctx* c);
+// fused: not null -> the wave that completes a prompt also resamples it (a3 + a4 in the same launch)
 hipError_t launch_vocab_pass(smc_ctx* c, const void* logits, int64_t row_stride, int t, double alpha_t,
-                             double alpha_prev, double beta, int32_t* tokens_out);
+                             double alpha_prev, double tau_t, int32_t* tokens_out, const FusedResample* fused);
+hipError_t launch_advance_step(smc_ctx* c);
+int integer_power(double beta);   // the integer-exponent kernel instantiation for beta, or 0 for the generic one
 hipError_t launch_ess(smc_ctx* c, const double* logW, double* ess_out, double* lognormw_out);
 hipError_t launch_resample(smc_ctx* c, double* logW, int t, int32_t* anc, int32_t* resampled, double* ess_out);
 hipError_t launch_reindex(smc_ctx* c, const int32_t* anc, const int32_t* resampled, int valid_len, int t);

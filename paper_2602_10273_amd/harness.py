@@ -80,6 +80,11 @@ class Session:
     def step(self, logits, t, alpha_t, alpha_prev, tau_t=-1.0):
         smc.smc_step(self.ctx, logits, logits.stride(0), t, alpha_t, alpha_prev, tau_t, self.tokens)
 
+    def step_resample(self, logits, t, alpha_t, alpha_prev, tau_t=-1.0):
+        """a0..a4 in one launch (the same results as step() followed by resample())."""
+        smc.smc_step_resample(self.ctx, logits, logits.stride(0), t, alpha_t, alpha_prev, tau_t, self.tokens, self.anc,
+                              self.resampled, self.ess)
+
     def compute_ess(self):
         smc.smc_ess(self.ctx, self.ess, self.lognormw)
 

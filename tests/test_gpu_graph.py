@@ -2,14 +2,17 @@
 
 The library keeps no host-side state between these calls and records no memset nodes, so the sequence can be
 captured once and replayed; every replay is checked against a second context that makes the same calls eagerly, with
-eager work and synchronisations between the replays.  (The step number t is a launch argument, so a captured step
-redraws the same random numbers: the replays here repeat step t on purpose.)"""
+eager work and synchronisations between the replays.  With by-value arguments a captured step repeats step t (the
+first test does so on purpose); with the step and the exponent schedule kept on the device the same capture advances
+from token to token (the second test: T distinct steps from one graph, against eager calls and the oracle)."""
 import numpy as np
 import pytest
 import torch
 
+from oracle import reference as orc
+from paper_2602_10273_amd import binding as smc
 from paper_2602_10273_amd import synth
-from paper_2602_10273_amd.harness import Session
+from paper_2602_10273_amd.harness import Session, to_device_logits
 
 pytestmark = pytest.mark.gpu
 
@@ -61,4 +64,58 @@ def test_graph_replay_matches_eager(paged):
             assert np.array_equal(a[k], b[k]), (it, k)
         n_res += int(a["flag"].sum())
     assert n_res > 0
+    eager.close(); graph.close()
+
+
+@pytest.mark.parametrize("name,ramp", [("cfg2", 0), ("cfg4", 6)])
+def test_graph_with_device_step_advances_like_eager_steps_and_the_oracle(name, ramp):
+    """One capture of [smc_step_resample, smc_kv_reindex, smc_advance_step], replayed T times while the decoder's
+    logits buffer is refilled in between: every replay runs the next token (its own random numbers, its own exponent
+    from the uploaded schedule) and matches both eager by-value calls on a second context and the CPU oracle."""
+    T = 10
+    w = synth.scaled(synth.WORKLOADS[name], B=5, N=8, V=8200, layers=1, H=2, S=16, D=64, ramp=ramp)
+    kv = synth.kv_numpy(w, 3)
+    side = torch.cuda.Stream()
+    eager = Session(w.B, w.N, w.V, 16, w.dtype, w.kappa, 5, kv=kv)
+    graph = Session(w.B, w.N, w.V, 16, w.dtype, w.kappa, 5, kv=kv, stream=side)
+    o = orc.OracleSMC(w.B, w.N, w.V, 16, w.kappa, 5, w.dtype, kv=[k.copy() for k in kv])
+    smc.smc_set_schedule(graph.ctx, [w.alpha_at(t) for t in range(0, T + 2)])
+    smc.smc_set_device_step(graph.ctx, 1, 1)
+    x_buf = to_device_logits(synth.logits_numpy(w, 1, 5), w.dtype)            # the buffer the "decoder" writes into
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        # by-value t / alpha arguments are ignored in this mode (1 and 1.0 are placeholders that pass validation)
+        graph.step_resample(x_buf, 1, 1.0, 1.0)
+        graph.reindex(w.S, 1)
+        smc.smc_advance_step(graph.ctx)
+    n_res = 0
+    for t in range(1, T + 1):
+        x = synth.logits_numpy(w, t, 5)
+        x_buf.copy_(to_device_logits(x, w.dtype))
+        torch.cuda.synchronize()
+        g.replay()
+        eager.step(x_buf, t, w.alpha_at(t), w.alpha_at(t - 1)); eager.resample(t); eager.reindex(w.S, t)
+        want = o.step(x, t, w.alpha_at(t), w.alpha_at(t - 1))
+        anc_ref, flag_ref, _ = o.resample(t)
+        o.reindex(anc_ref, flag_ref, w.S, t)
+        torch.cuda.synchronize()
+        assert smc.smc_get_device_step(graph.ctx) == t + 1
+        for f in ("tokens", "anc", "resampled"):
+            assert torch.equal(getattr(eager, f), getattr(graph, f)), (t, f)
+        tie = want["gap"] < 1e-6
+        assert np.array_equal(graph.tokens.cpu().numpy()[~tie], want["tokens"][~tie])
+        assert np.array_equal(graph.anc.cpu().numpy(), anc_ref) and np.array_equal(graph.resampled.cpu().numpy(), flag_ref)
+        a, b = eager.state(), graph.state()
+        if ramp == 0:                   # same kernel instantiation on both sides: bit-identical state
+            assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+        else:                           # under a ramp the captured launch uses the generic-exponent instantiation throughout
+            assert np.abs(a[0] - b[0]).max() < 1e-5 and np.abs(a[1] - b[1]).max() < 1e-5
+        assert np.array_equal(a[2], b[2])
+        assert np.abs(b[0] - o.logW).max() < 1e-4 and np.abs(b[1] - o.cumlogp).max() < 1e-4
+        assert np.array_equal(graph.live_hist()[:, :t], o.hist[:, :t])
+        assert np.array_equal(graph.live_kv(0), o.kv[0])
+        n_res += int(flag_ref.sum())
+    assert n_res > 0
+    smc.smc_set_device_step(graph.ctx, 0, 1)
     eager.close(); graph.close()
