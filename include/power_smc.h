@@ -225,7 +225,7 @@ smc_status smc_set_state(smc_ctx* ctx, const double* h_logW, const double* h_cum
 
 /* Synchronous per-row diagnostics of the last smc_step (host arrays of R entries, any may be NULL):
  * increment a2, log Z_1 = LSE(l), log Z_beta = LSE(l/tau), runner-up token, key gap between winner and
- * runner-up (in fp64), and h_counters[4] = {rows with non-finite sums, candidates scored, candidate-queue
+ * runner-up (from fp64 keys where the call is closer than 1e-3, else the fp32 estimate that decided it), and h_counters[4] = {rows with non-finite sums, candidates scored, candidate-queue
  * drains, vocabulary entries seen}, all of that one step. */
 smc_status smc_get_diag(smc_ctx* ctx, double* h_delta, double* h_logZ1, double* h_logZb, int32_t* h_second,
                         double* h_gap, uint64_t* h_counters);

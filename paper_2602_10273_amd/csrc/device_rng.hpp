@@ -73,32 +73,64 @@ __device__ __forceinline__ double gumbel_f64(uint32_t x)
     return -log(E);
 }
 
-__device__ __forceinline__ float wave_max_f32(float v)
+// ---- wave64 reductions through the data-parallel-primitive lane network (no LDS round trips) ----------------------
+// Six combine steps: neighbours within quads (quad_perm [1,0,3,2], [2,3,0,1]), rotations by 4 and 8 within each row of
+// 16 lanes, then the last lane of a row broadcast into the next row (row_bcast:15) and lane 31 into the upper half
+// (row_bcast:31).  After them lane 63 holds the combination of all 64 lanes; it is handed to every lane through a
+// scalar register.  All 64 lanes must be active.  The order of combination differs from a butterfly, which only
+// matters for the rounding of floating-point sums.
+template <int CTRL> __device__ __forceinline__ uint32_t dpp_move(uint32_t v)
 {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
-    return v;
+    return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, CTRL, 0xF, 0xF, false);
 }
-__device__ __forceinline__ float wave_sum_f32(float v)
+template <int CTRL> __device__ __forceinline__ float dpp_move(float v) { return __uint_as_float(dpp_move<CTRL>(__float_as_uint(v))); }
+template <int CTRL> __device__ __forceinline__ int dpp_move(int v) { return (int)dpp_move<CTRL>((uint32_t)v); }
+template <int CTRL> __device__ __forceinline__ double dpp_move(double v)
 {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-    return v;
+    const unsigned long long b = (unsigned long long)__double_as_longlong(v);
+    const uint32_t lo = dpp_move<CTRL>((uint32_t)b), hi = dpp_move<CTRL>((uint32_t)(b >> 32));
+    return __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
 }
-__device__ __forceinline__ double wave_max_f64(double v)
+__device__ __forceinline__ float last_lane(float v) { return __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(v), 63)); }
+__device__ __forceinline__ int last_lane(int v) { return __builtin_amdgcn_readlane(v, 63); }
+__device__ __forceinline__ uint32_t last_lane(uint32_t v) { return (uint32_t)__builtin_amdgcn_readlane((int)v, 63); }
+__device__ __forceinline__ double last_lane(double v)
 {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fmax(v, __shfl_xor(v, o));
-    return v;
-}
-__device__ __forceinline__ double wave_sum_f64(double v)
-{
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-    return v;
+    const unsigned long long b = (unsigned long long)__double_as_longlong(v);
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)b, 63);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(b >> 32), 63);
+    return __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
 }
 
+template <class T, class Op> __device__ __forceinline__ T wave_reduce(T v, Op op)
+{
+    v = op(v, dpp_move<0xB1>(v));      // quad_perm:[1,0,3,2]
+    v = op(v, dpp_move<0x4E>(v));      // quad_perm:[2,3,0,1]
+    v = op(v, dpp_move<0x124>(v));     // row_ror:4
+    v = op(v, dpp_move<0x128>(v));     // row_ror:8
+    v = op(v, dpp_move<0x142>(v));     // row_bcast:15
+    v = op(v, dpp_move<0x143>(v));     // row_bcast:31
+    return last_lane(v);
+}
+
+__device__ __forceinline__ float wave_max_f32(float v) { return wave_reduce(v, [](float a, float b) { return fmaxf(a, b); }); }
+__device__ __forceinline__ float wave_sum_f32(float v) { return wave_reduce(v, [](float a, float b) { return a + b; }); }
+__device__ __forceinline__ double wave_max_f64(double v) { return wave_reduce(v, [](double a, double b) { return fmax(a, b); }); }
+__device__ __forceinline__ double wave_sum_f64(double v) { return wave_reduce(v, [](double a, double b) { return a + b; }); }
+__device__ __forceinline__ int wave_sum_i32(int v) { return wave_reduce(v, [](int a, int b) { return a + b; }); }
+__device__ __forceinline__ int wave_min_i32(int v) { return wave_reduce(v, [](int a, int b) { return a < b ? a : b; }); }
+
 __device__ __forceinline__ int lane_id() { return __lane_id(); }
+
+// value of `v` on lane `src`, where src is the same on every lane (a scalar read, no LDS round trip)
+__device__ __forceinline__ int read_lane(int v, int src) { return __builtin_amdgcn_readlane(v, __builtin_amdgcn_readfirstlane(src)); }
+__device__ __forceinline__ float read_lane(float v, int src) { return __uint_as_float((uint32_t)read_lane((int)__float_as_uint(v), src)); }
+__device__ __forceinline__ double read_lane(double v, int src)
+{
+    const unsigned long long b = (unsigned long long)__double_as_longlong(v);
+    const uint32_t lo = (uint32_t)read_lane((int)(uint32_t)b, src), hi = (uint32_t)read_lane((int)(uint32_t)(b >> 32), src);
+    return __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
+}
 
 // number of set bits of a wave mask below this lane
 __device__ __forceinline__ int mask_rank(unsigned long long m)

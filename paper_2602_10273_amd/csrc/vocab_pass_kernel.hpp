@@ -157,9 +157,7 @@ __device__ __forceinline__ void block_epilogue(float beta, float m_wave, float M
             red_cl[wave][1] = sec_b ? top.b.l : top.a.l; red_cg[wave][1] = sec_b ? top.b.g : top.a.g;
             red_ci[wave][1] = sec_b ? top.b.i : top.a.i;
         }
-        unsigned long long sc = n_scored;
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) sc += __shfl_xor(sc, o);
+        const int sc = wave_sum_i32((int)n_scored);
         if (lane == 0) {
             if (lb < 0) red_ci[wave][0] = -1;
             if (l2 < 0) red_ci[wave][1] = -1;
@@ -178,9 +176,8 @@ __device__ __forceinline__ void block_epilogue(float beta, float m_wave, float M
         // slice is like that the difference of the references is not a number, hence the explicit zero
         const float t1 = wave_sum_f32(hw && wM1 > -INFINITY ? red_f[lane][1] * fast_exp2(wM1 - gM1) : 0.f);
         const float tb = wave_sum_f32(hw && wMb > -INFINITY ? red_f[lane][3] * fast_exp2(wMb - gMb) : 0.f);
-        uint32_t nsc = hw ? red_n[lane][0] : 0u, ndr = hw ? red_n[lane][1] : 0u;
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) { nsc += __shfl_xor(nsc, o); ndr += __shfl_xor(ndr, o); }
+        const uint32_t nsc = (uint32_t)wave_sum_i32(hw ? (int)red_n[lane][0] : 0);
+        const uint32_t ndr = (uint32_t)wave_sum_i32(hw ? (int)red_n[lane][1] : 0);
         // candidates: lane c < 2*NW holds candidate (c & 1) of wave (c >> 1)
         const bool hc = lane < 2 * NW;
         const float cl = hc ? red_cl[lane >> 1][lane & 1] : 0.f, cg = hc ? red_cg[lane >> 1][lane & 1] : 0.f;
@@ -189,8 +186,8 @@ __device__ __forceinline__ void block_epilogue(float beta, float m_wave, float M
         int lb, l2; bool sec_b;
         wave_best_two(key, NEG, ci >= 0, lb, l2, sec_b);
         const int sb_lane = lb < 0 ? 0 : lb, s2_lane = (l2 < 0 || sec_b) ? 0 : l2;
-        const float l1v = __shfl(cl, sb_lane), g1v = __shfl(cg, sb_lane); const int32_t i1v = __shfl(ci, sb_lane);
-        const float l2v = __shfl(cl, s2_lane), g2v = __shfl(cg, s2_lane); const int32_t i2v = __shfl(ci, s2_lane);
+        const float l1v = read_lane(cl, sb_lane), g1v = read_lane(cg, sb_lane); const int32_t i1v = read_lane(ci, sb_lane);
+        const float l2v = read_lane(cl, s2_lane), g2v = read_lane(cg, s2_lane); const int32_t i2v = read_lane(ci, s2_lane);
         if (lane == 0) {
             Partial p;
             p.M1 = gM1; p.s1 = t1; p.Mb = gMb; p.sb = tb;
@@ -230,53 +227,87 @@ __device__ __forceinline__ StepScalars step_scalars(const StepArgs& a)
 // Gumbel-max draw with fp64 keys beta*l + g (ties to the lower index), then applies the boundary reweight of
 // exponent bridging (Sec. 5.3) and the increment alpha*log p(y) - log q(y) (Eq. "inc").
 // pp: the row's n_split partial records (global memory, or LDS for a row of one slice).
-__device__ inline void finalize_row(const StepArgs& a, const StepScalars& sc, uint32_t row, const Partial* pp, int n_split)
+// What the finalizer needs of a row's state.  Read when the kernel starts, long before it is used: a dependent global read
+// at the end of the kernel would wait behind the whole chip's logit stream.
+struct RowState { double logW, cumlogp; int32_t* hist; };
+
+__device__ __forceinline__ RowState load_row_state(const StepArgs& a, uint32_t row)
+{
+    RowState r;
+    r.logW = a.logW[row];
+    r.cumlogp = a.cumlogp[row];
+    r.hist = a.histAB ? a.histAB[a.parity[row]] : nullptr;
+    return r;
+}
+
+__device__ inline void finalize_row(const StepArgs& a, const StepScalars& sc, uint32_t row, const Partial* pp, int n_split,
+                                    const RowState& rs)
 {
     const int lane = lane_id();
     const double beta = sc.beta, alpha_t = sc.alpha_t, alpha_prev = sc.alpha_prev;
     const uint32_t step = sc.step;
 
-    // sums
+    // sums: the references are integer powers of two, so bringing a slice to the common reference is exact
     double M1 = -1e300, Mb = -1e300, s1 = 0.0, sb = 0.0;
     if (lane < n_split) { M1 = pp[lane].M1; Mb = pp[lane].Mb; s1 = pp[lane].s1; sb = pp[lane].sb; }
     const double gM1 = wave_max_f64(M1), gMb = wave_max_f64(Mb);
-    const double S1 = wave_sum_f64(lane < n_split ? s1 * exp2(M1 - gM1) : 0.0);
-    const double Sb = wave_sum_f64(lane < n_split ? sb * exp2(Mb - gMb) : 0.0);
+    const double S1 = wave_sum_f64(lane < n_split && M1 > -1e300 ? ldexp(s1, (int)fmax(M1 - gM1, -2000.0)) : 0.0);
+    const double Sb = wave_sum_f64(lane < n_split && Mb > -1e300 ? ldexp(sb, (int)fmax(Mb - gMb, -2000.0)) : 0.0);
     constexpr double LN2 = 0.69314718055994530942;
-    const double logZ1 = gM1 * LN2 + log(S1);
-    const double logZb = gMb * LN2 + log(Sb);
+    // the two logarithms side by side on two lanes (one pass through the fp64 log instead of two in a row)
+    const double lg = log((lane & 1) ? Sb : S1);
+    const double logZ1 = gM1 * LN2 + read_lane(lg, 0);
+    const double logZb = gMb * LN2 + read_lane(lg, 1);
 
-    int32_t nsc = 0, ndr = 0;
-    if (lane < n_split) { nsc = pp[lane].n_scored; ndr = pp[lane].n_drains; }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) { nsc += __shfl_xor(nsc, o); ndr += __shfl_xor(ndr, o); }
+    const int32_t nsc = wave_sum_i32(lane < n_split ? pp[lane].n_scored : 0);
+    const int32_t ndr = wave_sum_i32(lane < n_split ? pp[lane].n_drains : 0);
 
-    // finalists: lane c -> candidate (c & 1) of split (c >> 1)
+    // finalists: lane c -> candidate (c & 1) of split (c >> 1).  The finalist's logit and fp32 Gumbel variate travel in
+    // the partial record (the logit is an exact copy: bf16 and fp32 both fit a float), so no second read of the logits.
     int32_t idx = -1;
-    if (lane < 2 * n_split) idx = (lane & 1) ? pp[lane >> 1].i2 : pp[lane >> 1].i1;
-    if (idx >= a.V) idx = -1;                          // never trust an index outside the row, whatever the partial holds
-    double key = -INFINITY, lv = 0.0;
-    if (idx >= 0) {
-        // the finalist's logit travels in the partial record (an exact copy: bf16 and fp32 both fit a float), so no
-        // second, dependent read of the logits is needed here
-        lv = (double)((lane & 1) ? pp[lane >> 1].l2 : pp[lane >> 1].l1);
-        const U4 blk = philox4x32_10((uint32_t)idx >> 2, row, step, 0u, a.key0, a.key1);
-        key = beta * lv + gumbel_f64(pick_word(blk, (uint32_t)idx & 3u));
+    float lf = 0.f, gf = 0.f;
+    if (lane < 2 * n_split) {
+        const Partial& q = pp[lane >> 1];
+        idx = (lane & 1) ? q.i2 : q.i1;
+        lf = (lane & 1) ? q.l2 : q.l1;
+        gf = (lane & 1) ? q.g2 : q.g1;
     }
-    // winner: max key, lowest index among equals
-    const double k1 = wave_max_f64(key);
-    int32_t cand = (idx >= 0 && key == k1) ? idx : 0x7FFFFFFF;
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) cand = min(cand, __shfl_xor(cand, o));
-    const int32_t y = cand;
-    const double key2v = (idx >= 0 && idx != y) ? key : -INFINITY;
-    const double k2 = wave_max_f64(key2v);
-    int32_t cand2 = (idx >= 0 && idx != y && key == k2) ? idx : 0x7FFFFFFF;
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) cand2 = min(cand2, __shfl_xor(cand2, o));
-    const unsigned long long ymask = __ballot(idx == y);
-    const int ylane = __ffsll((long long)ymask) - 1;
-    const double ly = __shfl(lv, ylane < 0 ? 0 : ylane);
+    if (idx >= a.V) idx = -1;                          // never trust an index outside the row, whatever the partial holds
+    const bool has = idx >= 0;
+    // fp32 keys relative to the largest finalist logit (differences of logits are exact or nearly so)
+    const float lref = wave_max_f32(has ? lf : -3.4e38f);
+    const float kf = has ? fmaf((float)beta, lf - lref, gf) : -3.4e38f;
+    const float kf1 = wave_max_f32(kf);
+    const unsigned long long lead = __ballot(has && kf == kf1);
+    const int lead_lane = lead ? __ffsll((long long)lead) - 1 : 0;
+    const float kf2 = wave_max_f32(lane == lead_lane ? -3.4e38f : kf);
+    int32_t y, second;
+    double gap, ly;
+    // The fp32 keys carry an error of a few 1e-7; a lead of more than 1e-3 decides the draw.  Closer calls (and rows
+    // with no finalist) are re-ranked with fp64 keys beta*l + g from the random stream, ties to the lower index --
+    // the arithmetic of the plain definition.
+    if (lead != 0ull && (lead & (lead - 1)) == 0ull && kf1 - kf2 > 1.0e-3f) {
+        y = read_lane(idx, lead_lane);
+        ly = (double)read_lane(lf, lead_lane);
+        const unsigned long long runner = __ballot(has && lane != lead_lane && kf == kf2);
+        second = runner ? read_lane(idx, __ffsll((long long)runner) - 1) : -1;
+        gap = runner ? (double)(kf1 - kf2) : (double)INFINITY;
+    } else {
+        double key = -INFINITY;
+        const double lv = (double)lf;
+        if (has) {
+            const U4 blk = philox4x32_10((uint32_t)idx >> 2, row, step, 0u, a.key0, a.key1);
+            key = beta * lv + gumbel_f64(pick_word(blk, (uint32_t)idx & 3u));
+        }
+        const double k1 = wave_max_f64(key);
+        y = wave_min_i32((has && key == k1) ? idx : 0x7FFFFFFF);       // max key, lowest index among equals
+        const double k2 = wave_max_f64((has && idx != y) ? key : -INFINITY);
+        const int32_t c2 = wave_min_i32((has && idx != y && key == k2) ? idx : 0x7FFFFFFF);
+        second = c2 == 0x7FFFFFFF ? -1 : c2;
+        gap = k1 - k2;
+        const unsigned long long ymask = __ballot(idx == y);
+        ly = read_lane(lv, ymask ? __ffsll((long long)ymask) - 1 : 0);
+    }
 
     if (lane == 0) {
         const bool ok = (y != 0x7FFFFFFF) && isfinite(logZ1) && isfinite(logZb);
@@ -284,18 +315,16 @@ __device__ inline void finalize_row(const StepArgs& a, const StepScalars& sc, ui
         const double logp = ly - logZ1;
         const double logq = beta * ly - logZb;
         const double delta = alpha_t * logp - logq;
-        double w = a.logW[row] + (alpha_t - alpha_prev) * a.cumlogp[row];  // stage boundary on the prefix y_{1:t-1}
+        double w = rs.logW + (alpha_t - alpha_prev) * rs.cumlogp;          // stage boundary on the prefix y_{1:t-1}
         w += delta;
         a.logW[row] = w;
-        a.cumlogp[row] += logp;
+        a.cumlogp[row] = rs.cumlogp + logp;
         a.tokens_out[row] = tok;
-        if (a.histAB && step >= 1u && step <= (uint32_t)a.T_max) {   // (a device-resident step may have run past the end)
-            int32_t* h = a.histAB[a.parity[row]];
-            if (h) h[(int64_t)row * a.T_max + (step - 1)] = tok;
-        }
+        // (a device-resident step may have run past the end of the history)
+        if (rs.hist && step >= 1u && step <= (uint32_t)a.T_max) rs.hist[(int64_t)row * a.T_max + (step - 1)] = tok;
         a.d_delta[row] = delta; a.d_logZ1[row] = logZ1; a.d_logZb[row] = logZb;
-        a.d_gap[row] = k1 - k2;
-        a.d_second[row] = cand2 == 0x7FFFFFFF ? -1 : cand2;
+        a.d_gap[row] = gap;
+        a.d_second[row] = second;
         a.d_rowstat[3 * row] = ok ? 0 : 1; a.d_rowstat[3 * row + 1] = nsc; a.d_rowstat[3 * row + 2] = ndr;
         if (a.eos_id >= 0 && ok && tok == a.eos_id) a.done[row] = 1;
     }
@@ -327,7 +356,7 @@ __device__ inline void after_row_final(const StepArgs& a, const StepScalars& sc,
         __threadfence();                               // this row's weight is visible before the ticket is
         tk = atomicAdd(&a.prompt_ticket[b], 1);
     }
-    tk = __shfl(tk, 0);
+    tk = __builtin_amdgcn_readfirstlane(tk);
     if (tk != a.rs.N - 1) return;
     if (lane == 0) a.prompt_ticket[b] = 0;             // nobody else touches it until the next step
     __threadfence();                                   // the other rows' weights, written by other workgroups
@@ -347,11 +376,16 @@ __global__ __launch_bounds__(NW * kWave, 4) void vocab_pass_kernel(const StepArg
 {
     constexpr int EPV = Elems<DT>::kPerVec;
     constexpr int QPV = EPV / 4;                       // Philox blocks (four entries each) per vector
-    constexpr int UNROLL = 4;                          // 16-byte vectors per thread and batch (two batches in flight)
+    constexpr int UNROLL = DT == SMC_BF16 ? 4 : 8;     // 16-byte loads per thread in flight
     constexpr int THREADS = NW * kWave;
     constexpr int kRingV = 256;                        // queued vectors per wave (power of two, >= 2 wave-widths)
+    constexpr int kRingE = 128;                        // queued single entries per wave (power of two, 2 wave-widths)
+    // A drain that finds more than this many entries still above the bound scores its vectors as they are (one Philox
+    // block serves the four entries of a quad); fewer are compacted into the entry ring first, so that every lane of
+    // a scoring pass has an entry to score.  The two costs meet at about 2.5 entries per lane.
+    constexpr int kScoreAsVectors = 160;
     // LDS: the candidate rings while streaming; afterwards the same bytes serve the resampling of a prompt
-    constexpr int kRingBytes = DENSE ? 0 : NW * kRingV * 20;
+    constexpr int kRingBytes = DENSE ? 0 : NW * (kRingV * 20 + kRingE * 8);
     constexpr int kTailBytes = 2 * SMC_MAX_PARTICLES * 8 + 16;
     constexpr int kLdsBytes = kRingBytes > kTailBytes ? kRingBytes : kTailBytes;
     __shared__ __align__(16) unsigned char lds[kLdsBytes];
@@ -372,11 +406,14 @@ __global__ __launch_bounds__(NW * kWave, 4) void vocab_pass_kernel(const StepArg
     }
     uint4* const ring_raw = reinterpret_cast<uint4*>(lds) + (DENSE ? 0 : wave * kRingV);
     uint32_t* const ring_idx = reinterpret_cast<uint32_t*>(lds + (DENSE ? 0 : NW * kRingV * 16)) + (DENSE ? 0 : wave * kRingV);
+    uint2* const ring_ent = reinterpret_cast<uint2*>(lds + (DENSE ? 0 : NW * kRingV * 20)) + (DENSE ? 0 : wave * kRingE);
     const char* rowp = (const char*)a.logits + (int64_t)row * a.row_stride_bytes;
     const int V = a.V;
     const uint32_t key0 = a.key0, key1 = a.key1, step = sc.step;
     if (tid == 0) wg_bound = enc_bound(-INFINITY);
     __syncthreads();
+    RowState row_state{};
+    if (wave == 0) row_state = load_row_state(a, row);    // wave-uniform (scalar) reads, consumed by the tail
 
     const int nvec_full = V / EPV;                      // vectors wholly inside the row
     const int nvec = (V + EPV - 1) / EPV;
@@ -387,20 +424,43 @@ __global__ __launch_bounds__(NW * kWave, 4) void vocab_pass_kernel(const StepArg
     const float beta_l2e = beta * kLog2e;
     const float window = (kGumbelMax - kGumbelMin + kKeyMargin) / beta;   // in logit units
 
+    constexpr uint32_t kPadWord = DT == SMC_BF16 ? 0xFF80FF80u : 0xFF800000u;      // -inf in every element
+
     // wave-uniform running state
     float m = -3.0e38f;            // running max of the logits seen by this wave
-    float M1 = -INFINITY, Mb = -INFINITY;   // power-of-two references (integers): M1 >= m*log2e, Mb >= m*beta*log2e
+    // power-of-two references (integers): M1 >= m*log2e, Mb >= m*beta*log2e.  Finite from the start, so that a masked
+    // (-inf) entry met before any finite one has a well-defined exponent of -inf
+    float M1 = -3.0e38f, Mb = -3.0e38f;
     float thr = -3.4e38f;          // entries below thr cannot win
     float published = -3.4e38f;    // what this wave last wrote to the row's shared bound
     float c1 = 0.f, cb = 0.f;      // c1 = M1 - m*log2e, cb = Mb - m*beta*log2e, both >= 0
     float s1 = 0.f, sb = 0.f;      // per-lane sums relative to the references
-    int q_head = 0, q_count = 0;
+    float thr_rel = -3.4e38f;      // the filter bound in the units the stream works in, rounded down: thr - m where the
+                                   // stream forms d = x - m (fp32 rows), thr*log2e - M1 where it forms t = x*log2e - M1 (bf16 rows)
+    float t_max = -3.4e38f;        // bf16 rows: m in those units, t_max = m*log2e - M1
+    int q_head = 0, q_count = 0;   // ring of queued vectors
+    int e_head = 0, e_count = 0;   // ring of queued single entries (always < 64 between drains)
     unsigned long long n_scored = 0, n_drains = 0;
     LaneTop2 top; top.init();
 
     auto lower = [](float b) { return b - fabsf(b) * 4e-7f; };    // a few ulps down: never drop a possible winner
 
-    auto raise_max = [&](float nm) {                    // nm > m, wave-uniform
+    // thr in units relative to the running maximum, with the rounding of both subtractions on the safe side
+    // bf16 rows take the exponent straight from the logit, t = fma(x, log2e, -M1): one instruction less per entry than
+    // forming x - m first.  The product is exact inside the fma, so the only error is that of the fp32 constant,
+    // 2^(x*kLog2eLow); its bulk 2^(m*kLog2eLow) is a per-wave factor applied to the sums at the end, what remains is
+    // below 1e-6 for entries within a hundred units of the maximum (others add nothing).  fp32 rows, whose magnitudes
+    // are unbounded and whose stream is bound by HBM anyway, keep the x - m form.
+    constexpr bool kDirect = DT == SMC_BF16;
+    constexpr double kLog2eLow = 1.4426950408889634074 - (double)kLog2e;
+
+    auto set_thr = [&](float t) __attribute__((always_inline)) {
+        thr = fmaxf(thr, t);
+        if constexpr (kDirect) thr_rel = fmaf(thr, kLog2e, -M1) - (fabsf(thr) * kLog2e + fabsf(M1)) * 3e-7f;
+        else thr_rel = (thr - m) - (fabsf(thr) + fabsf(m)) * 3e-7f;
+    };
+
+    auto raise_max = [&](float nm) __attribute__((always_inline)) {                    // nm > m, wave-uniform
         nm = uniform(nm);
         const float nM1 = ceilf(nm * kLog2e);
         const float nMb = P > 0 ? (float)P * nM1 : ceilf(nm * beta_l2e);
@@ -411,29 +471,29 @@ __global__ __launch_bounds__(NW * kWave, 4) void vocab_pass_kernel(const StepArg
         // fp32 rounding of the SMALL quantity (x-m), not of the large products x*log2e
         c1 = (float)((double)nM1 - (double)nm * 1.4426950408889634074);
         cb = (float)((double)nMb - (double)nm * (double)beta * 1.4426950408889634074);
-        thr = fmaxf(thr, lower(m - window));
+        t_max = fmaf(m, kLog2e, -M1);
+        set_thr(lower(m - window));
     };
 
-    auto publish = [&]() {                              // let the other waves of the workgroup use this wave's bound
+    auto publish = [&]() __attribute__((always_inline)) {                              // let the other waves of the workgroup use this wave's bound
         if (thr > published) {
             if (lane == 0) atomicMax(&wg_bound, enc_bound(thr));
             published = thr;
         }
     };
-    auto adopt = [&]() {                                // and take theirs (no waiting: stale is only conservative)
+    auto adopt = [&]() __attribute__((always_inline)) {                                // and take theirs (no waiting: stale is only conservative)
         const int seen = __hip_atomic_load(&wg_bound, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-        thr = fmaxf(thr, uniform(dec_bound(seen)));
+        set_thr(uniform(dec_bound(seen)));
     };
 
     // the bound that the best key found so far implies: entries below it cannot beat that key
-    auto tighten = [&]() {
+    auto tighten = [&]() __attribute__((always_inline)) {
         float bound = top.a.i >= 0 ? top.a.l + (top.a.g - kGumbelMax - kKeyMargin) / beta : -3.4e38f;
-        bound = uniform(wave_max_f32(bound));
-        thr = fmaxf(thr, lower(bound));
+        set_thr(lower(wave_max_f32(bound)));
     };
 
     // Scores the entries of one vector that are at or above `bar`: one Philox block per quad that holds such an entry.
-    auto score_vector = [&](const float (&x)[EPV], uint32_t vec_index, float bar) {
+    auto score_vector = [&](const float (&x)[EPV], uint32_t vec_index, float bar) __attribute__((always_inline)) {
 #pragma unroll
         for (int q4 = 0; q4 < QPV; ++q4) {
             bool need = false;
@@ -453,31 +513,76 @@ __global__ __launch_bounds__(NW * kWave, 4) void vocab_pass_kernel(const StepArg
         }
     };
 
-    // Scores up to 64 queued vectors (one per lane) and tightens thr from the keys reached.
-    auto drain = [&](int n) {
+    // Scores the first k (<= 64) queued single entries, one per lane, and tightens thr from the keys reached.
+    auto score_entries = [&](int k) __attribute__((always_inline)) {
         wave_sync();                                    // ring writes of other lanes, same wave
-        if (lane < n) {
-            const int slot = (q_head + lane) & (kRingV - 1);
-            const uint4 raw = ring_raw[slot];
-            const uint32_t vi = ring_idx[slot];
-            float x[EPV];
+        if (lane < k) {
+            const uint2 ent = ring_ent[(e_head + lane) & (kRingE - 1)];
+            const uint32_t idx = ent.x;
+            const float xv = __uint_as_float(ent.y);
+            if (xv >= thr) {
+                const U4 blk = philox4x32_10(idx >> 2, row, step, 0u, key0, key1);
+                top.offer(beta, xv, gumbel_f32(pick_word(blk, idx & 3u)), (int32_t)idx);
+                ++n_scored;
+            }
+        }
+        e_head = (e_head + k) & (kRingE - 1);
+        e_count -= k;
+        tighten();
+    };
+
+    // Takes up to 64 queued vectors (one per lane) off the ring.  Entries still at or above thr are either scored where
+    // they are (many: a flat proposal) or compacted into the entry ring, which is scored whenever it holds a full
+    // wave-width.
+    auto drain = [&](int n) __attribute__((always_inline)) {
+        wave_sync();                                    // ring writes of other lanes, same wave
+        float x[EPV];
+        uint32_t vi = 0u;
+        const bool in = lane < n;
+        {
+            uint4 raw = make_uint4(kPadWord, kPadWord, kPadWord, kPadWord);
+            if (in) {
+                const int slot = (q_head + lane) & (kRingV - 1);
+                raw = ring_raw[slot];
+                vi = ring_idx[slot];
+            }
             unpack<DT>(raw, x);
-            score_vector(x, vi, thr);
         }
         q_head = (q_head + n) & (kRingV - 1);
         q_count -= n;
         ++n_drains;
-        tighten();
+        int mine = 0;
+#pragma unroll
+        for (int j = 0; j < EPV; ++j) mine += x[j] >= thr ? 1 : 0;
+        const int total = wave_sum_i32(mine);
+        if (total > kScoreAsVectors) {
+            if (in) score_vector(x, vi, thr);
+            tighten();
+        } else if (total > 0) {
+#pragma unroll
+            for (int j = 0; j < EPV; ++j) {
+                const bool hit = x[j] >= thr;
+                const unsigned long long mk = __ballot(hit);
+                if (mk) {                               // wave-uniform
+                    if (hit) {
+                        const int slot = (e_head + e_count + mask_rank(mk)) & (kRingE - 1);
+                        ring_ent[slot] = make_uint2(vi * EPV + j, __float_as_uint(x[j]));
+                    }
+                    e_count += __popcll(mk);
+                    if (e_count >= kWave) score_entries(kWave);
+                }
+            }
+        }
     };
 
     // Drops queued vectors whose entries have all fallen below thr, keeping the order of the rest.
-    auto compact = [&]() {
+    auto compact = [&]() __attribute__((always_inline)) {
         wave_sync();
         int kept = 0;
         for (int base = 0; base < q_count; base += kWave) {
             const int src = (q_head + base + lane) & (kRingV - 1);
             const bool in = base + lane < q_count;
-            uint4 raw = make_uint4(0u, 0u, 0u, 0u);
+            uint4 raw = make_uint4(kPadWord, kPadWord, kPadWord, kPadWord);
             uint32_t vi = 0u;
             if (in) { raw = ring_raw[src]; vi = ring_idx[src]; }
             float x[EPV];
@@ -495,41 +600,79 @@ __global__ __launch_bounds__(NW * kWave, 4) void vocab_pass_kernel(const StepArg
         q_count = kept;
     };
 
-    // Appends the vectors of the lanes in `lanes` (those that hold an entry at or above thr) to the wave's ring.
-    auto enqueue = [&](const uint4& raw, uint32_t vec_index, bool hit, unsigned long long lanes) {
-        if (q_count > kRingV - kWave) {                 // rare: make room for one more wave-width of vectors
+    // Before a batch of the stream: leaves at most half of the vector ring occupied (one copy of the drain code, outside
+    // the unrolled loop over the batch's vectors).
+    auto make_room = [&]() __attribute__((always_inline)) {
+        if (q_count > kRingV / 2) {                     // wave-uniform, rare
             compact();
-            while (q_count > kRingV - kWave) drain(kWave);
+            while (q_count > kRingV / 2) drain(kWave);
         }
-        if (hit) {
-            const int slot = (q_head + q_count + mask_rank(lanes)) & (kRingV - 1);
-            ring_raw[slot] = raw;
-            ring_idx[slot] = vec_index;
-        }
-        q_count += __popcll(lanes);
     };
 
-    // both sums; every x[j] <= m here, so the exponents are <= 0
-    auto accumulate = [&](const float (&x)[EPV]) {
+    // both sums from d[j] = x[j] - m (fp32 rows) or t[j] = x[j]*log2e - M1 (bf16 rows); the exponents are <= 0 up to rounding
+    auto accumulate = [&](const float (&x)[EPV], const float (&d)[EPV]) __attribute__((always_inline)) {
 #pragma unroll
         for (int j = 0; j < EPV; ++j) {
-            const float d = x[j] - m;
-            const float e = fast_exp2(fmaf(d, kLog2e, -c1));
+            const float e = kDirect ? fast_exp2(d[j]) : fast_exp2(fmaf(d[j], kLog2e, -c1));
             s1 += e;
             if constexpr (P > 0) sb += ipow<P>(e);
-            else sb += fast_exp2(fmaf(d, beta_l2e, -cb));
+            else if constexpr (kDirect) sb += fast_exp2(fmaf(x[j], beta_l2e, -Mb));
+            else sb += fast_exp2(fmaf(d[j], beta_l2e, -cb));
         }
+    };
+    auto relative = [&](const float (&x)[EPV], float (&d)[EPV]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int j = 0; j < EPV; ++j) d[j] = kDirect ? fmaf(x[j], kLog2e, -M1) : x[j] - m;
+    };
+
+    // One vector of the stream: running maximum, filter, sums.  The maximum and the filter work on the relative values
+    // (which the sums need anyway); only when some lane holds an entry above the running maximum is the maximum itself formed.
+    auto stream_vector = [&](const uint4& raw, int vi, bool in_slice) __attribute__((always_inline)) {
+        float x[EPV], d[EPV];
+        unpack<DT>(raw, x);
+        relative(x, d);
+        float dm = vec_max<DT>(d);
+        if (__ballot(dm > (kDirect ? t_max : 0.f))) {   // wave-uniform, rare
+            const float nm = wave_max_f32(vec_max<DT>(x));
+            if (nm > m) raise_max(nm);
+            relative(x, d);
+            dm = vec_max<DT>(d);
+        }
+        if constexpr (DENSE) {
+            if (in_slice) score_vector(x, (uint32_t)vi, -INFINITY);                  // padding has no index to score
+        } else {
+            // Scoring is deferred: a vector that holds an entry which may still win is only queued here.  By the
+            // time the queue is scored the row's bound is far better than what this wave knows now, and most
+            // entries drop out.
+            const bool hit = dm >= thr_rel;
+            const unsigned long long lanes = __ballot(hit);
+            if (lanes) {                                                              // wave-uniform branch
+                if (q_count <= kRingV - kWave) {
+                    if (hit) {
+                        const int slot = (q_head + q_count + mask_rank(lanes)) & (kRingV - 1);
+                        ring_raw[slot] = raw;
+                        ring_idx[slot] = (uint32_t)vi;
+                    }
+                    q_count += __popcll(lanes);
+                } else {
+                    // the ring is full although it was at most half full when the batch began: so many entries may still
+                    // win (a flat proposal) that scoring the vector where it is costs no more than queueing it would
+                    if (hit) score_vector(x, (uint32_t)vi, thr);
+                    tighten();
+                }
+            }
+        }
+        accumulate(x, d);
     };
 
     // The main stream covers the vectors that lie wholly inside the row; the ragged last vector of a row (V not a
     // multiple of the vector width) is handled after it.  A batch that lies wholly inside the slice is loaded without
     // any guard; only the last, partial batch pays for clamped addresses and selects (-inf where there is no vector:
     // such an entry adds 0 to the sums and never passes the filter).
-    constexpr uint32_t kPadWord = DT == SMC_BF16 ? 0xFF80FF80u : 0xFF800000u;      // -inf in every element
     const int full_end = min(vec_end, nvec_full);
     constexpr int kBatch = THREADS * UNROLL;
     // vector u of the batch that starts at b0; `whole`: the batch lies wholly inside the slice (wave-uniform)
-    auto load_vec = [&](int b0, int u, bool whole) -> uint4 {
+    auto load_vec = [&](int b0, int u, bool whole) __attribute__((always_inline)) -> uint4 {
         const int vi = b0 + u * THREADS + tid;
         if (whole) {
             // every logit is read exactly once: non-temporal loads keep the stream out of the caches
@@ -544,54 +687,44 @@ __global__ __launch_bounds__(NW * kWave, 4) void vocab_pass_kernel(const StepArg
         return r;
     };
 
-    // UNROLL loads per thread stay in flight: as soon as a vector has been taken out of its register the same register
-    // receives the corresponding vector of the next batch
-    uint4 cur[UNROLL];
-    if (vec_begin < full_end) {
-        const bool whole = vec_begin + kBatch <= full_end;
+    // Two register sets of UNROLL vectors per thread alternate: while one batch is processed the next is in flight.
+    auto load_batch = [&](uint4 (&dst)[UNROLL], int b0) __attribute__((always_inline)) {
+        const bool whole = b0 + kBatch <= full_end;
 #pragma unroll
-        for (int u = 0; u < UNROLL; ++u) cur[u] = load_vec(vec_begin, u, whole);
+        for (int u = 0; u < UNROLL; ++u) dst[u] = load_vec(b0, u, whole);
+    };
+    auto stream_batch = [&](const uint4 (&src)[UNROLL], int b0) __attribute__((always_inline)) {
+        if constexpr (!DENSE) { publish(); adopt(); make_room(); }   // no waiting: whatever the other waves have found so far
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const int vi = b0 + u * THREADS + tid;
+            stream_vector(src[u], vi, vi < full_end);
+        }
+    };
+    uint4 buf_a[UNROLL], buf_b[UNROLL];
+    if (vec_begin < full_end) {
+        load_batch(buf_a, vec_begin);
         // warm start: the maximum of the wave's first batch gives a useful threshold at once
         float bm = -INFINITY;
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
             float x[EPV];
-            unpack<DT>(cur[u], x);
+            unpack<DT>(buf_a[u], x);
             bm = fmaxf(bm, vec_max<DT>(x));
         }
         bm = wave_max_f32(bm);
         if (bm > m) raise_max(bm);
     }
-    for (int base = vec_begin; base < full_end; base += kBatch) {
-        const bool more = base + kBatch < full_end;
-        const bool more_whole = base + 2 * kBatch <= full_end;
-        if constexpr (!DENSE) { publish(); adopt(); }   // no waiting: whatever the other waves have found so far
-#pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
-            const uint4 raw = cur[u];
-            if (more) cur[u] = load_vec(base + kBatch, u, more_whole);
-            float x[EPV];
-            unpack<DT>(raw, x);
-            // the running maximum first (the sums need x <= m); thr may sit above m when another wave of the
-            // workgroup has seen a larger logit
-            const float vm = vec_max<DT>(x);
-            if (__ballot(vm > m)) raise_max(wave_max_f32(vm));
-            const int vi = base + u * THREADS + tid;
-            if constexpr (DENSE) {
-                if (vi < full_end) score_vector(x, (uint32_t)vi, -INFINITY);        // padding has no index to score
-            } else {
-                // Scoring is deferred: a vector that holds an entry which may still win is only queued here.  By the
-                // time the queue is scored the row's bound is far better than what this wave knows now, and most
-                // entries drop out.
-                const bool hit = vm >= thr;
-                const unsigned long long lanes = __ballot(hit);
-                if (lanes) enqueue(raw, (uint32_t)vi, hit, lanes);                   // wave-uniform branch
-            }
-            accumulate(x);
-        }
+    for (int base = vec_begin; base < full_end; base += 2 * kBatch) {
+        const bool second = base + kBatch < full_end;
+        if (second) load_batch(buf_b, base + kBatch);
+        stream_batch(buf_a, base);
+        if (!second) break;
+        if (base + 2 * kBatch < full_end) load_batch(buf_a, base + 2 * kBatch);
+        stream_batch(buf_b, base + kBatch);
     }
     if (nvec > nvec_full && vec_end == nvec && wave == 0) {                // the ragged tail: lane 0 of wave 0
-        float x[EPV];
+        float x[EPV], d[EPV];
 #pragma unroll
         for (int j = 0; j < EPV; ++j) {
             const int v = nvec_full * EPV + j;
@@ -601,19 +734,29 @@ __global__ __launch_bounds__(NW * kWave, 4) void vocab_pass_kernel(const StepArg
         if (__ballot(vm > m)) { const float nm = wave_max_f32(vm); if (nm > m) raise_max(nm); }
         // the few entries past the last full vector are scored where they are (-inf padding never reaches the bar)
         if (lane == 0) score_vector(x, (uint32_t)nvec_full, DENSE ? -3.4e38f : thr);
-        accumulate(x);
+        relative(x, d);
+        accumulate(x, d);
     }
     if constexpr (!DENSE) {
-        // every wave has streamed its share: the workgroup's bound now reflects the maximum of the whole slice
-        tighten(); publish();
-        __syncthreads();
-        adopt();
+        // No barrier here: a wave that is done streaming scores its queue against the bound as the workgroup knows it
+        // now, while slower waves still stream -- a few more entries are scored than with the final bound, but the
+        // scoring overlaps with the stream instead of following it.
+        tighten(); publish(); adopt();
         while (q_count > 0) {
             if (q_count > kWave) compact();
             if (q_count > 0) { drain(min(q_count, kWave)); publish(); adopt(); }
         }
+        if (e_count > 0) score_entries(e_count);
+        publish();
     }
 
+    if constexpr (kDirect) {
+        // the per-wave part of the error of the fp32 constant log2e (see kDirect above)
+        if (m > -3.0e38f) {
+            s1 *= fast_exp2((float)((double)m * kLog2eLow));
+            sb *= fast_exp2((float)((double)m * (double)beta * kLog2eLow));
+        }
+    }
     Partial* const slot_out = a.partials + (int64_t)row * kMaxSplit + split;
     block_epilogue<NW>(beta, m, M1, Mb, s1, sb, top, n_scored, n_drains, slot_out, &sh_part);
     if (wave != 0) return;
@@ -626,7 +769,7 @@ __global__ __launch_bounds__(NW * kWave, 4) void vocab_pass_kernel(const StepArg
             __threadfence();                           // this slice's record is visible before its ticket is
             tk = atomicAdd(&a.row_ticket[row], 1);
         }
-        tk = __shfl(tk, 0);
+        tk = __builtin_amdgcn_readfirstlane(tk);
         if (tk != n_split - 1) return;
         if (lane == 0) a.row_ticket[row] = 0;          // nobody else touches it until the next step
         __threadfence();                               // the other slices' records, written by other workgroups
@@ -634,7 +777,7 @@ __global__ __launch_bounds__(NW * kWave, 4) void vocab_pass_kernel(const StepArg
     } else {
         wave_sync();                                   // lane 0's copy of the record in LDS
     }
-    finalize_row(a, sc, row, pp, n_split);
+    finalize_row(a, sc, row, pp, n_split, row_state);
     after_row_final(a, sc, row, lds);
 }
 

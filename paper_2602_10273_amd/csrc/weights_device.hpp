@@ -35,7 +35,7 @@ __device__ inline void prompt_lse(const double* __restrict__ lw, int N, double* 
     if (lane == 0) {
         for (int i = 0; i < N; ++i) { s1 += sh_a[i]; s2 += sh_b[i]; }
     }
-    s1 = __shfl(s1, 0); s2 = __shfl(s2, 0);
+    s1 = read_lane(s1, 0); s2 = read_lane(s2, 0);
     L1 = mx + log(s1);
     L2 = 2.0 * mx + log(s2);
     wave_sync();
