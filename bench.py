@@ -2,8 +2,8 @@
 """Throughput of the Power-SMC per-token step on one MI355X.
 
 One "step" is one pass of the whole hot path over one batch of synthetic logits with the KV cache resident in
-HBM: smc_step (boundary reweight, vocabulary pass, increment) -> smc_resample (ESS, trigger, ancestors) ->
-smc_kv_reindex (KV / history / cumulative-log-p gather for the prompts that resampled).  Resampling fires
+HBM: smc_step_resample (boundary reweight, vocabulary pass, increment, ESS, trigger, ancestors: one launch) ->
+smc_kv_reindex (KV / history / cumulative-log-p gather for the prompts that resampled: two launches).  Resampling fires
 whenever the weights say so; how often is an observed quantity and is reported.
 
 Prints ONE JSON line.  `value` is particle-steps/s over the timed steps.  `roofline` describes the kernel that
@@ -36,6 +36,8 @@ def parse():
     ap.add_argument("--steps", type=int, default=0, help="timed steps (0: per-workload default)")
     ap.add_argument("--warmup", type=int, default=4)
     ap.add_argument("--workload", default="cfg4", choices=["cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--separate-launches", action="store_true",
+                    help="smc_step and smc_resample as two calls instead of smc_step_resample (one launch for a0..a4)")
     ap.add_argument("--no-prologue", action="store_true",
                     help="skip the untimed steps through the workload's exponent ramp (the run then starts at t = 1)")
     ap.add_argument("--cpu-single-leg", action="store_true", help=argparse.SUPPRESS)
@@ -383,8 +385,11 @@ def main():
         t = step_no[0]
         if P:
             s.prepare_append(len0 + (t - first_t))  # the decoder would now write this position and emit logits
-        s.step(logits_of(t), t, w.alpha_at(t), w.alpha_at(t - 1), -1.0)
-        s.resample(t)
+        if args.separate_launches:
+            s.step(logits_of(t), t, w.alpha_at(t), w.alpha_at(t - 1), -1.0)
+            s.resample(t)
+        else:       # a0..a4 in one launch: the wave that completes a prompt's last row resamples the prompt
+            s.step_resample(logits_of(t), t, w.alpha_at(t), w.alpha_at(t - 1), -1.0)
         reorder(t)
 
     n_pro_resampled = 0
@@ -410,8 +415,11 @@ def main():
         t = step_no[0]
         if P:
             s.prepare_append(len0 + (t - first_t))
-        s.step(logits_of(t), t, w.alpha_at(t), w.alpha_at(t - 1), -1.0)
-        s.resample(t)
+        if args.separate_launches:
+            s.step(logits_of(t), t, w.alpha_at(t), w.alpha_at(t - 1), -1.0)
+            s.resample(t)
+        else:
+            s.step_resample(logits_of(t), t, w.alpha_at(t), w.alpha_at(t - 1), -1.0)
         anc_log[i].copy_(s.anc); flag_log[i].copy_(s.resampled)
         reorder(t)
     first_logged = step_no[0] - K + 1
@@ -480,6 +488,7 @@ def main():
                                                  if P else f"{w.layers}x2 tensors [{w.R},{w.H},{w.S},{w.D}] bf16 x2 buffers"),
                    "valid_len": w.S, "resampled_prompt_fraction": resample_frac,
                    "rows_read_per_row_written": rows_read / max(rows_written, 1),
+                   "launches_per_step": (4 if P else 3) + (1 if args.separate_launches else 0),
                    "logits_ring": f"{n_ring} buffers of {w_gen.R} rows, window of {w.R} rows sliding one row per {n_ring} steps"},
         "roofline": dominant, "roofline_other": other,
     }

@@ -40,7 +40,9 @@ def _ambiguous_resample(o, lnw, t):
 
 
 def run_lockstep(w, seed, steps, tau=-1.0, table=None, grow_kv=True, kv_seed=3, eos_id=-1, in_place=False,
-                 skip_terminated_kv=False):
+                 skip_terminated_kv=False, logits_fn=None, fused=False):
+    """logits_fn(t) -> (numpy logits for the oracle, device tensor with the same bits): for shapes too large to draw
+    on the CPU.  fused: smc_step_resample (one launch) instead of smc_step + smc_ess + smc_resample."""
     from paper_2602_10273_amd import binding as smc
     kv = synth.kv_numpy(w, kv_seed)
     T_max = (steps + 3) // 4 * 4
@@ -55,14 +57,22 @@ def run_lockstep(w, seed, steps, tau=-1.0, table=None, grow_kv=True, kv_seed=3, 
     stats = dict(token_ties=0, ess_band=0, pos_band=0, resamples=0, steps=0, max_dw=0.0, max_dess=0.0, done=0,
                  draw_band=0, rows_moved=0)
     for t in range(1, steps + 1):
-        if table is not None:
+        x_dev = None
+        if logits_fn is not None:
+            x, x_dev = logits_fn(t)
+        elif table is not None:
             prev = np.zeros(w.R, np.int64) if t == 1 else o.hist[:, t - 2]
             x = synth.logits_numpy(w, t, seed, prev_tokens=prev, table=table)
         else:
             x = synth.logits_numpy(w, t, seed)
+        if x_dev is None:
+            x_dev = to_device_logits(x, w.dtype)
         a_t, a_p = w.alpha_at(t), w.alpha_at(t - 1)
         want = o.step(x, t, a_t, a_p, tau)
-        s.step(to_device_logits(x, w.dtype), t, a_t, a_p, tau)
+        if fused:
+            s.step_resample(x_dev, t, a_t, a_p, tau)
+        else:
+            s.step(x_dev, t, a_t, a_p, tau)
         got = s.tokens.cpu().numpy()
         mism = got != want["tokens"]
         tie = want["gap"] < 1e-6
@@ -71,17 +81,24 @@ def run_lockstep(w, seed, steps, tau=-1.0, table=None, grow_kv=True, kv_seed=3, 
         stats["token_ties"] += int(mism.sum())
 
         e_ref, lnw_ref = o.ess()
-        s.compute_ess()
-        lnw = s.lognormw.cpu().numpy(); e = s.ess.cpu().numpy()
-        if not dirty or tau <= 0:           # with tau = 1/alpha the weights do not depend on the token drawn (Thm 1)
-            keep = np.exp(lnw_ref) > 1e-12  # log-weights of particles with no mass left are not compared
-            stats["max_dw"] = max(stats["max_dw"], float(np.abs(lnw - lnw_ref)[keep].max()))
-            stats["max_dess"] = max(stats["max_dess"], float(np.abs(e - e_ref).max()))
-            assert np.abs(lnw - lnw_ref)[keep].max() < TOL, t
-            assert np.abs(e - e_ref).max() < TOL, t
+        if fused:                           # the weights were reset inside the launch: only the ESS is there to compare
+            e = s.ess.cpu().numpy()
+            if not dirty or tau <= 0:
+                stats["max_dess"] = max(stats["max_dess"], float(np.abs(e - e_ref).max()))
+                assert np.abs(e - e_ref).max() < TOL, t
+        else:
+            s.compute_ess()
+            lnw = s.lognormw.cpu().numpy(); e = s.ess.cpu().numpy()
+            if not dirty or tau <= 0:       # with tau = 1/alpha the weights do not depend on the token drawn (Thm 1)
+                keep = np.exp(lnw_ref) > 1e-12  # log-weights of particles with no mass left are not compared
+                stats["max_dw"] = max(stats["max_dw"], float(np.abs(lnw - lnw_ref)[keep].max()))
+                stats["max_dess"] = max(stats["max_dess"], float(np.abs(e - e_ref).max()))
+                assert np.abs(lnw - lnw_ref)[keep].max() < TOL, t
+                assert np.abs(e - e_ref).max() < TOL, t
 
         anc_ref, flag_ref, _ = o.resample(t)
-        s.resample(t)
+        if not fused:
+            s.resample(t)
         anc = s.anc.cpu().numpy(); flag = s.resampled.cpu().numpy()
         band = np.abs(e_ref - w.kappa * w.N) < TOL
         assert np.array_equal(flag[~band], flag_ref[~band]), t
