@@ -36,6 +36,13 @@ def parse():
     ap.add_argument("--steps", type=int, default=0, help="timed steps (0: per-workload default)")
     ap.add_argument("--warmup", type=int, default=4)
     ap.add_argument("--workload", default="cfg4", choices=["cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--kv-positions", type=int, default=0,
+                    help="--mode reindex: cache positions per head instead of the workload's (other row lengths)")
+    ap.add_argument("--concentration", type=float, default=0.5,
+                    help="--mode reindex: Dirichlet concentration of the synthetic weights the ancestors are drawn from "
+                         "(smaller: fewer distinct ancestors, i.e. fewer rows read per row written)")
+    ap.add_argument("--gather-variant", default="", metavar="V:G",
+                    help="--mode reindex: kernel variant and workgroups per CU for smc_set_gather_tuning")
     ap.add_argument("--separate-launches", action="store_true",
                     help="smc_step and smc_resample as two calls instead of smc_step_resample (one launch for a0..a4)")
     ap.add_argument("--no-prologue", action="store_true",
@@ -191,11 +198,16 @@ def check_rows_after_reorder(s, w, anc_before, torch, np, n_rows=6):
 
 def reindex_only(args, w, K, W, smc, synth, Session, np, torch):
     """The KV reorder alone at the workload's full cache: K launches with distinct synthetic ancestor vectors."""
+    if args.kv_positions:
+        w = synth.scaled(w, S=args.kv_positions)
     s = Session(w.B, w.N, w.V, 8, w.dtype, w.kappa, args.seed, kv_geom=(w.kv_tensors, w.H, w.S, w.D))
+    if args.gather_variant:
+        v, g_ = (int(x) for x in args.gather_variant.split(":"))
+        smc.smc_set_gather_tuning(s.ctx, g_, v)
     g = torch.Generator(device="cuda"); g.manual_seed(args.seed + 12345)
     for t in s.kvA:
         t.normal_(generator=g)
-    ancs = [synth.ancestors_numpy(w, args.seed + i) for i in range(W + K)]
+    ancs = [synth.ancestors_numpy(w, args.seed + i, args.concentration) for i in range(W + K)]
     d_anc = [torch.as_tensor(a).cuda() for a in ancs]
     flag = torch.ones(w.B, dtype=torch.int32, device="cuda")
     for i in range(W):
@@ -228,7 +240,7 @@ def reindex_only(args, w, K, W, smc, synth, Session, np, torch):
         "dtype": "u8", "data": "synthetic",
         "config": {"workload": w.name, "mode": "reindex", "B": w.B, "N": w.N,
                    "kv": f"{w.layers}x2 tensors [{w.R},{w.H},{w.S},{w.D}] bf16 x2 buffers", "valid_len": w.S,
-                   "ancestors": "sorted draws from Dirichlet(0.5) weights, every prompt resampled",
+                   "ancestors": f"sorted draws from Dirichlet({args.concentration}) weights, every prompt resampled",
                    "rows_read_per_row_written": rows_read / max(rows_written, 1)},
         "roofline": {"kernel": "gather_kernel", "bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": gbps / HBM_PEAK_GBPS, "traffic": None, "launches": int(n_gather),

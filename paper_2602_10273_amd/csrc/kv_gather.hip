@@ -20,7 +20,6 @@
 namespace psmc {
 
 namespace {
-constexpr int kGatherThreads = 256;
 typedef unsigned int vec16 __attribute__((ext_vector_type(4)));    // one 16-byte global load / store
 }  // namespace
 
@@ -133,14 +132,15 @@ struct GatherGeom {               // one family of tensors with identical geomet
 
 // Row r of a tensor starts at r*row_stride bytes; of each of its n_chunks chunks (chunk_stride bytes apart) the first
 // copy_bytes bytes (a multiple of 16) are copied.  `kv` and `hist` are the two families handled by one launch.
-// VPT: 16-byte vectors in flight per thread (a workgroup iteration moves a slab of 256*VPT*16 bytes);
-// NT_LD / NT_ST: non-temporal loads / stores.
-template <int VPT, bool NT_LD, bool NT_ST>
-__global__ __launch_bounds__(kGatherThreads) void gather_kernel(
+// THREADS: workgroup size; VPT: 16-byte vectors in flight per thread (a workgroup iteration moves a slab of
+// THREADS*VPT*16 bytes); NT_LD / NT_ST: non-temporal loads / stores.
+template <int THREADS, int VPT, bool NT_LD, bool NT_ST>
+__global__ __launch_bounds__(THREADS) void gather_kernel(
     GatherGeom kv, GatherGeom hist, const int32_t* __restrict__ parity, int mask_words,
     const GatherPlan* __restrict__ plan, const int32_t* __restrict__ grp_src, const int32_t* __restrict__ grp_base,
     const int32_t* __restrict__ grp_srcpar, const unsigned long long* __restrict__ grp_mask)
 {
+    constexpr int kGatherThreads = THREADS;
     constexpr int kVecPerThread = VPT;
     constexpr int kSlabBytes = kGatherThreads * VPT * 16;
     const int n_groups = plan->n_groups[plan->phase ^ 1];          // the plan flipped the phase after using it
@@ -202,33 +202,42 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(
     }
 }
 
-template <int VPT, bool NT_LD, bool NT_ST>
+template <int THREADS, int VPT, bool NT_LD, bool NT_ST>
 static void launch_gather(smc_ctx* c, GatherGeom kv, GatherGeom hist)
 {
-    constexpr int64_t slab = (int64_t)kGatherThreads * VPT * 16;
+    constexpr int64_t slab = (int64_t)THREADS * VPT * 16;
     kv.slabs_per_chunk = (int)((kv.copy_bytes + slab - 1) / slab);
     hist.slabs_per_chunk = (int)((hist.copy_bytes + slab - 1) / slab);
     auto& w = c->ws;
-    hipLaunchKernelGGL((gather_kernel<VPT, NT_LD, NT_ST>), dim3(c->gather_grid), dim3(kGatherThreads), 0, c->stream, kv, hist,
+    // the same number of resident waves whatever the workgroup size
+    const int grid = c->gather_grid * 256 / THREADS > 0 ? c->gather_grid * 256 / THREADS : 1;
+    hipLaunchKernelGGL((gather_kernel<THREADS, VPT, NT_LD, NT_ST>), dim3(grid), dim3(THREADS), 0, c->stream, kv, hist,
                        w.parity, c->mask_words, w.plan, w.grp_src, w.grp_base, w.grp_srcpar, w.grp_mask);
 }
 
 static void launch_gather_variant(smc_ctx* c, int variant, const GatherGeom& kv, const GatherGeom& hist)
 {
-#define PSMC_G(V, L, S) launch_gather<V, L, S>(c, kv, hist)
+#define PSMC_G(T, V, L, S) launch_gather<T, V, L, S>(c, kv, hist)
     switch (variant) {
-        case 0: PSMC_G(8, true, true); break;
-        case 1: PSMC_G(8, false, true); break;
-        case 2: PSMC_G(8, false, false); break;
-        case 3: PSMC_G(4, true, true); break;
-        case 4: PSMC_G(4, false, true); break;
-        case 5: PSMC_G(4, false, false); break;
-        case 6: PSMC_G(16, true, true); break;
-        case 7: PSMC_G(16, false, true); break;
-        case 8: PSMC_G(16, false, false); break;
-        case 9: PSMC_G(2, true, true); break;
-        case 10: PSMC_G(2, false, false); break;
-        default: PSMC_G(4, false, true); break;
+        case 0: PSMC_G(256, 8, true, true); break;
+        case 1: PSMC_G(256, 8, false, true); break;
+        case 2: PSMC_G(256, 8, false, false); break;
+        case 3: PSMC_G(256, 4, true, true); break;
+        case 4: PSMC_G(256, 4, false, true); break;
+        case 5: PSMC_G(256, 4, false, false); break;
+        case 6: PSMC_G(256, 16, true, true); break;
+        case 7: PSMC_G(256, 16, false, true); break;
+        case 8: PSMC_G(256, 16, false, false); break;
+        case 9: PSMC_G(256, 2, true, true); break;
+        case 10: PSMC_G(256, 2, false, false); break;
+        case 11: PSMC_G(1024, 4, false, true); break;
+        case 12: PSMC_G(1024, 4, false, false); break;
+        case 13: PSMC_G(1024, 4, true, true); break;
+        case 14: PSMC_G(1024, 2, false, true); break;
+        case 15: PSMC_G(1024, 8, false, true); break;
+        case 16: PSMC_G(512, 4, false, true); break;
+        case 17: PSMC_G(512, 8, false, true); break;
+        default: PSMC_G(256, 4, false, true); break;
     }
 #undef PSMC_G
 }

@@ -437,7 +437,7 @@ smc_status smc_set_ancestor_order(smc_ctx* ctx, int32_t order)
 smc_status smc_set_gather_tuning(smc_ctx* ctx, int32_t wgs_per_cu, int32_t variant)
 {
     if (!ctx) return SMC_E_NULL;
-    if (wgs_per_cu < 1 || wgs_per_cu > 64 || variant < 0 || variant > 10) return SMC_E_RANGE;
+    if (wgs_per_cu < 1 || wgs_per_cu > 64 || variant < 0 || variant > 17) return SMC_E_RANGE;
     ctx->gather_grid = ctx->n_cus * wgs_per_cu;
     ctx->gather_variant = variant;
     return SMC_OK;
