@@ -500,7 +500,7 @@ def main():
                                                  if P else f"{w.layers}x2 tensors [{w.R},{w.H},{w.S},{w.D}] bf16 x2 buffers"),
                    "valid_len": w.S, "resampled_prompt_fraction": resample_frac,
                    "rows_read_per_row_written": rows_read / max(rows_written, 1),
-                   "launches_per_step": (4 if P else 3) + (1 if args.separate_launches else 0),
+                   "launches_per_step": (4 if P else 3) + (1 if args.separate_launches or w.R >= 1024 else 0),
                    "logits_ring": f"{n_ring} buffers of {w_gen.R} rows, window of {w.R} rows sliding one row per {n_ring} steps"},
         "roofline": dominant, "roofline_other": other,
     }

@@ -106,10 +106,11 @@ smc_status smc_kv_parity(smc_ctx* ctx, const int32_t** d_parity);
 smc_status smc_step(smc_ctx* ctx, const void* d_logits, int64_t row_stride_elems, int32_t t, double alpha_t,
                     double alpha_prev, double tau_t, int32_t* d_tokens_out);
 
-/* a0 .. a4 in ONE launch: smc_step followed by smc_resample, with the same arguments, outputs and results as the
- * two calls.  The workgroup that completes a row finalizes it, and the wave that finalizes the last row of a prompt
- * goes on to normalise and resample that prompt, so no second launch (and no launch gap) is needed.  Follow it with
- * smc_kv_reindex / smc_paged_reindex on d_anc_out / d_resampled_out as after smc_resample. */
+/* a0 .. a4 in one call: smc_step followed by smc_resample, with the same arguments, outputs and results as the two
+ * calls.  With fewer than 1024 rows it is ONE launch: the workgroup that completes a row finalizes it, and the wave
+ * that finalizes the last row of a prompt goes on to normalise and resample that prompt, so no second launch (and no
+ * launch gap) is needed.  Larger batches, where a launch is cheap beside the logit stream, take the two launches.
+ * Follow it with smc_kv_reindex / smc_paged_reindex on d_anc_out / d_resampled_out as after smc_resample. */
 smc_status smc_step_resample(smc_ctx* ctx, const void* d_logits, int64_t row_stride_elems, int32_t t, double alpha_t,
                              double alpha_prev, double tau_t, int32_t* d_tokens_out, int32_t* d_anc_out,
                              int32_t* d_resampled_out, double* d_ess_out);

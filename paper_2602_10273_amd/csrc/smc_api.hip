@@ -241,6 +241,15 @@ smc_status smc_step_resample(smc_ctx* ctx, const void* d_logits, int64_t row_str
     if (!isfinite(tau_t)) return SMC_E_RANGE;
     const double beta = tau_t <= 0.0 ? alpha_t : 1.0 / tau_t;
     if (!(beta > 0.0) || !isfinite(beta) || beta > 1.0e4) return SMC_E_RANGE;
+    // Folding the resampling into the launch costs every row a release at device scope (its weight must be visible to the
+    // wave that resamples the prompt).  With few rows that is far cheaper than a second launch; with a thousand rows
+    // or more the write-backs slow the logit stream of the whole chip by more than a launch costs (measured on 2048
+    // fp32 rows: 284 us folded against 201 + 5 us apart), so large batches take the two launches.
+    if (ctx->R >= 1024) {
+        if (launch_vocab_pass(ctx, d_logits, row_stride_elems, t, alpha_t, alpha_prev, tau_t, d_tokens_out, nullptr) != hipSuccess)
+            return SMC_E_HIP;
+        return launch_resample(ctx, ctx->ws.logW, t, d_anc_out, d_resampled_out, d_ess_out) == hipSuccess ? SMC_OK : SMC_E_HIP;
+    }
     const FusedResample f{d_anc_out, d_resampled_out, d_ess_out};
     return launch_vocab_pass(ctx, d_logits, row_stride_elems, t, alpha_t, alpha_prev, tau_t, d_tokens_out, &f) == hipSuccess
                ? SMC_OK : SMC_E_HIP;

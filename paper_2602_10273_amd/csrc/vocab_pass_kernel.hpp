@@ -352,14 +352,13 @@ __device__ inline void after_row_final(const StepArgs& a, const StepScalars& sc,
     const int lane = lane_id();
     const int b = (int)row / a.rs.N;
     int tk = 0;
-    if (lane == 0) {
-        __threadfence();                               // this row's weight is visible before the ticket is
-        tk = atomicAdd(&a.prompt_ticket[b], 1);
-    }
+    // release: this row's weight is visible before its ticket is (write-back only; the caches are not invalidated, which
+    // every row would otherwise do to the logit stream of its neighbours)
+    if (lane == 0) tk = __hip_atomic_fetch_add(&a.prompt_ticket[b], 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
     tk = __builtin_amdgcn_readfirstlane(tk);
     if (tk != a.rs.N - 1) return;
     if (lane == 0) a.prompt_ticket[b] = 0;             // nobody else touches it until the next step
-    __threadfence();                                   // the other rows' weights, written by other workgroups
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent"); // the other rows' weights, written by other workgroups
     double* sh_a = reinterpret_cast<double*>(lds);
     double* sh_b = sh_a + a.rs.N;
     int* sh_k = reinterpret_cast<int*>(sh_b + a.rs.N);
@@ -376,7 +375,7 @@ __global__ __launch_bounds__(NW * kWave, 4) void vocab_pass_kernel(const StepArg
 {
     constexpr int EPV = Elems<DT>::kPerVec;
     constexpr int QPV = EPV / 4;                       // Philox blocks (four entries each) per vector
-    constexpr int UNROLL = DT == SMC_BF16 ? 4 : 8;     // 16-byte loads per thread in flight
+    constexpr int UNROLL = 4;                          // 16-byte loads per thread and register set (two sets alternate)
     constexpr int THREADS = NW * kWave;
     constexpr int kRingV = 256;                        // queued vectors per wave (power of two, >= 2 wave-widths)
     constexpr int kRingE = 128;                        // queued single entries per wave (power of two, 2 wave-widths)
@@ -765,14 +764,12 @@ __global__ __launch_bounds__(NW * kWave, 4) void vocab_pass_kernel(const StepArg
     const Partial* pp = &sh_part;
     if (n_split > 1) {
         int tk = 0;
-        if (lane == 0) {
-            __threadfence();                           // this slice's record is visible before its ticket is
-            tk = atomicAdd(&a.row_ticket[row], 1);
-        }
+        // release: this slice's record (written by this lane) is visible before its ticket is
+        if (lane == 0) tk = __hip_atomic_fetch_add(&a.row_ticket[row], 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
         tk = __builtin_amdgcn_readfirstlane(tk);
         if (tk != n_split - 1) return;
         if (lane == 0) a.row_ticket[row] = 0;          // nobody else touches it until the next step
-        __threadfence();                               // the other slices' records, written by other workgroups
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");   // the other slices' records, written by other workgroups
         pp = a.partials + (int64_t)row * kMaxSplit;
     } else {
         wave_sync();                                   // lane 0's copy of the record in LDS
