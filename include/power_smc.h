@@ -137,7 +137,7 @@ smc_status smc_get_device_step(smc_ctx* ctx, int32_t* h_t);
 /* smc_step for callers that cannot allocate device memory: code under HIP graph capture, tight serving loops,
  * harnesses that forbid hipMalloc.  The same a0 + a1 + a2, the same kernels, but no context and no workspace: the
  * scratch of the vocabulary pass (one 48-byte record per row and slice, per-row diagnostics) lives in a device array
- * inside the library (about 6.5 MB, held by every GPU the library runs on until the process ends), and the state is
+ * inside the library (about 6.6 MB, held by every GPU the library runs on until the process ends), and the state is
  * the caller's:
  *   cfg: as for smc_init (B, N, V, logits_dtype, eos_id, seed are used); B*N <= SMC_NOALLOC_MAX_ROWS, else SMC_E_SHAPE.
  *   hip_stream: the stream to enqueue on (NULL = default stream).
@@ -146,9 +146,9 @@ smc_status smc_get_device_step(smc_ctx* ctx, int32_t* h_t);
  *   d_done_inout: device int32 [R] termination flags, read and updated; required when eos_id >= 0, else ignored.
  * No token history is written.  Calls nothing that allocates (no hipMalloc / hipFree, no workspace); argument errors
  * are detected on the host before anything is enqueued.  Every call on one GPU uses that GPU's one scratch array,
- * which keeps the previous call's contents (nothing in it has to start at zero: each call writes what it reads):
- * calls that overlap in time on one GPU -- other streams, other threads -- race on it and must be serialised by
- * the caller. */
+ * which keeps the previous call's contents (only the per-row ticket counters have to start at zero; each call clears
+ * them with a small fill kernel first, everything else it reads it has written itself): calls that overlap in time
+ * on one GPU -- other streams, other threads -- race on it and must be serialised by the caller. */
 smc_status smc_step_noalloc(const smc_config* cfg, void* hip_stream, const void* d_logits, int64_t row_stride_elems,
                             int32_t t, double alpha_t, double alpha_prev, double tau_t, double* d_logW_inout,
                             double* d_cumlogp_inout, int32_t* d_done_inout, int32_t* d_tokens_out);
