@@ -51,7 +51,8 @@ def parse():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kv", action="store_true", help="vocabulary pass + weights only (no cache bound)")
-    ap.add_argument("--n-split", type=int, default=0)
+    ap.add_argument("--n-split", type=int, default=0, help="slices a row is split over in the vocabulary pass (0: automatic)")
+    ap.add_argument("--wg-waves", type=int, default=0, help="waves per workgroup of the vocabulary pass: 4, 8 or 16 (0: automatic)")
     ap.add_argument("--mode", default="step", choices=["step", "reindex", "attention"],
                     help="step: the whole hot path (default); reindex: the KV reorder alone, every prompt resampled "
                          "with synthetic ancestors (sorted draws from Dirichlet(0.5) weights); attention: decode "
@@ -362,8 +363,8 @@ def main():
         kv_geom = (w.kv_tensors, w.H, w.S, w.D)
         len0 = max(0, w.S - (prologue + W + 2 * K) - 1)
         s = Session(w.B, w.N, w.V, T_max, w.dtype, w.kappa, args.seed, kv_geom=kv_geom, page_len=P, len0=len0)
-    if args.n_split:
-        smc.smc_set_tuning(s.ctx, args.n_split, 0)
+    if args.n_split or args.wg_waves:
+        smc.smc_set_tuning(s.ctx, args.n_split, 0, args.wg_waves)
     if args.in_place:
         smc.smc_set_ancestor_order(s.ctx, 1)
     if not args.no_kv:
