@@ -13,7 +13,8 @@
 // Exact lazy Gumbel-max: g is bounded, g in [kGumbelMin, kGumbelMax].  An entry whose best possible key
 // beta*l_v + kGumbelMax is below a key that some entry is already known to reach cannot be the argmax, so it
 // draws no random number.  The threshold on l_v ("thr") only ever rises; it comes from the wave's running maximum,
-// from keys already scored, and from one LDS word per workgroup that all its waves raise with an LDS atomic max
+// from the key that the entry holding a new running maximum really reaches (its variate is drawn at once, for the
+// bound alone), from keys already scored, and from one LDS word per workgroup that all its waves raise with an LDS atomic max
 // and read without waiting -- a stale value only makes the filter more conservative, never wrong.  The filter works
 // on whole 16-byte vectors: a lane whose vector holds an entry at or above thr appends the vector as loaded (16 bytes
 // + its index) to a per-wave LDS ring -- one compare and one ballot per vector, not per entry.  Scoring is deferred
@@ -441,6 +442,10 @@ __global__ __launch_bounds__(NW * kWave, 4) void vocab_pass_kernel(const StepArg
     int e_head = 0, e_count = 0;   // ring of queued single entries (always < 64 between drains)
     unsigned long long n_scored = 0, n_drains = 0;
     LaneTop2 top; top.init();
+    // the lane's highest entry among the vectors that raised the wave's running maximum since the last probe
+    float probe_l = -INFINITY;
+    uint32_t probe_i = 0u;
+    bool probe_pending = false;                        // wave-uniform
 
     auto lower = [](float b) { return b - fabsf(b) * 4e-7f; };    // a few ulps down: never drop a possible winner
 
@@ -489,6 +494,26 @@ __global__ __launch_bounds__(NW * kWave, 4) void vocab_pass_kernel(const StepArg
     auto tighten = [&]() __attribute__((always_inline)) {
         float bound = top.a.i >= 0 ? top.a.l + (top.a.g - kGumbelMax - kKeyMargin) / beta : -3.4e38f;
         set_thr(lower(wave_max_f32(bound)));
+    };
+
+    // A new running maximum alone only gives the bound "its key is at least beta*m + kGumbelMin".  Drawing the variate of
+    // that entry (and, in the same instructions, of every other lane's highest entry of the same vectors) replaces
+    // kGumbelMin by the key it really reaches, which raises the bound by a few units of 1/beta at once -- while
+    // the stream still runs, so that fewer vectors are queued at all.  Only the bound is kept: the entries are scored
+    // again with the rest of their vectors, so no candidate is offered twice.
+    auto probe = [&]() __attribute__((always_inline)) {
+        // wave-uniform: not worth a Philox block when the bound already lies so far above what this wave holds that only
+        // a variate beyond the 1 - e^-8 quantile could raise it
+        if (beta * (m - thr) > kGumbelMax - 8.0f) {
+            float b = -3.4e38f;
+            if (probe_l >= thr) {
+                const U4 blk = philox4x32_10(probe_i >> 2, row, step, 0u, key0, key1);
+                b = probe_l + (gumbel_f32(pick_word(blk, probe_i & 3u)) - kGumbelMax - kKeyMargin) / beta;
+            }
+            set_thr(lower(wave_max_f32(b)));
+        }
+        probe_pending = false;
+        probe_l = -INFINITY;
     };
 
     // Scores the entries of one vector that are at or above `bar`: one Philox block per quad that holds such an entry.
@@ -632,8 +657,21 @@ __global__ __launch_bounds__(NW * kWave, 4) void vocab_pass_kernel(const StepArg
         relative(x, d);
         float dm = vec_max<DT>(d);
         if (__ballot(dm > (kDirect ? t_max : 0.f))) {   // wave-uniform, rare
-            const float nm = wave_max_f32(vec_max<DT>(x));
-            if (nm > m) raise_max(nm);
+            const float lx = vec_max<DT>(x);
+            const float nm = wave_max_f32(lx);
+            if (nm > m) {
+                raise_max(nm);
+                if constexpr (!DENSE) {
+                    probe_pending = true;
+                    if (in_slice && lx > probe_l) {
+                        int jm = EPV - 1;
+#pragma unroll
+                        for (int j = EPV - 2; j >= 0; --j) jm = x[j] == lx ? j : jm;
+                        probe_l = lx;
+                        probe_i = (uint32_t)vi * EPV + (uint32_t)jm;
+                    }
+                }
+            }
             relative(x, d);
             dm = vec_max<DT>(d);
         }
@@ -699,24 +737,31 @@ __global__ __launch_bounds__(NW * kWave, 4) void vocab_pass_kernel(const StepArg
             const int vi = b0 + u * THREADS + tid;
             stream_vector(src[u], vi, vi < full_end);
         }
+        if constexpr (!DENSE) { if (probe_pending) probe(); }
     };
     uint4 buf_a[UNROLL], buf_b[UNROLL];
     if (vec_begin < full_end) {
         load_batch(buf_a, vec_begin);
         // warm start: the maximum of the wave's first batch gives a useful threshold at once
-        float bm = -INFINITY;
+        // (vectors past the slice were loaded as -inf and are never the lane's highest)
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
             float x[EPV];
             unpack<DT>(buf_a[u], x);
-            bm = fmaxf(bm, vec_max<DT>(x));
+            const uint32_t vi = (uint32_t)(vec_begin + u * THREADS + tid);
+#pragma unroll
+            for (int j = 0; j < EPV; ++j) {
+                if (x[j] > probe_l) { probe_l = x[j]; probe_i = vi * EPV + (uint32_t)j; }
+            }
         }
-        bm = wave_max_f32(bm);
+        const float bm = wave_max_f32(probe_l);
         if (bm > m) raise_max(bm);
+        probe_pending = true;                            // drawn once the next batch's loads are on their way
     }
     for (int base = vec_begin; base < full_end; base += 2 * kBatch) {
         const bool second = base + kBatch < full_end;
         if (second) load_batch(buf_b, base + kBatch);
+        if constexpr (!DENSE) { if (probe_pending) probe(); }      // (the warm start's: behind the loads just issued)
         stream_batch(buf_a, base);
         if (!second) break;
         if (base + 2 * kBatch < full_end) load_batch(buf_a, base + 2 * kBatch);
