@@ -241,10 +241,10 @@ smc_status smc_step_resample(smc_ctx* ctx, const void* d_logits, int64_t row_str
     if (!isfinite(tau_t)) return SMC_E_RANGE;
     const double beta = tau_t <= 0.0 ? alpha_t : 1.0 / tau_t;
     if (!(beta > 0.0) || !isfinite(beta) || beta > 1.0e4) return SMC_E_RANGE;
-    // Folding the resampling into the launch costs every row a release at device scope (its weight must be visible to the
-    // wave that resamples the prompt).  With few rows that is far cheaper than a second launch; with a thousand rows
-    // or more the write-backs slow the logit stream of the whole chip by more than a launch costs (measured on 2048
-    // fp32 rows: 284 us folded against 201 + 5 us apart), so large batches take the two launches.
+    // Folding the resampling into the launch saves a launch, but the wave that resamples a prompt keeps its workgroup's
+    // slot occupied while it does so.  With few rows the slot has nothing else to run and the fold is a gain; with a
+    // thousand rows or more it delays the logit stream of the next row by more than the launch costs (measured on 2048
+    // fp32 rows: 206 us folded against 197 + 5 us apart), so large batches take the two launches.
     if (ctx->R >= 1024) {
         if (launch_vocab_pass(ctx, d_logits, row_stride_elems, t, alpha_t, alpha_prev, tau_t, d_tokens_out, nullptr) != hipSuccess)
             return SMC_E_HIP;

@@ -26,7 +26,9 @@
 // Tail.  The workgroup that writes the last slice of a row (a ticket per row) merges the row's slices in fp64,
 // re-ranks the finalists with fp64 keys, and applies the boundary reweight and the increment.  With resampling
 // folded in, the wave that finalizes the last row of a prompt (a ticket per prompt) goes on to normalise the
-// prompt's weights and resample it.  Tickets return to zero by themselves, so the launch can be replayed.
+// prompt's weights and resample it.  Tickets return to zero by themselves, so the launch can be replayed.  What is handed
+// over behind a ticket (a slice's record, a row's weight) is written and read at agent scope, and the ticket is taken once
+// those writes have completed; no cache is written back or invalidated for it.
 #pragma once
 #include "weights_device.hpp"
 
@@ -133,6 +135,29 @@ __device__ __forceinline__ void wave_best_two(float ka, float kb, bool has_a, in
 // Workgroup summary: per-wave sums (each against its own power-of-two reference) and per-lane best-two candidates
 // are merged and written as this slice's Partial, to global memory and to `lds_copy` (for a row of one slice the
 // finalizer reads it from there).  m_wave is the wave's reference for comparing keys across lanes.
+// Data that one workgroup hands to another inside a launch (a slice's record, a row's weight) is written and read
+// with agent-scope accesses: they go to the level of the memory system that all compute units share, so that a ticket
+// taken after the writes have completed (the wait of a workgroup-scope release) publishes them.  A release at agent
+// scope would do as well, but it writes back -- and the matching acquire invalidates -- whole caches, which every row
+// would then do to the logit stream of its neighbours.
+template <typename T> __device__ __forceinline__ void store_shared(T* p, T v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+template <typename T> __device__ __forceinline__ T load_shared(const T* p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Takes a ticket after this lane's earlier stores have completed; returns its number (lane 0's, on every lane).
+__device__ __forceinline__ int take_ticket(int32_t* ticket)
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");      // waits for the stores; no cache maintenance
+    int tk = 0;
+    if (lane_id() == 0) tk = __hip_atomic_fetch_add(ticket, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return __builtin_amdgcn_readfirstlane(tk);
+}
+
 template <int NW>
 __device__ __forceinline__ void block_epilogue(float beta, float m_wave, float M1, float Mb, float s1, float sb,
                                                const LaneTop2 top, unsigned long long n_scored,
@@ -195,7 +220,12 @@ __device__ __forceinline__ void block_epilogue(float beta, float m_wave, float M
             p.l1 = l1v; p.g1 = g1v; p.i1 = lb < 0 ? -1 : i1v;
             p.l2 = l2v; p.g2 = g2v; p.i2 = (l2 < 0 || sec_b) ? -1 : i2v;
             p.n_scored = (int32_t)nsc; p.n_drains = (int32_t)ndr;
-            *out = p;
+            if (out) {                                  // a row of several slices: another workgroup may read the record
+                store_shared(&out->M1, p.M1); store_shared(&out->s1, p.s1); store_shared(&out->Mb, p.Mb); store_shared(&out->sb, p.sb);
+                store_shared(&out->l1, p.l1); store_shared(&out->g1, p.g1); store_shared(&out->i1, p.i1);
+                store_shared(&out->l2, p.l2); store_shared(&out->g2, p.g2); store_shared(&out->i2, p.i2);
+                store_shared(&out->n_scored, p.n_scored); store_shared(&out->n_drains, p.n_drains);
+            }
             *lds_copy = p;
         }
     }
@@ -248,9 +278,28 @@ __device__ inline void finalize_row(const StepArgs& a, const StepScalars& sc, ui
     const double beta = sc.beta, alpha_t = sc.alpha_t, alpha_prev = sc.alpha_prev;
     const uint32_t step = sc.step;
 
+    // lane c takes what it needs of the records: the sums of slice c, candidate (c & 1) of slice (c >> 1).  A row of one
+    // slice reads this workgroup's own record (LDS); records of other workgroups are read at agent scope.
+    Partial mine{}, cand{};
+    mine.M1 = -INFINITY; mine.Mb = -INFINITY; cand.i1 = -1; cand.i2 = -1;
+    if (n_split == 1) {
+        if (lane < 2) { mine = pp[0]; cand = mine; }
+    } else {
+        if (lane < n_split) {
+            const Partial* q = pp + lane;
+            mine.M1 = load_shared(&q->M1); mine.s1 = load_shared(&q->s1); mine.Mb = load_shared(&q->Mb); mine.sb = load_shared(&q->sb);
+            mine.n_scored = load_shared(&q->n_scored); mine.n_drains = load_shared(&q->n_drains);
+        }
+        if (lane < 2 * n_split) {
+            const Partial* q = pp + (lane >> 1);
+            if (lane & 1) { cand.i2 = load_shared(&q->i2); cand.l2 = load_shared(&q->l2); cand.g2 = load_shared(&q->g2); }
+            else { cand.i1 = load_shared(&q->i1); cand.l1 = load_shared(&q->l1); cand.g1 = load_shared(&q->g1); }
+        }
+    }
+
     // sums: the references are integer powers of two, so bringing a slice to the common reference is exact
     double M1 = -1e300, Mb = -1e300, s1 = 0.0, sb = 0.0;
-    if (lane < n_split) { M1 = pp[lane].M1; Mb = pp[lane].Mb; s1 = pp[lane].s1; sb = pp[lane].sb; }
+    if (lane < n_split) { M1 = mine.M1; Mb = mine.Mb; s1 = mine.s1; sb = mine.sb; }
     const double gM1 = wave_max_f64(M1), gMb = wave_max_f64(Mb);
     const double S1 = wave_sum_f64(lane < n_split && M1 > -1e300 ? ldexp(s1, (int)fmax(M1 - gM1, -2000.0)) : 0.0);
     const double Sb = wave_sum_f64(lane < n_split && Mb > -1e300 ? ldexp(sb, (int)fmax(Mb - gMb, -2000.0)) : 0.0);
@@ -260,18 +309,17 @@ __device__ inline void finalize_row(const StepArgs& a, const StepScalars& sc, ui
     const double logZ1 = gM1 * LN2 + read_lane(lg, 0);
     const double logZb = gMb * LN2 + read_lane(lg, 1);
 
-    const int32_t nsc = wave_sum_i32(lane < n_split ? pp[lane].n_scored : 0);
-    const int32_t ndr = wave_sum_i32(lane < n_split ? pp[lane].n_drains : 0);
+    const int32_t nsc = wave_sum_i32(lane < n_split ? mine.n_scored : 0);
+    const int32_t ndr = wave_sum_i32(lane < n_split ? mine.n_drains : 0);
 
     // finalists: lane c -> candidate (c & 1) of split (c >> 1).  The finalist's logit and fp32 Gumbel variate travel in
     // the partial record (the logit is an exact copy: bf16 and fp32 both fit a float), so no second read of the logits.
     int32_t idx = -1;
     float lf = 0.f, gf = 0.f;
     if (lane < 2 * n_split) {
-        const Partial& q = pp[lane >> 1];
-        idx = (lane & 1) ? q.i2 : q.i1;
-        lf = (lane & 1) ? q.l2 : q.l1;
-        gf = (lane & 1) ? q.g2 : q.g1;
+        idx = (lane & 1) ? cand.i2 : cand.i1;
+        lf = (lane & 1) ? cand.l2 : cand.l1;
+        gf = (lane & 1) ? cand.g2 : cand.g1;
     }
     if (idx >= a.V) idx = -1;                          // never trust an index outside the row, whatever the partial holds
     const bool has = idx >= 0;
@@ -318,7 +366,7 @@ __device__ inline void finalize_row(const StepArgs& a, const StepScalars& sc, ui
         const double delta = alpha_t * logp - logq;
         double w = rs.logW + (alpha_t - alpha_prev) * rs.cumlogp;          // stage boundary on the prefix y_{1:t-1}
         w += delta;
-        a.logW[row] = w;
+        store_shared(&a.logW[row], w);                  // (the wave that resamples the prompt may belong to another workgroup)
         a.cumlogp[row] = rs.cumlogp + logp;
         a.tokens_out[row] = tok;
         // (a device-resident step may have run past the end of the history)
@@ -335,7 +383,7 @@ __device__ inline void finalize_row(const StepArgs& a, const StepScalars& sc, ui
 // the particle's prefix (App. B).  One lane.
 __device__ inline void finalize_done_row(const StepArgs& a, const StepScalars& sc, uint32_t row)
 {
-    a.logW[row] += (sc.alpha_t - sc.alpha_prev) * a.cumlogp[row];
+    store_shared(&a.logW[row], a.logW[row] + (sc.alpha_t - sc.alpha_prev) * a.cumlogp[row]);
     a.tokens_out[row] = a.eos_id;
     if (a.histAB && sc.step >= 1u && sc.step <= (uint32_t)a.T_max) {
         int32_t* h = a.histAB[a.parity[row]];
@@ -352,14 +400,10 @@ __device__ inline void after_row_final(const StepArgs& a, const StepScalars& sc,
     if (!a.fuse_resample) return;
     const int lane = lane_id();
     const int b = (int)row / a.rs.N;
-    int tk = 0;
-    // release: this row's weight is visible before its ticket is (write-back only; the caches are not invalidated, which
-    // every row would otherwise do to the logit stream of its neighbours)
-    if (lane == 0) tk = __hip_atomic_fetch_add(&a.prompt_ticket[b], 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
-    tk = __builtin_amdgcn_readfirstlane(tk);
+    const int tk = take_ticket(&a.prompt_ticket[b]);   // this row's weight has been written
     if (tk != a.rs.N - 1) return;
-    if (lane == 0) a.prompt_ticket[b] = 0;             // nobody else touches it until the next step
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent"); // the other rows' weights, written by other workgroups
+    if (lane == 0) store_shared(&a.prompt_ticket[b], 0);   // nobody else touches it until the next step
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup"); // (keeps the reads below behind the ticket)
     double* sh_a = reinterpret_cast<double*>(lds);
     double* sh_b = sh_a + a.rs.N;
     int* sh_k = reinterpret_cast<int*>(sh_b + a.rs.N);
@@ -801,20 +845,17 @@ __global__ __launch_bounds__(NW * kWave, 4) void vocab_pass_kernel(const StepArg
             sb *= fast_exp2((float)((double)m * (double)beta * kLog2eLow));
         }
     }
-    Partial* const slot_out = a.partials + (int64_t)row * kMaxSplit + split;
+    Partial* const slot_out = n_split > 1 ? a.partials + (int64_t)row * kMaxSplit + split : nullptr;
     block_epilogue<NW>(beta, m, M1, Mb, s1, sb, top, n_scored, n_drains, slot_out, &sh_part);
     if (wave != 0) return;
 
     // ---- tail: the wave that completes the row finalizes it ---------------------------------------------------
     const Partial* pp = &sh_part;
     if (n_split > 1) {
-        int tk = 0;
-        // release: this slice's record (written by this lane) is visible before its ticket is
-        if (lane == 0) tk = __hip_atomic_fetch_add(&a.row_ticket[row], 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
-        tk = __builtin_amdgcn_readfirstlane(tk);
+        const int tk = take_ticket(&a.row_ticket[row]);    // this slice's record (written by lane 0) is complete
         if (tk != n_split - 1) return;
-        if (lane == 0) a.row_ticket[row] = 0;          // nobody else touches it until the next step
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");   // the other slices' records, written by other workgroups
+        if (lane == 0) store_shared(&a.row_ticket[row], 0);    // nobody else touches it until the next step
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup"); // (keeps the reads of the records behind the ticket)
         pp = a.partials + (int64_t)row * kMaxSplit;
     } else {
         wave_sync();                                   // lane 0's copy of the record in LDS

@@ -18,17 +18,25 @@ __device__ __forceinline__ void wave_sync()
     __builtin_amdgcn_wave_barrier();
 }
 
+// A log-weight as the resampling wave reads it: at agent scope, because inside the vocabulary pass's launch the weight
+// may have been written a moment ago by another workgroup.
+__device__ __forceinline__ double weight_at(const double* lw, int i)
+{
+    return __hip_atomic_load(lw + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 // log-sum-exp of x_i and of 2 x_i over one prompt, particle order.  Returns on every lane.
 // sh_a / sh_b: LDS scratch of N doubles each.
-__device__ inline void prompt_lse(const double* __restrict__ lw, int N, double* sh_a, double* sh_b, double& L1, double& L2)
+__device__ inline void prompt_lse(const double* lw, int N, double* sh_a, double* sh_b, double& L1, double& L2)
 {
     const int lane = lane_id();
     double mx = -INFINITY;
-    for (int i = lane; i < N; i += kWave) mx = fmax(mx, lw[i]);
+    for (int i = lane; i < N; i += kWave) mx = fmax(mx, weight_at(lw, i));
     mx = wave_max_f64(mx);
     for (int i = lane; i < N; i += kWave) {
-        sh_a[i] = exp(lw[i] - mx);
-        sh_b[i] = exp(2.0 * lw[i] - 2.0 * mx);
+        const double w = weight_at(lw, i);
+        sh_a[i] = exp(w - mx);
+        sh_b[i] = exp(2.0 * w - 2.0 * mx);
     }
     wave_sync();
     double s1 = 0.0, s2 = 0.0;
@@ -83,7 +91,7 @@ __device__ inline bool resample_prompt(const ResampleArgs& r, double* __restrict
         for (int i = lane; i < N; i += kWave) A[i] = b * N + i;
         return false;
     }
-    for (int i = lane; i < N; i += kWave) sh_a[i] = exp(lw[i] - L1);
+    for (int i = lane; i < N; i += kWave) sh_a[i] = exp(weight_at(lw, i) - L1);
     wave_sync();
     if (r.scheme != 3) {
         if (lane == 0) {
