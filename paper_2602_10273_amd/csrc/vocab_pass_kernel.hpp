@@ -546,11 +546,14 @@ __global__ __launch_bounds__(NW * kWave, 4) void vocab_pass_kernel(const StepArg
     // the stream still runs, so that fewer vectors are queued at all.  Only the bound is kept: the entries are scored
     // again with the rest of their vectors, so no candidate is offered twice.
     auto probe = [&]() __attribute__((always_inline)) {
-        // wave-uniform: not worth a Philox block when the bound already lies so far above what this wave holds that only
-        // a variate beyond the 1 - e^-8 quantile could raise it
-        if (beta * (m - thr) > kGumbelMax - 8.0f) {
+        // Wave-uniform conditions.  Not before the wave has met a finite entry; not when the bound already lies so far
+        // above what this wave holds that only a variate beyond the 1 - e^-8 quantile could raise it; and not when hardly
+        // any lane holds an entry near the bound -- then the logits are so thin up there that a somewhat higher bound
+        // would spare next to nothing.
+        const bool wanted = probe_l >= thr;
+        if (m > -3.0e38f && beta * (m - thr) > kGumbelMax - 8.0f && __popcll(__ballot(wanted)) >= 3) {
             float b = -3.4e38f;
-            if (probe_l >= thr) {
+            if (wanted) {
                 const U4 blk = philox4x32_10(probe_i >> 2, row, step, 0u, key0, key1);
                 b = probe_l + (gumbel_f32(pick_word(blk, probe_i & 3u)) - kGumbelMax - kKeyMargin) / beta;
             }
