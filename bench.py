@@ -7,8 +7,9 @@ smc_kv_reindex (KV / history / cumulative-log-p gather for the prompts that resa
 whenever the weights say so; how often is an observed quantity and is reported.
 
 Prints ONE JSON line.  `value` is particle-steps/s over the timed steps.  `roofline` describes the kernel that
-took the most time in a second, instrumented run of the same number of steps (HIP events recorded by the library
-on its own stream around each launch); `roofline_other` the other dominant kernel.  `cpu_baseline` times the CPU
+took the most time by the HIP events the library records on its own stream around each launch -- over the timed
+steps themselves when a dense cache is bound (millisecond steps), else over a second window of as many steps right
+after them (`config.kernel_events` says which); `roofline_other` the other dominant kernel.  `cpu_baseline` times the CPU
 oracle on a bounded sample of the same workload, on all host cores and (in a child process) on one.
 
 The default workload is the largest configuration (cfg4: 2048 rows of fp32 logits, 2 x 120 GB of KV cache), timed
