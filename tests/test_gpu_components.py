@@ -414,36 +414,39 @@ def test_step_resample_in_one_launch_equals_the_two_calls(name, kw, eos):
 
 
 def test_tickets_hand_every_record_over_on_many_contended_steps():
-    """Rows split over many slices and prompts of many rows, thousands of workgroups, 150 free-running steps: the run
-    whose slices and prompts are joined through tickets inside one launch (agent-scope stores of the records and the
-    weights, then the ticket) must reproduce, step by step and bit for bit, the run that takes every row in one slice
-    and resamples in a launch of its own as far as the draws go (tokens, ancestors, flags), and its sums to rounding.
-    A record or a weight read before it was written would show as a wrong sum, weight or ancestor."""
+    """Rows split over many slices and prompts of many rows, thousands of workgroups, 150 free-running steps.  Three runs
+    on the same logits: (a) eight slices per row, resampling in a launch of its own; (b) eight slices per row, slices
+    and prompts joined through tickets inside one launch (agent-scope stores of the records and the weights, then the
+    ticket); (c) every row in one slice, no ticket anywhere.  (a) and (b) merge the same records in the same order, so
+    they must agree to the last bit in everything; (c) sums in another order, so its draws are compared where no
+    near-tie decides them and its sums to rounding.  A record or a weight read before it was written would show as a
+    wrong sum, weight or ancestor."""
     w = synth.scaled(synth.WORKLOADS["cfg2"], B=8, N=64, V=8192 + 8, kappa=0.9)
-    a = Session(w.B, w.N, w.V, 160, w.dtype, w.kappa, 5, with_hist=False)
-    b = Session(w.B, w.N, w.V, 160, w.dtype, w.kappa, 5, with_hist=False)
-    smc.smc_set_tuning(a.ctx, 1, 0, 4)
+    a, b, c = (Session(w.B, w.N, w.V, 160, w.dtype, w.kappa, 5, with_hist=False) for _ in range(3))
+    smc.smc_set_tuning(a.ctx, 8, 0, 4)
     smc.smc_set_tuning(b.ctx, 8, 0, 4)
+    smc.smc_set_tuning(c.ctx, 1, 0, 4)
     xs = [to_device_logits(synth.logits_numpy(w, t, 5), w.dtype) for t in range(1, 9)]
     n_res = 0
     for t in range(1, 151):
         x = xs[t % 8]
         a.step(x, t, w.alpha, w.alpha); a.resample(t)
         b.step_resample(x, t, w.alpha, w.alpha)
+        c.step(x, t, w.alpha, w.alpha)
         torch.cuda.synchronize()
-        ga, gb = a.diag()["gap"], b.diag()["gap"]
-        clear = (ga > 1e-4) & (gb > 1e-4)
+        for f in ("tokens", "anc", "resampled", "ess"):
+            assert torch.equal(getattr(a, f), getattr(b, f)), (t, f)
+        sa, sb, sc = a.state(), b.state(), c.state()
+        assert np.array_equal(sa[0], sb[0]) and np.array_equal(sa[1], sb[1]), t
+        ga, gc = a.diag()["gap"], c.diag()["gap"]
+        clear = (ga > 1e-4) & (gc > 1e-4)
         assert clear.mean() > 0.99
-        assert np.array_equal(a.tokens.cpu().numpy()[clear], b.tokens.cpu().numpy()[clear]), t
-        if not clear.all():                               # a near-tie decided differently: bring b back in step
-            b.set_state(*a.state()[:2])
-            continue
-        sa, sb = a.state(), b.state()
-        np.testing.assert_allclose(sa[0], sb[0], rtol=0, atol=1e-5)
-        np.testing.assert_allclose(sa[1], sb[1], rtol=0, atol=1e-5)
-        assert torch.equal(a.resampled, b.resampled), t
-        assert torch.equal(a.anc, b.anc), t
+        assert np.array_equal(a.tokens.cpu().numpy()[clear], c.tokens.cpu().numpy()[clear]), t
+        if clear.all():                                   # (c has not resampled: compare the weights a had before it did)
+            da = a.diag()
+            np.testing.assert_allclose(da["delta"], c.diag()["delta"], rtol=0, atol=1e-5)
+            np.testing.assert_allclose(sa[1], sc[1], rtol=0, atol=1e-5)
+        c.set_state(sa[0], sa[1])                         # in step again, so that rounding cannot build up
         n_res += int(a.resampled.sum())
-        b.set_state(*sa[:2])                              # equal to the last bit again, so that rounding cannot build up
     assert n_res > 20
-    a.close(); b.close()
+    a.close(); b.close(); c.close()
