@@ -370,6 +370,9 @@ def main():
         smc.smc_set_tuning(s.ctx, args.n_split, 0, args.wg_waves)
     if args.in_place:
         smc.smc_set_ancestor_order(s.ctx, 1)
+    if args.gather_variant:
+        v, g_ = (int(x) for x in args.gather_variant.split(":"))
+        smc.smc_set_gather_tuning(s.ctx, g_, v)
     if not args.no_kv:
         g = torch.Generator(device=dev); g.manual_seed(args.seed + 12345)
         for t in (s.pools if P else s.kvA):

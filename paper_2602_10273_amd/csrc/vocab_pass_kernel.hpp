@@ -137,7 +137,7 @@ __device__ __forceinline__ void wave_best_two(float ka, float kb, bool has_a, in
 // finalizer reads it from there).  m_wave is the wave's reference for comparing keys across lanes.
 // Data that one workgroup hands to another inside a launch (a slice's record, a row's weight) is written and read
 // with agent-scope accesses: they go to the level of the memory system that all compute units share, so that a ticket
-// taken after the writes have completed (the wait of a workgroup-scope release) publishes them.  A release at agent
+// taken after the writes have completed (an explicit wait for the wave's vector memory operations) publishes them.  A release at agent
 // scope would do as well, but it writes back -- and the matching acquire invalidates -- whole caches, which every row
 // would then do to the logit stream of its neighbours.
 template <typename T> __device__ __forceinline__ void store_shared(T* p, T v)
@@ -152,7 +152,12 @@ template <typename T> __device__ __forceinline__ T load_shared(const T* p)
 // Takes a ticket after this lane's earlier stores have completed; returns its number (lane 0's, on every lane).
 __device__ __forceinline__ int take_ticket(int32_t* ticket)
 {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");      // waits for the stores; no cache maintenance
+    // The fence keeps the compiler from moving the stores behind the ticket; by itself it waits for nothing at this
+    // scope.  The wait is spelled out: vmcnt(0) -- every vector memory operation of this wave, the agent-scope stores
+    // among them, has been acknowledged (s_waitcnt encoding of this family: vmcnt in bits 3:0 and 15:14, expcnt 6:4
+    // and lgkmcnt 11:8 left at their maxima, i.e. not waited for).
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_s_waitcnt(0x0F70);
     int tk = 0;
     if (lane_id() == 0) tk = __hip_atomic_fetch_add(ticket, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     return __builtin_amdgcn_readfirstlane(tk);
