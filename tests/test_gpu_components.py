@@ -160,6 +160,31 @@ def test_step_degenerate_rows():
         assert res["tokens"][1] == 777
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_step_with_the_maximum_in_awkward_places(dtype):
+    """The entry that holds the running maximum is drawn early for the bound (and scored again with its vector): rows
+    whose maximum sits in the first entry, the last full vector, the ragged tail behind it, in every lane's first
+    vector at once (equal maxima), or rises in steps of one batch -- same tokens and sums as the oracle, with a
+    row split over slices and not."""
+    V = 8 * 6000 + 3
+    w = synth.scaled(synth.WORKLOADS["cfg2"], B=1, N=8, V=V, dtype=dtype)
+    x = synth.logits_numpy(synth.scaled(w, dtype="f32"), 1, 9)
+    x[0, 0] = 14.0
+    x[1, V - 4] = 14.0                                   # last entry of the last full vector
+    x[2, V - 1] = 14.0                                   # last entry of the ragged tail
+    x[3, V - 3] = 14.0                                   # first entry of the ragged tail
+    x[4, 0:2048:8] = 11.0                                # every lane of the first waves starts with the same maximum
+    x[5, ::4096] += 6.0                                  # a new maximum every few batches
+    x[6, :] = np.float32(-3.0); x[6, V - 2] = 0.5         # flat but for one entry in the tail
+    x[7, : V // 2] = -np.inf                             # the first half masked: no finite entry in the first batches
+    xs = synth.f32_to_bf16_bits(x) if dtype == "bf16" else x
+    pad = (-V) % (8 if dtype == "bf16" else 4)
+    for ww, ns in ((4, 1), (4, 3), (16, 0), (8, 2)):
+        for alpha in (4.0, 1.25):
+            res = check_step(w, seed=9, t=2, alpha_t=alpha, alpha_prev=alpha, tau=-1.0, logits=xs, stride_pad=pad, wg_waves=ww, n_split=ns)
+            assert res["tokens"][7] >= V // 2
+
+
 def test_ess_and_resample_match_oracle():
     from paper_2602_10273_amd import binding as smc
     rng = np.random.default_rng(0)
