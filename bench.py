@@ -393,8 +393,20 @@ def main():
 
     step_no = [first_t - 1]
 
+    # Paged cache: the reorder after token t and the preparation of the next position are one call (and one launch
+    # less) unless --separate-launches asks for the two calls; the first position is prepared before the first step.
+    paged_fused = bool(P) and not args.separate_launches
+    if paged_fused:
+        s.prepare_append(len0)
+
+    def prepare(t):
+        if P and not paged_fused:
+            s.prepare_append(len0 + (t - first_t))  # the decoder would now write this position and emit logits
+
     def reorder(t):
-        if P:
+        if paged_fused:
+            s.paged_reindex_prepare(t, len0 + (t - first_t) + 1)
+        elif P:
             s.paged_reindex(t)
         else:
             s.reindex(w.S, t)
@@ -402,8 +414,7 @@ def main():
     def one_step():
         step_no[0] += 1
         t = step_no[0]
-        if P:
-            s.prepare_append(len0 + (t - first_t))  # the decoder would now write this position and emit logits
+        prepare(t)
         if args.separate_launches:
             s.step(logits_of(t), t, w.alpha_at(t), w.alpha_at(t - 1), -1.0)
             s.resample(t)
@@ -425,8 +436,7 @@ def main():
     def logged_step(i):                                   # one_step() + what the step resampled (two small device copies)
         step_no[0] += 1
         t = step_no[0]
-        if P:
-            s.prepare_append(len0 + (t - first_t))
+        prepare(t)
         if args.separate_launches:
             s.step(logits_of(t), t, w.alpha_at(t), w.alpha_at(t - 1), -1.0)
             s.resample(t)
@@ -475,9 +485,12 @@ def main():
         # rows of the prompts that resampled at the previous step, minus their distinct ancestors
         gather_bytes_total = 0.0
         pos_bytes = w.kv_row_bytes // w.S
-        for i in range(1, K):
-            o = (len0 + first_logged - first_t + i) % P
-            needy = sum(w.N - len(np.unique(local[i - 1, b])) for b in range(w.B) if flag_h[i - 1, b])
+        # (with reorder and preparation in one call, step i prepares the position after its own and the sharers are
+        # those its own resampling made)
+        for i in range(0 if paged_fused else 1, K):
+            o = (len0 + first_logged - first_t + i + (1 if paged_fused else 0)) % P
+            src = i if paged_fused else i - 1
+            needy = sum(w.N - len(np.unique(local[src, b])) for b in range(w.B) if flag_h[src, b])
             gather_bytes_total += 2.0 * needy * o * pos_bytes * w.kv_tensors
     resample_frac = float(flag_h.mean())
 
@@ -524,7 +537,7 @@ def main():
                                                  if P else f"{w.layers}x2 tensors [{w.R},{w.H},{w.S},{w.D}] bf16 x2 buffers"),
                    "valid_len": w.S, "resampled_prompt_fraction": resample_frac,
                    "rows_read_per_row_written": rows_read / max(rows_written, 1),
-                   "launches_per_step": (4 if P else 3) + (1 if args.separate_launches or w.R >= 1024 else 0),
+                   "launches_per_step": ((3 if paged_fused else 4) if P else 3) + (1 if args.separate_launches or w.R >= 1024 else 0),
                    "logits_ring": f"{n_ring} buffers of {w_gen.R} rows, window of {w.R} rows sliding one row per {n_ring} steps"},
         "roofline": dominant, "roofline_other": other,
     }

@@ -280,6 +280,16 @@ smc_status smc_paged_prepare_append(smc_ctx* ctx, int32_t pos, int32_t* d_slot_o
  * replays that follow later appends; `t` is baked into the capture like any launch argument. */
 smc_status smc_paged_reindex(smc_ctx* ctx, const int32_t* d_anc, const int32_t* d_resampled, int32_t t);
 
+/* smc_paged_reindex followed by smc_paged_prepare_append(next_pos, d_slot_out), with the same arguments, results and
+ * errors as the two calls, in one launch less: the table workgroup that finishes a prompt's reorder last goes on to
+ * prepare that prompt for next_pos (for a prompt that did not resample, its first table workgroup does).  In a
+ * decode loop the reorder after token t and the preparation for the next position are adjacent, and with a paged
+ * cache the step is a chain of short dependent launches, so each launch saved is several microseconds.  Returns
+ * SMC_E_STATE under stream capture, like smc_paged_prepare_append.  A convenience beside the paper's reorder
+ * (Alg. 1 "reorder KV cache by A"; App. C), not an operation of its own. */
+smc_status smc_paged_reindex_prepare(smc_ctx* ctx, const int32_t* d_anc, const int32_t* d_resampled, int32_t t,
+                                     int32_t next_pos, int32_t* d_slot_out);
+
 /* Device pointers to the table [R, M] and the reference counts [B*Q], M, Q and the number of appended positions
  * (each nullable).  No synchronisation: reads of the device arrays must be ordered after the context's stream. */
 smc_status smc_paged_view(smc_ctx* ctx, const int32_t** d_table, const int32_t** d_refcnt, int32_t* pages_per_row,

@@ -18,7 +18,7 @@ EXPORTS = ["smc_workspace_bytes", "smc_init", "smc_destroy", "smc_kv_bind", "smc
            "smc_kv_reindex", "smc_final_draw", "smc_get_done", "smc_set_done", "smc_ess_from", "smc_resample_from", "smc_get_state", "smc_set_state", "smc_get_diag",
            "smc_set_tuning", "smc_set_resampler", "smc_set_ancestor_order", "smc_set_gather_tuning", "smc_profile_enable", "smc_profile_read", "smc_status_str",
            "smc_paged_workspace_bytes", "smc_paged_pool_bytes", "smc_paged_bind", "smc_paged_prepare_append",
-           "smc_paged_reindex", "smc_paged_view", "smc_paged_check", "smc_hbm_probe",
+           "smc_paged_reindex", "smc_paged_reindex_prepare", "smc_paged_view", "smc_paged_check", "smc_hbm_probe",
            "smc_attn_workspace_bytes", "smc_attn_decode", "smc_kv_parity", "smc_kv_append", "smc_step_noalloc",
            "smc_get_log_zhat", "smc_set_log_zhat", "smc_set_kv_skip_terminated",
            "smc_step_resample", "smc_set_schedule", "smc_set_device_step", "smc_advance_step", "smc_get_device_step"]
@@ -87,6 +87,7 @@ def lib():
         L.smc_paged_bind.argtypes = [vp, C.POINTER(vp), i32, vp, C.c_size_t, i32]
         L.smc_paged_prepare_append.argtypes = [vp, i32, vp]
         L.smc_paged_reindex.argtypes = [vp, vp, vp, i32]
+        L.smc_paged_reindex_prepare.argtypes = [vp, vp, vp, i32, i32, vp]
         L.smc_paged_view.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), C.POINTER(i32), C.POINTER(i32), C.POINTER(i32)]
         L.smc_paged_check.argtypes = [vp, C.POINTER(i32)]
         L.smc_attn_workspace_bytes.restype = C.c_size_t
@@ -297,6 +298,11 @@ def smc_paged_prepare_append(ctx, pos, d_slot_out):
 
 def smc_paged_reindex(ctx, d_anc, d_resampled, t):
     _check("smc_paged_reindex", lib().smc_paged_reindex(ctx, _ptr(d_anc), _ptr(d_resampled), t))
+
+
+def smc_paged_reindex_prepare(ctx, d_anc, d_resampled, t, next_pos, d_slot_out):
+    _check("smc_paged_reindex_prepare",
+           lib().smc_paged_reindex_prepare(ctx, _ptr(d_anc), _ptr(d_resampled), t, next_pos, _ptr(d_slot_out)))
 
 
 def smc_paged_view(ctx):

@@ -18,7 +18,9 @@
 //   paged_reorder_kernel  : table[k, :] = old table[anc[k], :]; old row a's pages gain copies(a) - 1 references;
 //                           token histories, cumulative log p and termination flags follow in the same launch
 //   paged_prepare_kernel  : one workgroup per prompt; finds the needy rows, the lowest free pages, writes the slot of
-//                           every row and the list of (source page, new page) pairs
+//                           every row and the list of (source page, new page) pairs.  The reorder can do the same for
+//                           the next position in its own launch: the table workgroup that finishes a prompt last
+//                           goes on to prepare it
 //   paged_copy_kernel     : grid-stride over (pair, tensor): 16-byte vector copy of the filled part of a page
 #include "smc_internal.hpp"
 
@@ -56,7 +58,7 @@ __device__ inline int block_exclusive_scan(int v, int32_t* sh_wave, int& total)
 
 __global__ void paged_init_kernel(int R, int N, int M, int Q, int P, int len0, int32_t* __restrict__ table,
                                   int32_t* __restrict__ refcnt, int32_t* __restrict__ counters,
-                                  int32_t* __restrict__ arrive)
+                                  int32_t* __restrict__ arrive, int32_t* __restrict__ arrive_table)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int ncol = (len0 + P - 1) / P;
@@ -67,8 +69,17 @@ __global__ void paged_init_kernel(int R, int N, int M, int Q, int P, int len0, i
     }
     if (i < (int64_t)(R / N) * Q) refcnt[i] = (int)(i % Q) < ncol * N ? 1 : 0;
     if (i < 8) counters[i] = 0;                        // pair counters of the two phases, failures, phase, ticket
-    if (i < R / N) arrive[i] = 0;
+    if (i < R / N) { arrive[i] = 0; arrive_table[i] = 0; }
 }
+
+// What the preparation of one position needs besides the table itself.
+struct PrepareArgs {
+    int j, o;                     // page column and offset of the position
+    int32_t* counters; int32_t* cow_src; int32_t* cow_dst; int32_t* slot;
+};
+
+__device__ void prepare_prompt(int b, int n_prompts, int N, int M, int Q, const PrepareArgs& pa,
+                               int32_t* __restrict__ table, int32_t* __restrict__ refcnt);
 
 // The reorder in one launch.  Two kinds of workgroup, told apart by blockIdx:
 //
@@ -83,11 +94,15 @@ __global__ void paged_init_kernel(int R, int N, int M, int Q, int P, int len0, i
 //   The permutation acts along the rows and every column is permuted on its own, so one workgroup takes all N rows of
 //   `cols` columns of one prompt: it reads them into LDS, then writes them back permuted -- no other workgroup touches
 //   these entries, so no copy of the old table is needed.  N * cols <= kEntriesPerBlock.
+//   With `prepare` set, the table workgroup of a prompt that finishes last (a ticket per prompt; for a prompt that did
+//   not resample, its first table workgroup) goes on to prepare the prompt for the next position, as
+//   paged_prepare_kernel would in a launch of its own.
 __global__ __launch_bounds__(kPagedThreads) void paged_reorder_kernel(
     const int32_t* __restrict__ anc, const int32_t* __restrict__ resampled, int B, int N,
     int hb, int hist_vecs, long long hist_row_bytes, int32_t* const* __restrict__ histAB, double* __restrict__ cumlogp,
     int32_t* __restrict__ done, int32_t* __restrict__ parity, int32_t* __restrict__ bad_anc, int32_t* __restrict__ arrive,
-    int M, int Q, int ncol, int cols, int chunks, int32_t* __restrict__ table, int32_t* __restrict__ refcnt)
+    int M, int Q, int ncol, int cols, int chunks, int32_t* __restrict__ table, int32_t* __restrict__ refcnt,
+    int prepare, PrepareArgs pa, int32_t* __restrict__ arrive_table)
 {
     __shared__ int32_t sh_anc[SMC_MAX_PARTICLES];
     __shared__ int32_t sh_aux[SMC_MAX_PARTICLES];      // table: copies of each ancestor; state: parity of each row
@@ -146,7 +161,10 @@ __global__ __launch_bounds__(kPagedThreads) void paged_reorder_kernel(
     }
     const int bid = blockIdx.x - n_state;
     const int b = bid / chunks;
-    if (!resampled[b]) return;
+    if (!resampled[b]) {
+        if (prepare && bid % chunks == 0) prepare_prompt(b, B, N, M, Q, pa, table, refcnt);
+        return;
+    }
     const int row0 = b * N, page0 = b * Q;
     for (int k = tid; k < N; k += kPagedThreads) sh_aux[k] = 0;
     __syncthreads();
@@ -174,6 +192,19 @@ __global__ __launch_bounds__(kPagedThreads) void paged_reorder_kernel(
             if (p >= page0 && p < page0 + Q) atomicAdd(&refcnt[p], gained);
         }
     }
+    if (prepare) {
+        // every thread's table entries and counts are out before the workgroup's ticket; the workgroup with the
+        // prompt's last ticket sees what the others wrote
+        __threadfence();
+        __syncthreads();
+        if (tid == 0) sh_last = atomicAdd(&arrive_table[b], 1) == chunks - 1;
+        __syncthreads();
+        if (sh_last) {
+            if (tid == 0) arrive_table[b] = 0;
+            __threadfence();
+            prepare_prompt(b, B, N, M, Q, pa, table, refcnt);
+        }
+    }
 }
 
 // counters: [0], [1] number of (source, new page) pairs, alternating between successive calls; [2] rows that found no
@@ -182,17 +213,21 @@ __global__ __launch_bounds__(kPagedThreads) void paged_reorder_kernel(
 // counter and flips counters[3] on the device (no memset between calls).  The page column j and offset o are launch
 // arguments derived from the host-side count of appended positions, so smc_paged_prepare_append refuses to be
 // captured into a graph.
-__global__ __launch_bounds__(kPagedThreads) void paged_prepare_kernel(
-    int N, int M, int Q, int j, int o, int32_t* __restrict__ table, int32_t* __restrict__ refcnt,
-    int32_t* __restrict__ counters, int32_t* __restrict__ cow_src, int32_t* __restrict__ cow_dst,
-    int32_t* __restrict__ slot)
+// One 256-thread workgroup prepares prompt b; n_prompts workgroups do so per call (the last of them flips the phase).
+__device__ void prepare_prompt(int b, int n_prompts, int N, int M, int Q, const PrepareArgs& pa,
+                               int32_t* __restrict__ table, int32_t* __restrict__ refcnt)
 {
+    const int j = pa.j, o = pa.o;
+    int32_t* const counters = pa.counters;
+    int32_t* const cow_src = pa.cow_src;
+    int32_t* const cow_dst = pa.cow_dst;
+    int32_t* const slot = pa.slot;
     __shared__ int32_t sh_page[SMC_MAX_PARTICLES];     // page of each row for this position (-1 at a page start)
     __shared__ int32_t sh_rank[SMC_MAX_PARTICLES];     // rank of a needy row among the prompt's needy rows, else -1
     __shared__ int32_t sh_free[SMC_MAX_PARTICLES];     // the prompt's lowest free pages, increasing
     __shared__ int32_t sh_wave[kPagedThreads / kWave];
     __shared__ int32_t sh_base;
-    const int b = blockIdx.x, tid = threadIdx.x;
+    const int tid = threadIdx.x;
     const int row0 = b * N, page0 = b * Q;
     const int phase = counters[3];
     for (int k = tid; k < N; k += kPagedThreads) sh_page[k] = o == 0 ? -1 : table[(int64_t)(row0 + k) * M + j];
@@ -265,12 +300,18 @@ __global__ __launch_bounds__(kPagedThreads) void paged_prepare_kernel(
     }
     if (tid == 0) {
         __threadfence();                               // the read of counters[3] precedes the ticket
-        if (atomicAdd(&counters[4], 1) == (int)gridDim.x - 1) {
+        if (atomicAdd(&counters[4], 1) == n_prompts - 1) {
             counters[phase ^ 1] = 0;
             counters[4] = 0;
             counters[3] = phase ^ 1;
         }
     }
+}
+
+__global__ __launch_bounds__(kPagedThreads) void paged_prepare_kernel(
+    int N, int M, int Q, PrepareArgs pa, int32_t* __restrict__ table, int32_t* __restrict__ refcnt)
+{
+    prepare_prompt((int)blockIdx.x, (int)gridDim.x, N, M, Q, pa, table, refcnt);
 }
 
 // Copies the first copy_bytes bytes (a multiple of 16) of each of the n_heads head chunks of a page, for every tensor
@@ -309,6 +350,8 @@ inline size_t up(size_t x) { return (x + kAlign - 1) & ~(kAlign - 1); }
 
 struct PagedDims { int P, M, Q; size_t n_table, n_pages; };
 
+void launch_paged_copy(smc_ctx* ctx, int o);       // below, with the reorder launch
+
 bool stream_is_capturing(hipStream_t s)
 {
     hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
@@ -343,6 +386,7 @@ size_t paged_layout(const smc_config* c, const PagedDims& d, char* base, PagedKV
     q = take(R * 4); if (p) p->cow_dst = (int32_t*)q;
     q = take(8 * 4); if (p) p->counters = (int32_t*)q;
     q = take((size_t)c->B * 4); if (p) p->arrive = (int32_t*)q;
+    q = take((size_t)c->B * 4); if (p) p->arrive_table = (int32_t*)q;
     q = take((size_t)c->kv_tensors * sizeof(void*)); if (p) p->pools = (void**)q;
     return off;
 }
@@ -387,7 +431,7 @@ smc_status smc_paged_bind(smc_ctx* ctx, void* const* h_pools, int32_t page_len, 
     try { ctx->h_pools.assign(h_pools, h_pools + ctx->cfg.kv_tensors); } catch (...) { return SMC_E_STATE; }
     const size_t n = d.n_table > d.n_pages ? d.n_table : d.n_pages;
     hipLaunchKernelGGL(paged_init_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, ctx->stream, ctx->R, ctx->cfg.N,
-                       d.M, d.Q, d.P, len0, p.table, p.refcnt, p.counters, p.arrive);
+                       d.M, d.Q, d.P, len0, p.table, p.refcnt, p.counters, p.arrive, p.arrive_table);
     if (hipGetLastError() != hipSuccess) return SMC_E_HIP;
     p.bound = 1;
     return SMC_OK;
@@ -405,27 +449,25 @@ smc_status smc_paged_prepare_append(smc_ctx* ctx, int32_t pos, int32_t* d_slot_o
     if (stream_is_capturing(ctx->stream)) return SMC_E_STATE;
     const auto& cfg = ctx->cfg;
     const int j = pos / p.P, o = pos % p.P;
-    hipLaunchKernelGGL(paged_prepare_kernel, dim3(cfg.B), dim3(kPagedThreads), 0, ctx->stream, cfg.N, p.M, p.Q, j, o,
-                       p.table, p.refcnt, p.counters, p.cow_src, p.cow_dst, d_slot_out);
-    if (o > 0) {
-        const long long pos_bytes = (long long)cfg.kv_D * cfg.kv_elem_bytes;
-        const long long head_stride = pos_bytes * p.P;
-        ScopedKernelTimer timer(ctx, 2);
-        hipLaunchKernelGGL(paged_copy_kernel, dim3(ctx->n_cus * 8), dim3(kPagedThreads), 0, ctx->stream,
-                           (void* const*)p.pools, cfg.kv_tensors, cfg.kv_H, head_stride * cfg.kv_H, head_stride,
-                           (int)(pos_bytes * o / 16), cfg.B * p.Q, p.counters, p.cow_src, p.cow_dst);
-    }
+    const PrepareArgs pa{j, o, p.counters, p.cow_src, p.cow_dst, d_slot_out};
+    hipLaunchKernelGGL(paged_prepare_kernel, dim3(cfg.B), dim3(kPagedThreads), 0, ctx->stream, cfg.N, p.M, p.Q, pa,
+                       p.table, p.refcnt);
+    if (o > 0) launch_paged_copy(ctx, o);
     if (hipGetLastError() != hipSuccess) return SMC_E_HIP;
     p.len = pos + 1;
     return SMC_OK;
 }
 
-smc_status smc_paged_reindex(smc_ctx* ctx, const int32_t* d_anc, const int32_t* d_resampled, int32_t t)
+}  // extern "C"
+
+namespace {
+
+// The reorder launch; with `pa`, the same launch also prepares every prompt for the position pa describes.
+// *fused tells whether it did (a cache without a page in use has no table workgroup to do it).
+smc_status launch_paged_reorder(smc_ctx* ctx, const int32_t* d_anc, const int32_t* d_resampled, int32_t t,
+                                const PrepareArgs* pa, bool* fused)
 {
-    if (!ctx || !d_anc || !d_resampled) return SMC_E_NULL;
     PagedKV& p = ctx->paged;
-    if (!p.bound) return SMC_E_STATE;
-    if (t < 0 || t > ctx->cfg.T_max) return SMC_E_RANGE;
     const auto& cfg = ctx->cfg;
     const int N = cfg.N;
     // token history: whole 16-byte vectors of the first t columns, as in the dense reorder
@@ -451,11 +493,60 @@ smc_status smc_paged_reindex(smc_ctx* ctx, const int32_t* d_anc, const int32_t* 
     }
     const int64_t blocks = (int64_t)cfg.B * hb + (int64_t)cfg.B * chunks;
     if (blocks > 0x7FFFFFFFll) return SMC_E_SHAPE;
+    const bool prepare = pa && chunks > 0;
+    if (fused) *fused = prepare;
     hipLaunchKernelGGL(paged_reorder_kernel, dim3((unsigned)blocks), dim3(kPagedThreads), 0, ctx->stream, d_anc, d_resampled,
                        cfg.B, N, hb, hist_vecs, (long long)cfg.T_max * 4, (int32_t* const*)ctx->ws.histAB, ctx->ws.cumlogp,
                        ctx->ws.done, ctx->ws.parity, &ctx->ws.plan->bad_anc, p.arrive, p.M, p.Q, ncol, cols, chunks, p.table,
-                       p.refcnt);
+                       p.refcnt, prepare ? 1 : 0, prepare ? *pa : PrepareArgs{}, p.arrive_table);
     return hipGetLastError() == hipSuccess ? SMC_OK : SMC_E_HIP;
+}
+
+// The copy of the filled part of every shared page that the preparation of position `pos` (offset o > 0) listed.
+void launch_paged_copy(smc_ctx* ctx, int o)
+{
+    const auto& cfg = ctx->cfg;
+    PagedKV& p = ctx->paged;
+    const long long pos_bytes = (long long)cfg.kv_D * cfg.kv_elem_bytes;
+    const long long head_stride = pos_bytes * p.P;
+    ScopedKernelTimer timer(ctx, 2);
+    hipLaunchKernelGGL(paged_copy_kernel, dim3(ctx->n_cus * 8), dim3(kPagedThreads), 0, ctx->stream,
+                       (void* const*)p.pools, cfg.kv_tensors, cfg.kv_H, head_stride * cfg.kv_H, head_stride,
+                       (int)(pos_bytes * o / 16), cfg.B * p.Q, p.counters, p.cow_src, p.cow_dst);
+}
+
+}  // namespace
+
+extern "C" {
+
+smc_status smc_paged_reindex(smc_ctx* ctx, const int32_t* d_anc, const int32_t* d_resampled, int32_t t)
+{
+    if (!ctx || !d_anc || !d_resampled) return SMC_E_NULL;
+    if (!ctx->paged.bound) return SMC_E_STATE;
+    if (t < 0 || t > ctx->cfg.T_max) return SMC_E_RANGE;
+    return launch_paged_reorder(ctx, d_anc, d_resampled, t, nullptr, nullptr);
+}
+
+smc_status smc_paged_reindex_prepare(smc_ctx* ctx, const int32_t* d_anc, const int32_t* d_resampled, int32_t t,
+                                     int32_t next_pos, int32_t* d_slot_out)
+{
+    if (!ctx || !d_anc || !d_resampled || !d_slot_out) return SMC_E_NULL;
+    PagedKV& p = ctx->paged;
+    if (!p.bound) return SMC_E_STATE;
+    if (t < 0 || t > ctx->cfg.T_max) return SMC_E_RANGE;
+    if (next_pos < 0 || next_pos >= ctx->cfg.kv_S) return SMC_E_RANGE;
+    if (next_pos != p.len) return SMC_E_STATE;
+    if (stream_is_capturing(ctx->stream)) return SMC_E_STATE;     // as smc_paged_prepare_append: the position is host-side state
+    const int j = next_pos / p.P, o = next_pos % p.P;
+    const PrepareArgs pa{j, o, p.counters, p.cow_src, p.cow_dst, d_slot_out};
+    bool fused = false;
+    const smc_status st = launch_paged_reorder(ctx, d_anc, d_resampled, t, &pa, &fused);
+    if (st != SMC_OK) return st;
+    if (!fused) return smc_paged_prepare_append(ctx, next_pos, d_slot_out);
+    if (o > 0) launch_paged_copy(ctx, o);
+    if (hipGetLastError() != hipSuccess) return SMC_E_HIP;
+    p.len = next_pos + 1;
+    return SMC_OK;
 }
 
 smc_status smc_paged_view(smc_ctx* ctx, const int32_t** d_table, const int32_t** d_refcnt, int32_t* pages_per_row,

@@ -115,6 +115,7 @@ struct PagedKV {
     int32_t* cow_dst;             // [R] new page of each pending copy
     int32_t* counters;            // [8] pairs of phase 0 / 1, rows that found no free page, phase, ticket, spare
     int32_t* arrive;              // [B] state workgroups of the running reorder that have finished, per prompt
+    int32_t* arrive_table;        // [B] table workgroups of the running reorder that have finished, per prompt
     void** pools;                 // [kv_tensors] page pools [B*Q, H, P, D]
 };
 

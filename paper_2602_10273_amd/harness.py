@@ -102,6 +102,10 @@ class Session:
         smc.smc_paged_reindex(self.ctx, self.anc if anc is None else anc,
                               self.resampled if resampled is None else resampled, t)
 
+    def paged_reindex_prepare(self, t, next_pos, anc=None, resampled=None):
+        smc.smc_paged_reindex_prepare(self.ctx, self.anc if anc is None else anc,
+                                      self.resampled if resampled is None else resampled, t, next_pos, self.slot)
+
     def paged_state(self):
         """(table [R, M], refcnt [B*Q]) as numpy, after synchronising."""
         torch.cuda.synchronize()

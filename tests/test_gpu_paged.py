@@ -94,6 +94,58 @@ def test_paged_matches_model_and_dense_gather(B, N, H, S, D, P, len0):
     s.close()
 
 
+@pytest.mark.parametrize("B,N,H,S,D,P,len0", [
+    (3, 4, 2, 24, 8, 4, 0), (2, 5, 1, 23, 8, 3, 0), (1, 8, 2, 9, 8, 1, 0), (2, 3, 1, 7, 8, 7, 0),
+    (2, 64, 1, 40, 8, 16, 0), (1, 100, 1, 12, 8, 5, 0), (1, 1024, 1, 6, 8, 4, 0), (4, 1, 2, 10, 8, 4, 0),
+    (3, 6, 2, 40, 16, 8, 21), (2, 130, 1, 600, 8, 4, 100),
+])
+def test_paged_reorder_and_preparation_in_one_launch(B, N, H, S, D, P, len0):
+    """smc_paged_reindex_prepare (the table workgroup that finishes a prompt last prepares it for the next position)
+    against the CPU model's reindex followed by prepare_append: slots, tables and reference counts bit-exact after
+    every step, logical cache content bit-exact against the dense gather.  The last shape has several table workgroups
+    per prompt (130 rows, 25 to 37 columns in use, 15 columns per workgroup)."""
+    rng = np.random.default_rng(B * 1000 + N + P + 7)
+    R, n_t = B * N, 2
+    T = min(S, len0 + 48)                                      # positions appended in the test
+    s = Session(B, N, 64, 64, "f32", 0.5, 1, kv_geom=(n_t, H, S, D), page_len=P, len0=len0)
+    pk = PagedKV(B, N, H, S, D, P, n_t)
+    dense = [np.zeros((R, H, S, D), np.uint16) for _ in range(n_t)]
+    if len0:
+        pk.reset(len0)
+        for pos in range(len0):
+            new = [rng.integers(0, 65536, (R, H, D), dtype=np.uint16) for _ in range(n_t)]
+            pk.write(pos, new)
+            for d, x in zip(dense, new):
+                d[:, :, pos, :] = x
+        for ten in range(n_t):
+            s.pools[ten].view(torch.int16).copy_(torch.as_tensor(pk.pool[ten].view(np.int16)))
+    slot_ref, _ = pk.prepare_append(len0)
+    s.prepare_append(len0)
+    for pos in range(len0, T):
+        assert np.array_equal(s.slot.cpu().numpy(), slot_ref), pos
+        new = [rng.integers(0, 65536, (R, H, D), dtype=np.uint16) for _ in range(n_t)]
+        _write(s, pk, pos, new)
+        for d, x in zip(dense, new):
+            d[:, :, pos, :] = x
+        flag = (rng.random(B) < 0.6).astype(np.int32)
+        anc = np.concatenate([b * N + np.sort(rng.integers(0, N, N)) for b in range(B)]).astype(np.int32)
+        if pos % 3 == 1:
+            anc = np.concatenate([b * N + rng.integers(0, N, N) for b in range(B)]).astype(np.int32)
+        pk.reindex(anc, flag)
+        dense = [orc.gather_kv(d, anc, flag, N, pos + 1, d.copy()) for d in dense]
+        if pos + 1 < T:
+            slot_ref, _ = pk.prepare_append(pos + 1)
+            s.paged_reindex_prepare(0, pos + 1, torch.as_tensor(anc).cuda(), torch.as_tensor(flag).cuda())
+        else:
+            s.paged_reindex(0, torch.as_tensor(anc).cuda(), torch.as_tensor(flag).cuda())
+        table = _compare_tables(s, pk)
+        if pos % 4 == 3 or pos == T - 1:
+            for ten in range(n_t):
+                assert np.array_equal(_logical(s, ten, table, pos + 1), dense[ten][:, :, :pos + 1]), (pos, ten)
+    assert smc.smc_paged_check(s.ctx) == 0
+    s.close()
+
+
 def test_paged_argument_errors_and_foreign_ancestors():
     cfg = smc.make_config(2, 4, 64, 8, "f32", 0.5, 0, 2, 1, 10, 8, 2)
     assert smc.smc_paged_workspace_bytes(cfg, 0) == 0 and smc.smc_paged_workspace_bytes(cfg, 11) == 0
