@@ -2,8 +2,8 @@
 """Throughput of the Power-SMC per-token step on one MI355X.
 
 One "step" is one pass of the whole hot path over one batch of synthetic logits with the KV cache resident in
-HBM: smc_step_resample (boundary reweight, vocabulary pass, increment, ESS, trigger, ancestors: one launch) ->
-smc_kv_reindex (KV / history / cumulative-log-p gather for the prompts that resampled: two launches).  Resampling fires
+HBM: smc_step_resample_reindex = smc_step_resample (boundary reweight, vocabulary pass, increment, ESS, trigger,
+ancestors) -> smc_kv_reindex (KV / history / cumulative-log-p gather for the prompts that resampled), three launches.  Resampling fires
 whenever the weights say so; how often is an observed quantity and is reported.
 
 Prints ONE JSON line.  `value` is particle-steps/s over the timed steps.  `roofline` describes the kernel that
@@ -418,8 +418,11 @@ def main():
         if args.separate_launches:
             s.step(logits_of(t), t, w.alpha_at(t), w.alpha_at(t - 1), -1.0)
             s.resample(t)
-        else:       # a0..a4 in one launch: the wave that completes a prompt's last row resamples the prompt
+        elif P:     # a0..a4 in one launch: the wave that completes a prompt's last row resamples the prompt
             s.step_resample(logits_of(t), t, w.alpha_at(t), w.alpha_at(t - 1), -1.0)
+        else:       # a0..a5 in one call, three launches
+            s.step_resample_reindex(logits_of(t), t, w.alpha_at(t), w.alpha_at(t - 1), w.S)
+            return
         reorder(t)
 
     n_pro_resampled = 0
@@ -440,8 +443,12 @@ def main():
         if args.separate_launches:
             s.step(logits_of(t), t, w.alpha_at(t), w.alpha_at(t - 1), -1.0)
             s.resample(t)
-        else:
+        elif P:
             s.step_resample(logits_of(t), t, w.alpha_at(t), w.alpha_at(t - 1), -1.0)
+        else:
+            s.step_resample_reindex(logits_of(t), t, w.alpha_at(t), w.alpha_at(t - 1), w.S)
+            anc_log[i].copy_(s.anc); flag_log[i].copy_(s.resampled)
+            return
         anc_log[i].copy_(s.anc); flag_log[i].copy_(s.resampled)
         reorder(t)
 
@@ -537,7 +544,7 @@ def main():
                                                  if P else f"{w.layers}x2 tensors [{w.R},{w.H},{w.S},{w.D}] bf16 x2 buffers"),
                    "valid_len": w.S, "resampled_prompt_fraction": resample_frac,
                    "rows_read_per_row_written": rows_read / max(rows_written, 1),
-                   "launches_per_step": ((3 if paged_fused else 4) if P else 3) + (1 if args.separate_launches or w.R >= 1024 else 0),
+                   "launches_per_step": (3 if paged_fused else 5) if P else (4 if args.separate_launches else 3),
                    "logits_ring": f"{n_ring} buffers of {w_gen.R} rows, window of {w.R} rows sliding one row per {n_ring} steps"},
         "roofline": dominant, "roofline_other": other,
     }

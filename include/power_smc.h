@@ -115,6 +115,16 @@ smc_status smc_step_resample(smc_ctx* ctx, const void* d_logits, int64_t row_str
                              double alpha_prev, double tau_t, int32_t* d_tokens_out, int32_t* d_anc_out,
                              int32_t* d_resampled_out, double* d_ess_out);
 
+/* a0 .. a5 in one call: smc_step_resample followed by smc_kv_reindex(d_anc_out, d_resampled_out, valid_len, t), with
+ * the same arguments, outputs, results and errors as the two calls -- the whole per-token step of Alg. 1 ("sample",
+ * "update", "resample", "reorder KV cache by A") in three launches at every size: with 1024 rows or more, where
+ * smc_step_resample takes a launch of its own for the resampling, the wave that resamples a prompt goes on to plan
+ * the prompt's reorder, so the plan needs no launch. */
+smc_status smc_step_resample_reindex(smc_ctx* ctx, const void* d_logits, int64_t row_stride_elems, int32_t t,
+                                     double alpha_t, double alpha_prev, double tau_t, int32_t valid_len,
+                                     int32_t* d_tokens_out, int32_t* d_anc_out, int32_t* d_resampled_out,
+                                     double* d_ess_out);
+
 /* ---- Step kept on the device: for launch sequences captured once (HIP graph) and replayed every token -----------
  * The step number t and the exponents alpha_t, alpha_{t-1} are launch arguments, so a captured step would redraw the
  * same random numbers on every replay.  With the step kept on the device, the kernels of smc_step, smc_step_resample,

@@ -21,7 +21,7 @@ EXPORTS = ["smc_workspace_bytes", "smc_init", "smc_destroy", "smc_kv_bind", "smc
            "smc_paged_reindex", "smc_paged_reindex_prepare", "smc_paged_view", "smc_paged_check", "smc_hbm_probe",
            "smc_attn_workspace_bytes", "smc_attn_decode", "smc_kv_parity", "smc_kv_append", "smc_step_noalloc",
            "smc_get_log_zhat", "smc_set_log_zhat", "smc_set_kv_skip_terminated",
-           "smc_step_resample", "smc_set_schedule", "smc_set_device_step", "smc_advance_step", "smc_get_device_step"]
+           "smc_step_resample", "smc_step_resample_reindex", "smc_set_schedule", "smc_set_device_step", "smc_advance_step", "smc_get_device_step"]
 
 
 class smc_config(C.Structure):
@@ -56,6 +56,7 @@ def lib():
         L.smc_step.argtypes = [vp, vp, i64, i32, f64, f64, f64, vp]
         L.smc_step_noalloc.argtypes = [C.POINTER(smc_config), vp, vp, i64, i32, f64, f64, f64, vp, vp, vp, vp]
         L.smc_step_resample.argtypes = [vp, vp, i64, i32, f64, f64, f64, vp, vp, vp, vp]
+        L.smc_step_resample_reindex.argtypes = [vp, vp, i64, i32, f64, f64, f64, i32, vp, vp, vp, vp]
         L.smc_set_schedule.argtypes = [vp, vp, i32]
         L.smc_set_device_step.argtypes = [vp, i32, i32]
         L.smc_advance_step.argtypes = [vp]
@@ -168,6 +169,13 @@ def smc_step_resample(ctx, d_logits, row_stride_elems, t, alpha_t, alpha_prev, t
     _check("smc_step_resample", lib().smc_step_resample(ctx, _ptr(d_logits), row_stride_elems, t, alpha_t, alpha_prev, tau_t,
                                                         _ptr(d_tokens_out), _ptr(d_anc_out), _ptr(d_resampled_out),
                                                         _ptr(d_ess_out)))
+
+
+def smc_step_resample_reindex(ctx, d_logits, row_stride_elems, t, alpha_t, alpha_prev, tau_t, valid_len, d_tokens_out,
+                              d_anc_out, d_resampled_out, d_ess_out=None):
+    _check("smc_step_resample_reindex",
+           lib().smc_step_resample_reindex(ctx, _ptr(d_logits), row_stride_elems, t, alpha_t, alpha_prev, tau_t, valid_len,
+                                           _ptr(d_tokens_out), _ptr(d_anc_out), _ptr(d_resampled_out), _ptr(d_ess_out)))
 
 
 def smc_set_schedule(ctx, h_alpha):

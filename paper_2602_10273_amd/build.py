@@ -14,7 +14,7 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libpower_smc.so")
 SOURCES = ["smc_api.hip", "vocab_pass_bf16.hip", "vocab_pass_f32.hip", "vocab_pass.hip", "weights.hip", "kv_gather.hip", "paged_kv.hip", "hbm_probe.hip",
            "attn_decode.hip", "kv_append.hip", "noalloc.hip"]
-HEADERS = ["smc_internal.hpp", "device_rng.hpp", "weights_device.hpp", "vocab_pass_kernel.hpp", os.path.join(ROOT, "include", "power_smc.h")]
+HEADERS = ["smc_internal.hpp", "device_rng.hpp", "weights_device.hpp", "gather_plan_device.hpp", "vocab_pass_kernel.hpp", os.path.join(ROOT, "include", "power_smc.h")]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

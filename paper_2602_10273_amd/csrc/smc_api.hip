@@ -290,6 +290,28 @@ smc_status smc_kv_reindex(smc_ctx* ctx, const int32_t* d_anc, const int32_t* d_r
     return launch_reindex(ctx, d_anc, d_resampled, valid_len, t) == hipSuccess ? SMC_OK : SMC_E_HIP;
 }
 
+smc_status smc_step_resample_reindex(smc_ctx* ctx, const void* d_logits, int64_t row_stride_elems, int32_t t,
+                                     double alpha_t, double alpha_prev, double tau_t, int32_t valid_len,
+                                     int32_t* d_tokens_out, int32_t* d_anc_out, int32_t* d_resampled_out, double* d_ess_out)
+{
+    if (!ctx) return SMC_E_NULL;
+    if (valid_len < 0 || (ctx->cfg.kv_tensors > 0 && valid_len > ctx->cfg.kv_S)) return SMC_E_RANGE;
+    if (ctx->cfg.kv_tensors > 0 && valid_len > 0 && !ctx->kv_bound) return SMC_E_STATE;
+    if (ctx->R < 1024) {
+        // few rows: the resampling already rides in the vocabulary pass's launch; plan and gather follow
+        const smc_status st = smc_step_resample(ctx, d_logits, row_stride_elems, t, alpha_t, alpha_prev, tau_t, d_tokens_out,
+                                                d_anc_out, d_resampled_out, d_ess_out);
+        if (st != SMC_OK) return st;
+        return launch_reindex(ctx, d_anc_out, d_resampled_out, valid_len, t) == hipSuccess ? SMC_OK : SMC_E_HIP;
+    }
+    // many rows: the vocabulary pass, then one launch that resamples every prompt and plans its reorder, then the gather
+    if (!d_anc_out || !d_resampled_out) return SMC_E_NULL;
+    const smc_status st = smc_step(ctx, d_logits, row_stride_elems, t, alpha_t, alpha_prev, tau_t, d_tokens_out);
+    if (st != SMC_OK) return st;
+    if (launch_resample_plan(ctx, ctx->ws.logW, t, d_anc_out, d_resampled_out, d_ess_out) != hipSuccess) return SMC_E_HIP;
+    return launch_reindex(ctx, d_anc_out, d_resampled_out, valid_len, t, true) == hipSuccess ? SMC_OK : SMC_E_HIP;
+}
+
 smc_status smc_final_draw(smc_ctx* ctx, int32_t t, int32_t* d_choice_out)
 {
     if (!ctx || !d_choice_out) return SMC_E_NULL;

@@ -188,7 +188,9 @@ hipError_t launch_advance_step(smc_ctx* c);
 int integer_power(double beta);   // the integer-exponent kernel instantiation for beta, or 0 for the generic one
 hipError_t launch_ess(smc_ctx* c, const double* logW, double* ess_out, double* lognormw_out);
 hipError_t launch_resample(smc_ctx* c, double* logW, int t, int32_t* anc, int32_t* resampled, double* ess_out);
-hipError_t launch_reindex(smc_ctx* c, const int32_t* anc, const int32_t* resampled, int valid_len, int t);
+hipError_t launch_reindex(smc_ctx* c, const int32_t* anc, const int32_t* resampled, int valid_len, int t, bool planned = false);
+// a3 + a4 and, for the prompts that resample, the plan of the reorder that follows (one launch)
+hipError_t launch_resample_plan(smc_ctx* c, double* logW, int t, int32_t* anc, int32_t* resampled, double* ess_out);
 hipError_t launch_final_draw(smc_ctx* c, int t, int32_t* choice);
 hipError_t launch_log_zhat(smc_ctx* c, double* out);
 

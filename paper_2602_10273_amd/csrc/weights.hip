@@ -3,6 +3,7 @@
 //
 // The sums that decide discrete outcomes (ESS < kappa*N, cumulative weights against the resampling positions)
 // are accumulated in particle order by one lane, so that they round like a plain left-to-right loop.
+#include "gather_plan_device.hpp"
 #include "weights_device.hpp"
 
 namespace psmc {
@@ -30,6 +31,24 @@ __global__ __launch_bounds__(kWave) void resample_kernel(double* __restrict__ lo
     __shared__ int sh_k;
     if (d_step) step = (uint32_t)*d_step;
     resample_prompt(r, logW, blockIdx.x, step, sh_a, sh_b, &sh_k);
+}
+
+// a3 + a4 and the first half of a5 in one launch: the wave that resampled a prompt goes on to plan its reorder (the
+// grouping of the moved rows by ancestor that plan_kernel would make in a launch of its own).
+__global__ __launch_bounds__(kWave) void resample_plan_kernel(double* __restrict__ logW, ResampleArgs r, uint32_t step,
+                                                              const int32_t* __restrict__ d_step, PlanArgs pl)
+{
+    __shared__ double sh_a[SMC_MAX_PARTICLES], sh_b[SMC_MAX_PARTICLES];
+    __shared__ int sh_k;
+    if (d_step) step = (uint32_t)*d_step;
+    const int phase = pl.plan->phase;
+    const bool fire = resample_prompt(r, logW, blockIdx.x, step, sh_a, sh_b, &sh_k);
+    if (fire) {
+        __threadfence();                                // the ancestors this wave just wrote are read back through memory
+        plan_prompt(r.anc, pl.N, pl.mask_words, phase, pl.plan, pl.grp_src, pl.grp_base, pl.grp_srcpar, pl.grp_mask, pl.cumlogp,
+                    pl.done, pl.parity, pl.skip_terminated);
+    }
+    plan_finish(pl.plan, phase, (int)gridDim.x);
 }
 
 // log of the SMC estimate of the normalising constant Z_alpha of the power target, per prompt: the factors
@@ -126,6 +145,16 @@ hipError_t launch_resample(smc_ctx* c, double* logW, int t, int32_t* anc, int32_
     hipLaunchKernelGGL(resample_kernel, dim3(c->cfg.B), dim3(kWave), 0, c->stream, logW,
                        resample_args(c, logW, anc, resampled, ess_out), (uint32_t)t,
                        c->device_step ? c->ws.d_step : nullptr);
+    return hipGetLastError();
+}
+
+PlanArgs plan_args(const smc_ctx* c);                  // kv_gather.hip
+
+hipError_t launch_resample_plan(smc_ctx* c, double* logW, int t, int32_t* anc, int32_t* resampled, double* ess_out)
+{
+    hipLaunchKernelGGL(resample_plan_kernel, dim3(c->cfg.B), dim3(kWave), 0, c->stream, logW,
+                       resample_args(c, logW, anc, resampled, ess_out), (uint32_t)t,
+                       c->device_step ? c->ws.d_step : nullptr, plan_args(c));
     return hipGetLastError();
 }
 

@@ -85,6 +85,11 @@ class Session:
         smc.smc_step_resample(self.ctx, logits, logits.stride(0), t, alpha_t, alpha_prev, tau_t, self.tokens, self.anc,
                               self.resampled, self.ess)
 
+    def step_resample_reindex(self, logits, t, alpha_t, alpha_prev, valid_len, tau_t=-1.0):
+        """a0..a5 in one call (the same results as step_resample() followed by reindex())."""
+        smc.smc_step_resample_reindex(self.ctx, logits, logits.stride(0), t, alpha_t, alpha_prev, tau_t, valid_len,
+                                      self.tokens, self.anc, self.resampled, self.ess)
+
     def compute_ess(self):
         smc.smc_ess(self.ctx, self.ess, self.lognormw)
 

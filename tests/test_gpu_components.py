@@ -438,6 +438,41 @@ def test_step_resample_in_one_launch_equals_the_two_calls(name, kw, eos):
         a.close(); b.close()
 
 
+@pytest.mark.parametrize("B,N,V,eos,order", [(64, 16, 2048 + 8, -1, 0), (40, 32, 1024 + 8, 7, 0), (5, 8, 4096 + 8, -1, 1),
+                                             (33, 32, 1024, -1, 1), (3, 400, 1024 + 8, 5, 0)])
+def test_step_resample_reindex_equals_the_separate_calls(B, N, V, eos, order):
+    """smc_step_resample_reindex (three launches at every size: from 1024 rows on the wave that resamples a prompt goes
+    on to plan its reorder) against smc_step_resample + smc_kv_reindex on a second context: tokens, ancestors, flags,
+    ESS, weights, sums, parities, termination flags, histories and every KV byte after every step, with a partly
+    filled cache and with the survivors-in-place ancestor order."""
+    w = synth.scaled(synth.WORKLOADS["cfg2"], B=B, N=N, V=V, H=2, S=12, D=16, layers=1, kappa=0.9)
+    kv = synth.kv_numpy(w, 3)
+    a = Session(w.B, w.N, w.V, 12, w.dtype, w.kappa, 3, kv=[k.copy() for k in kv], eos_id=eos)
+    b = Session(w.B, w.N, w.V, 12, w.dtype, w.kappa, 3, kv=[k.copy() for k in kv], eos_id=eos)
+    for s in (a, b):
+        smc.smc_set_ancestor_order(s.ctx, order)
+    n_res = 0
+    for t in range(1, 9):
+        x = to_device_logits(synth.logits_numpy(w, t, 3), w.dtype)
+        valid = min(t + 3, w.S)
+        a.step_resample(x, t, w.alpha, w.alpha); a.reindex(valid, t)
+        b.step_resample_reindex(x, t, w.alpha, w.alpha, valid)
+        torch.cuda.synchronize()
+        for f in ("tokens", "anc", "resampled", "ess"):
+            assert torch.equal(getattr(a, f), getattr(b, f)), (t, f)
+        sa, sb = a.state(), b.state()
+        for u, v in zip(sa, sb):
+            assert np.array_equal(u, v), t
+        if eos >= 0:
+            assert np.array_equal(a.done(), b.done())
+        n_res += int(a.resampled.sum())
+    assert n_res > 0
+    assert np.array_equal(a.live_hist(), b.live_hist())
+    for ten in range(len(kv)):
+        assert np.array_equal(a.live_kv(ten), b.live_kv(ten))
+    a.close(); b.close()
+
+
 def test_tickets_hand_every_record_over_on_many_contended_steps():
     """Rows split over many slices and prompts of many rows, thousands of workgroups, 150 free-running steps.  Three runs
     on the same logits: (a) eight slices per row, resampling in a launch of its own; (b) eight slices per row, slices
