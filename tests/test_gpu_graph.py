@@ -119,3 +119,45 @@ def test_graph_with_device_step_advances_like_eager_steps_and_the_oracle(name, r
     assert n_res > 0
     smc.smc_set_device_step(graph.ctx, 0, 1)
     eager.close(); graph.close()
+
+
+@pytest.mark.parametrize("B,N", [(5, 8), (40, 32)])
+def test_graph_of_the_whole_step_in_one_call_advances_like_eager_steps(B, N):
+    """One capture of [smc_step_resample_reindex, smc_advance_step] with the step kept on the device, replayed T times
+    with eager work in between, against eager by-value smc_step + smc_resample + smc_kv_reindex on a second context:
+    tokens, ancestors, flags, weights, sums, parities, histories and KV bytes after every replay.  With 1280 rows the
+    captured sequence contains the launch in which the resampling wave plans the prompt's reorder, whose group
+    counters alternate on the device from one replay to the next."""
+    T = 8
+    w = synth.scaled(synth.WORKLOADS["cfg2"], B=B, N=N, V=2048 + 8, layers=1, H=2, S=16, D=16, kappa=0.9)
+    kv = synth.kv_numpy(w, 3)
+    side = torch.cuda.Stream()
+    eager = Session(w.B, w.N, w.V, 16, w.dtype, w.kappa, 5, kv=kv)
+    graph = Session(w.B, w.N, w.V, 16, w.dtype, w.kappa, 5, kv=kv, stream=side)
+    smc.smc_set_schedule(graph.ctx, [w.alpha_at(t) for t in range(0, T + 2)])
+    smc.smc_set_device_step(graph.ctx, 1, 1)
+    x_buf = to_device_logits(synth.logits_numpy(w, 1, 5), w.dtype)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        graph.step_resample_reindex(x_buf, 1, 1.0, 1.0, w.S)
+        smc.smc_advance_step(graph.ctx)
+    n_res = 0
+    for t in range(1, T + 1):
+        x_buf.copy_(to_device_logits(synth.logits_numpy(w, t, 5), w.dtype))
+        torch.cuda.synchronize()
+        g.replay()
+        junk = torch.randn(1 << 18, device="cuda").sum().item()              # unrelated eager work between replays
+        eager.step(x_buf, t, w.alpha_at(t), w.alpha_at(t - 1)); eager.resample(t); eager.reindex(w.S, t)
+        torch.cuda.synchronize()
+        for f in ("tokens", "anc", "resampled"):
+            assert torch.equal(getattr(eager, f), getattr(graph, f)), (t, f)
+        a, b = eager.state(), graph.state()
+        for u, v in zip(a, b):
+            assert np.array_equal(u, v), t
+        assert np.array_equal(eager.live_hist()[:, :t], graph.live_hist()[:, :t])
+        assert np.array_equal(eager.live_kv(0), graph.live_kv(0))
+        n_res += int(eager.resampled.sum())
+    assert n_res > 0
+    smc.smc_set_device_step(graph.ctx, 0, 1)
+    eager.close(); graph.close()
